@@ -1,0 +1,193 @@
+"""CPU oracle (test infrastructure).
+
+A thin ctypes/numpy layer over ``scout_oracle.c``: it loops over (sequence, KV
+head) pairs and query heads and calls the per-pair C functions, nothing more.
+Only tests, the smoke check and the benchmark's CPU-baseline leg import this
+package; the product package never does, and this package imports nothing of
+the product.
+
+Storage types: ``float32`` arrays are passed as they are; bf16 data is carried
+as ``uint16`` arrays holding the upper half of the binary32 pattern.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "scout_oracle.c")
+_LIB = os.path.join(_HERE, "libscout_oracle.so")
+
+F32, BF16 = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (-O2, no fast-math). Returns the library path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        vp, ip, dp = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_double)
+        ci, cd = ctypes.c_int, ctypes.c_double
+        lib.orc_num_blocks.argtypes = [ci, ci]
+        lib.orc_num_blocks.restype = ci
+        lib.orc_digest.argtypes = [ci, vp, ci, ci, ci, vp]
+        lib.orc_digest.restype = None
+        lib.orc_score.argtypes = [ci, vp, vp, ci, ci, ci, dp]
+        lib.orc_score.restype = None
+        lib.orc_rank.argtypes = [dp, ci, ip]
+        lib.orc_rank.restype = None
+        lib.orc_select.argtypes = [dp, ci, ci, ip]
+        lib.orc_select.restype = ci
+        lib.orc_split.argtypes = [ip, ci, ip, ci, ip, ip, ip, ip]
+        lib.orc_split.restype = None
+        lib.orc_partial_attn.argtypes = [ci, vp, vp, vp, ip, ci, ci, ci, ci, cd, dp, dp, dp]
+        lib.orc_partial_attn.restype = None
+        lib.orc_merge.argtypes = [dp, cd, cd, dp, cd, cd, ci, dp, dp]
+        lib.orc_merge.restype = None
+        lib.orc_recall_plan.argtypes = [dp, ci, ci, ip, ip, ip, ip]
+        lib.orc_recall_plan.restype = ci
+        _lib = lib
+    return _lib
+
+
+def _dtype_code(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError(f"storage arrays must be float32 or uint16 (bf16 bits), got {a.dtype}")
+
+
+def _vp(a: np.ndarray):
+    assert a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _ip(a: np.ndarray):
+    assert a.dtype == np.int32 and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int))
+
+
+def _dp(a: np.ndarray):
+    assert a.dtype == np.float64 and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def num_blocks(ctx_len: int, S: int) -> int:
+    return _L().orc_num_blocks(int(ctx_len), int(S))
+
+
+def digest(K: np.ndarray, ctx_len: int, S: int) -> np.ndarray:
+    """K: [>=ctx_len][d] storage array of one pair. Returns [nb][2][d] (min, max)."""
+    K = np.ascontiguousarray(K)
+    d = K.shape[1]
+    nb = num_blocks(ctx_len, S)
+    out = np.zeros((nb, 2, d), dtype=K.dtype)
+    _L().orc_digest(_dtype_code(K), _vp(K), int(ctx_len), int(S), int(d), _vp(out))
+    return out
+
+
+def score(q: np.ndarray, dig: np.ndarray) -> np.ndarray:
+    """q: [G][d], dig: [nb][2][d] (same storage type). Returns float64 [nb]."""
+    q = np.ascontiguousarray(q)
+    dig = np.ascontiguousarray(dig)
+    assert q.dtype == dig.dtype
+    G, d = q.shape
+    nb = dig.shape[0]
+    s = np.zeros(nb, dtype=np.float64)
+    _L().orc_score(_dtype_code(q), _vp(q), _vp(dig), nb, G, d, _dp(s))
+    return s
+
+
+def decision_scores(s: np.ndarray) -> np.ndarray:
+    """Scores as the selection sees them: rounded once to binary32.
+
+    The boundary carries scores as binary32, so both sides take the top-k
+    decision on the binary32 value.
+    """
+    return s.astype(np.float32).astype(np.float64)
+
+
+def rank(s: np.ndarray) -> np.ndarray:
+    s = np.ascontiguousarray(s, dtype=np.float64)
+    r = np.zeros(len(s), dtype=np.int32)
+    _L().orc_rank(_dp(s), len(s), _ip(r))
+    return r
+
+
+def select(s: np.ndarray, k: int) -> np.ndarray:
+    """Returns int32 [k]: the k_eff selected block indices ascending, then -1."""
+    s = np.ascontiguousarray(s, dtype=np.float64)
+    sel = np.full(max(k, 1), -1, dtype=np.int32)
+    _L().orc_select(_dp(s), len(s), int(k), _ip(sel))
+    return sel[:k]
+
+
+def split(sel: np.ndarray, table: np.ndarray):
+    """sel: [k] padded with -1; table: [>=nb] slots. Returns (sel_gpu, n_gpu, sel_host, n_host)."""
+    sel = np.ascontiguousarray(sel, dtype=np.int32)
+    table = np.ascontiguousarray(table, dtype=np.int32)
+    k = len(sel)
+    n_sel = int((sel >= 0).sum())
+    sg = np.full(max(k, 1), -1, dtype=np.int32)
+    sh = np.full(max(k, 1), -1, dtype=np.int32)
+    ng, nh = ctypes.c_int(0), ctypes.c_int(0)
+    _L().orc_split(_ip(sel), n_sel, _ip(table), k, _ip(sg), ctypes.byref(ng), _ip(sh), ctypes.byref(nh))
+    return sg[:k], ng.value, sh[:k], nh.value
+
+
+def partial_attn(q_h: np.ndarray, K: np.ndarray, V: np.ndarray, blocks, ctx_len: int, S: int,
+                 sm_scale: float):
+    """One head over the listed blocks. Returns (o float64 [d], m, l)."""
+    q_h = np.ascontiguousarray(q_h)
+    K = np.ascontiguousarray(K)
+    V = np.ascontiguousarray(V)
+    assert q_h.dtype == K.dtype == V.dtype
+    d = K.shape[1]
+    blocks = np.ascontiguousarray(np.asarray(blocks, dtype=np.int32))
+    blocks = blocks[blocks >= 0]
+    blk = blocks if len(blocks) else np.zeros(1, dtype=np.int32)
+    o = np.zeros(d, dtype=np.float64)
+    m, l = ctypes.c_double(0), ctypes.c_double(0)
+    _L().orc_partial_attn(_dtype_code(K), _vp(q_h), _vp(K), _vp(V), _ip(blk), len(blocks),
+                          int(ctx_len), int(S), int(d), float(sm_scale), _dp(o),
+                          ctypes.byref(m), ctypes.byref(l))
+    return o, m.value, l.value
+
+
+def merge(o_a, m_a, l_a, o_b, m_b, l_b):
+    """Returns (out float64 [d], lse)."""
+    o_a = np.ascontiguousarray(o_a, dtype=np.float64)
+    o_b = np.ascontiguousarray(o_b, dtype=np.float64)
+    d = len(o_a)
+    out = np.zeros(d, dtype=np.float64)
+    lse = ctypes.c_double(0)
+    _L().orc_merge(_dp(o_a), float(m_a), float(l_a), _dp(o_b), float(m_b), float(l_b), d,
+                   _dp(out), ctypes.byref(lse))
+    return out, lse.value
+
+
+def recall_plan(s: np.ndarray, k: int, table: np.ndarray):
+    """table is updated in place. Returns (recall_blk, recall_slot, evict_blk, n)."""
+    s = np.ascontiguousarray(s, dtype=np.float64)
+    assert table.dtype == np.int32 and table.flags["C_CONTIGUOUS"]
+    rb = np.full(max(k, 1), -1, dtype=np.int32)
+    rs = np.full(max(k, 1), -1, dtype=np.int32)
+    eb = np.full(max(k, 1), -1, dtype=np.int32)
+    n = _L().orc_recall_plan(_dp(s), len(s), int(k), _ip(table), _ip(rb), _ip(rs), _ip(eb))
+    return rb[:k], rs[:k], eb[:k], n

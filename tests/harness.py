@@ -1,0 +1,69 @@
+"""Oracle-side pipeline helpers for the tests (CPU only).
+
+Chains the per-pair oracle functions in the order of Algorithm 1: digest ->
+score -> top-k -> residency split -> partial attention on each side -> merge.
+Holds no arithmetic of its own.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, Tuple
+
+import numpy as np
+
+import oracle
+from paper_2603_27138_amd import workload as W
+
+
+@dataclass
+class OraclePair:
+    dig: np.ndarray            # [nb][2][d] storage
+    s: np.ndarray              # float64 [nb] exact scores
+    s32: np.ndarray            # float64 [nb] scores as the decision sees them (binary32 values)
+    sel: np.ndarray            # int32 [k]
+    sel_gpu: np.ndarray
+    n_gpu: int
+    sel_host: np.ndarray
+    n_host: int
+    gpu_part: list = field(default_factory=list)   # per head (o, m, l)
+    host_part: list = field(default_factory=list)
+    out: list = field(default_factory=list)        # per head (out, lse)
+
+
+def run_pair(wl: W.Workload, b: int, g: int, q=None, table=None, attention: bool = True) -> OraclePair:
+    cfg = wl.cfg
+    q = wl.q if q is None else q
+    table = wl.block_table if table is None else table
+    K, V = wl.K[(b, g)], wl.V[(b, g)]
+    ctx = int(cfg.ctx[b])
+    dig = oracle.digest(K, ctx, cfg.S)
+    qg = q[b, g * cfg.G:(g + 1) * cfg.G]
+    s = oracle.score(qg, dig)
+    s32 = oracle.decision_scores(s)
+    sel = oracle.select(s32, cfg.k)
+    sg, ng, sh, nh = oracle.split(sel, table[b, g])
+    res = OraclePair(dig, s, s32, sel, sg, ng, sh, nh)
+    if attention:
+        for h in range(cfg.G):
+            pg = oracle.partial_attn(qg[h], K, V, sg, ctx, cfg.S, cfg.sm_scale)
+            ph = oracle.partial_attn(qg[h], K, V, sh, ctx, cfg.S, cfg.sm_scale)
+            # the host hands its partial over in binary32
+            ph32 = (ph[0].astype(np.float32).astype(np.float64), float(np.float32(ph[1])), float(np.float32(ph[2])))
+            res.gpu_part.append(pg)
+            res.host_part.append(ph32)
+            res.out.append(oracle.merge(pg[0], pg[1], pg[2], ph32[0], ph32[1], ph32[2]))
+    return res
+
+
+def run_all(wl: W.Workload, **kw) -> Dict[Tuple[int, int], OraclePair]:
+    return {p: run_pair(wl, p[0], p[1], **kw) for p in wl.K}
+
+
+def boundary_gap(op: OraclePair, k: int) -> float:
+    """Relative gap between the last kept and first dropped score (binary64 scores)."""
+    nb = len(op.s)
+    if k >= nb:
+        return np.inf
+    r = oracle.rank(op.s32)
+    a, b = op.s[r[k - 1]], op.s[r[k]]
+    return abs(a - b) / max(abs(a), abs(b), 1e-300)

@@ -1,0 +1,118 @@
+"""Pins for the oracle's top-k selection, residency split and recall plan (CPU only).
+
+Selection: Algorithm 1 (TopK of the digest scores), ties toward the lower
+block index.  Recall plan: Sec. 3.4, minimal-movement reading.
+"""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+
+
+def brute_topk(s, k):
+    order = sorted(range(len(s)), key=lambda j: (-s[j], j))
+    return sorted(order[: min(k, len(s))])
+
+
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("nb,k", [(1, 1), (7, 3), (16, 16), (16, 40), (128, 16), (1000, 64)])
+def test_select_matches_brute_force(seed, nb, k):
+    rng = np.random.default_rng(seed)
+    s = rng.standard_normal(nb)
+    if seed % 2:  # heavy exact ties
+        s = np.round(s * 2) / 2
+    sel = oracle.select(s, k)
+    want = brute_topk(s.tolist(), k)
+    assert sel[: len(want)].tolist() == want
+    assert (sel[len(want):] == -1).all()
+
+
+def test_select_all_permutations_tiny():
+    vals = [0.0, 1.0, 1.0, 2.0, 2.0]
+    for perm in set(itertools.permutations(vals)):
+        for k in range(1, 6):
+            assert oracle.select(np.array(perm), k).tolist() == brute_topk(list(perm), k)
+
+
+def test_select_k1_is_first_argmax_and_ties_go_low():
+    s = np.array([1.0, 5.0, 5.0, -2.0])
+    assert oracle.select(s, 1).tolist() == [1]
+    assert oracle.select(s, 2).tolist() == [1, 2]
+    assert oracle.select(np.zeros(9), 4).tolist() == [0, 1, 2, 3]
+
+
+def test_select_minus_inf_never_beats_finite():
+    s = np.array([-np.inf, 0.0, -np.inf, -1e30])
+    assert oracle.select(s, 2).tolist() == [1, 3]
+
+
+def test_select_permutation_equivariance():
+    rng = np.random.default_rng(3)
+    s = rng.standard_normal(200)   # distinct with probability 1
+    perm = rng.permutation(200)
+    a = set(oracle.select(s, 20).tolist())
+    b = set(oracle.select(s[perm], 20).tolist())
+    assert {int(perm[j]) for j in b} == a
+
+
+def test_split_by_residency():
+    sel = np.array([2, 5, 7, 9, -1, -1], dtype=np.int32)
+    table = np.full(12, -1, dtype=np.int32)
+    table[[2, 9, 10]] = [40, 41, 42]
+    sg, ng, sh, nh = oracle.split(sel, table)
+    assert (ng, nh) == (2, 2)
+    assert sg.tolist() == [2, 9, -1, -1, -1, -1]
+    assert sh.tolist() == [5, 7, -1, -1, -1, -1]
+
+
+# ----------------------------------------------------------------- recall plan
+
+
+def brute_recall(s, k, table):
+    nb = len(s)
+    order = sorted(range(nb), key=lambda j: (-s[j], j))
+    T = set(order[: min(k, nb)])
+    R = {j for j in range(nb) if table[j] >= 0}
+    missing = [j for j in order if j in T and j not in R]
+    spare = [j for j in order if j in R and j not in T]
+    n = min(len(missing), len(spare))
+    recall = sorted(missing[:n])
+    evict = sorted(spare[len(spare) - n:]) if n else []
+    new = list(table)
+    slots = [table[e] for e in evict]
+    for r, e, sl in zip(recall, evict, slots):
+        new[r] = sl
+        new[e] = -1
+    return recall, slots, evict, new
+
+
+@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("nb,k,n_res", [(12, 4, 6), (12, 4, 2), (64, 16, 32), (64, 16, 64), (64, 16, 0), (9, 20, 5)])
+def test_recall_plan_matches_brute_force(seed, nb, k, n_res):
+    rng = np.random.default_rng(seed)
+    s = rng.standard_normal(nb)
+    if seed % 3 == 0:
+        s = np.round(s * 2) / 2
+    table = np.full(nb, -1, dtype=np.int32)
+    res = rng.permutation(nb)[:n_res]
+    table[res] = rng.permutation(1000)[:n_res]
+    want_r, want_s, want_e, want_t = brute_recall(s.tolist(), k, table.tolist())
+    t2 = table.copy()
+    rb, rs, eb, n = oracle.recall_plan(s, k, t2)
+    assert n == len(want_r)
+    assert rb[:n].tolist() == want_r and rs[:n].tolist() == want_s and eb[:n].tolist() == want_e
+    assert (rb[n:] == -1).all() and (rs[n:] == -1).all() and (eb[n:] == -1).all()
+    assert t2.tolist() == want_t
+    # invariants: capacity and slot set unchanged, no slot used twice
+    assert sorted(t2[t2 >= 0].tolist()) == sorted(table[table >= 0].tolist())
+    # when the cache holds at least k blocks the whole top-k is resident afterwards
+    if n_res >= min(k, nb):
+        T = oracle.select(s, k)
+        assert (t2[T[T >= 0]] >= 0).all()
+    # a second plan with the same scores moves nothing
+    t3 = t2.copy()
+    assert oracle.recall_plan(s, k, t3)[3] == 0 or n_res < min(k, nb)
+    if n_res >= min(k, nb):
+        assert (t3 == t2).all()
