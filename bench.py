@@ -1,0 +1,263 @@
+"""Benchmark: one layer-step of the sparse decode-attention hot path on one MI355X.
+
+Workload: benchmark config 3 (Qwen3-32B-shaped single layer: batch 16, 64 q / 8 KV
+heads, d 128, bf16, 32768-token contexts in blocks of 32, k = 64, 50 % of blocks
+host-resident), synthetic and seeded.  A step = score_blocks -> select_topk ->
+sparse_decode_attn -> merge with the host partial (scout_layer_step), inputs resident
+in HBM.  Steps rotate over several distinct copies of the layer's memory so that no
+timed read is served from the last-level cache.
+
+Prints ONE JSON line (see the keys below).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--layers", type=int, default=8, help="distinct memory copies the steps rotate over")
+    ap.add_argument("--batch", type=int, default=16)
+    ap.add_argument("--ctx", type=int, default=32768)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--attn-family", type=int, default=0)
+    ap.add_argument("--nsplit", type=int, default=0)
+    return ap.parse_args()
+
+
+class LayerSet:
+    """One copy of a layer's device state (own addresses, same content)."""
+
+    def __init__(self, src=None):
+        if src is not None:
+            for k, v in src.__dict__.items():
+                setattr(self, k, v.clone() if hasattr(v, "clone") else v)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only; every (sequence, KV head) pair is independent, so "
+              "more GPUs would each run this same path on their share. Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2603_27138_amd import binding as B
+    from paper_2603_27138_amd import workload as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    B.lib()   # fail loudly if the HIP library is missing
+    B.set_attn_mode(args.attn_family, args.nsplit)
+
+    cfg = W.qwen3_32b(B=args.batch, ctx=args.ctx)
+    t0 = time.time()
+    wl = W.generate(cfg, workers=16)
+    t_gen = time.time() - t0
+
+    def dev(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(a).cuda()
+
+    pairs = (cfg.B, cfg.Hkv)
+    L0 = LayerSet()
+    L0.ctx_len = torch.from_numpy(wl.ctx_len).cuda()
+    L0.q = dev(wl.q)
+    L0.block_table = torch.from_numpy(wl.block_table).cuda()
+    L0.k_pool, L0.v_pool = dev(wl.k_pool), dev(wl.v_pool)
+    L0.digest = torch.zeros(*pairs, cfg.max_blocks, 2, cfg.d, dtype=torch.bfloat16, device="cuda")
+    p0 = B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, B.BF16, cfg.max_blocks, cfg.k, L0.ctx_len)
+    ws = B.alloc_workspace(p0)
+
+    # digest cache from the keys of every block (device kernel), then drop the full key tensor
+    kb = np.empty((cfg.B, cfg.Hkv, cfg.max_blocks, cfg.S, cfg.d), dtype=np.uint16)
+    vb = np.empty_like(kb)
+    for (b, g) in wl.K:
+        kb[b, g] = wl.blocks_padded(b, g, "K")
+        vb[b, g] = wl.blocks_padded(b, g, "V")
+    k_all, v_all = dev(kb), dev(vb)
+    B.build_digests(p0, k_all, L0.digest)
+
+    i32 = dict(dtype=torch.int32, device="cuda")
+    f32 = dict(dtype=torch.float32, device="cuda")
+    L0.scores = torch.empty(*pairs, cfg.max_blocks, **f32)
+    L0.sel_all = torch.empty(*pairs, cfg.k, **i32)
+    L0.sel_gpu = torch.empty(*pairs, cfg.k, **i32)
+    L0.slot_gpu = torch.empty(*pairs, cfg.k, **i32)
+    L0.sel_host = torch.empty(*pairs, cfg.k, **i32)
+    L0.n_gpu = torch.empty(pairs, **i32)
+    L0.n_host = torch.empty(pairs, **i32)
+    L0.out = torch.empty(cfg.B, cfg.Hq, cfg.d, dtype=torch.bfloat16, device="cuda")
+    L0.lse = torch.empty(cfg.B, cfg.Hq, **f32)
+
+    # The host's partial for the offloaded selected blocks is an INPUT of the step.  Here it is produced
+    # once, before timing, by running the same attention kernel over a temporary pool that holds every
+    # block with a table that marks exactly the host-resident ones.
+    L0.host_o = torch.zeros(cfg.B, cfg.Hq, cfg.d, **f32)
+    L0.host_m = torch.full((cfg.B, cfg.Hq), float("-inf"), **f32)
+    L0.host_l = torch.zeros(cfg.B, cfg.Hq, **f32)
+    all_slots = torch.arange(cfg.B * cfg.Hkv * cfg.max_blocks, **i32).view(*pairs, cfg.max_blocks)
+    host_table = torch.where(L0.block_table < 0, all_slots, torch.full_like(all_slots, -1))
+    B.score_blocks(p0, L0.q, L0.digest, L0.scores, ws)
+    B.select_topk(p0, L0.scores, host_table, L0.sel_all, L0.sel_gpu, L0.slot_gpu, L0.n_gpu, L0.sel_host,
+                  L0.n_host, ws)
+    B.sparse_decode_attn(p0, L0.q, k_all.view(-1, cfg.S, cfg.d), v_all.view(-1, cfg.S, cfg.d),
+                         cfg.B * cfg.Hkv * cfg.max_blocks, L0.sel_gpu, L0.slot_gpu, L0.n_gpu, L0.host_o,
+                         L0.host_m, L0.host_l, ws)
+    torch.cuda.synchronize()
+    del k_all, v_all, kb, vb, host_table, all_slots
+    torch.cuda.empty_cache()
+
+    sets = [L0] + [LayerSet(L0) for _ in range(args.layers - 1)]
+    probs = [B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, B.BF16, cfg.max_blocks, cfg.k, s.ctx_len)
+             for s in sets]
+
+    def step(i):
+        s, p = sets[i % len(sets)], probs[i % len(sets)]
+        B.layer_step(p, s.q, s.digest, s.block_table, s.k_pool, s.v_pool, wl.n_slots, s.host_o, s.host_m,
+                     s.host_l, s.scores, s.sel_all, s.sel_gpu, s.slot_gpu, s.n_gpu, s.sel_host, s.n_host,
+                     s.out, s.lse, ws)
+
+    stream = torch.cuda.current_stream()
+
+    def timed(fn, n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(stream)
+        for i in range(n):
+            fn(i)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / n     # microseconds per call
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t_wall0 = time.time()
+    us_step = timed(step, args.steps)
+    t_wall = time.time() - t_wall0
+
+    # per-kernel figures on the same stream, same rotation: the attention split pass alone, the scoring
+    # pass alone (HIP events around `steps` back-to-back launches)
+    def attn_only(i):
+        s, p = sets[i % len(sets)], probs[i % len(sets)]
+        B.attn_partials(p, s.q, s.k_pool, s.v_pool, wl.n_slots, s.sel_gpu, s.slot_gpu, s.n_gpu, ws)
+
+    def score_only(i):
+        s, p = sets[i % len(sets)], probs[i % len(sets)]
+        B.score_blocks(p, s.q, s.digest, s.scores, ws)
+
+    def select_only(i):
+        s, p = sets[i % len(sets)], probs[i % len(sets)]
+        B.select_topk(p, s.scores, s.block_table, s.sel_all, s.sel_gpu, s.slot_gpu, s.n_gpu, s.sel_host,
+                      s.n_host, ws)
+
+    for i in range(args.warmup):
+        attn_only(i)
+    us_attn = timed(attn_only, args.steps)
+    us_score = timed(score_only, args.steps)
+    us_select = timed(select_only, args.steps)
+
+    tile_bytes = 2 * cfg.S * cfg.d * 2                       # K + V tile of one block, bf16
+    n_blocks = int(sets[0].n_gpu.sum().item())
+    attn_bytes = n_blocks * tile_bytes                       # algorithmic bytes of one attention launch
+    digest_bytes = cfg.B * cfg.Hkv * cfg.max_blocks * 2 * cfg.d * 2
+    attn_gbps = attn_bytes / us_attn * 1e-3
+    score_gbps = digest_bytes / us_score * 1e-3
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "attn_mfma_c3_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    result = {
+        "metric": "sparse decode attn us/layer-step (score+select+attend+merge), Qwen3-32B shape 32k",
+        "value": round(us_step, 3),
+        "unit": "us/layer-step",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(us_step * 1e-3, 6),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "C3 qwen3-32b-shaped single layer", "batch": cfg.B, "q_heads": cfg.Hq,
+                   "kv_heads": cfg.Hkv, "head_dim": cfg.d, "context": args.ctx, "block": cfg.S, "k_blocks": cfg.k,
+                   "host_resident": cfg.p_host, "layer_copies": len(sets), "gpu_blocks_per_step": n_blocks},
+        "kv_gbps": round(attn_gbps, 1),
+        "kernels_us": {"score_blocks": round(us_score, 3), "select_topk": round(us_select, 3),
+                       "attn_split_pass": round(us_attn, 3)},
+        "score_gbps": round(score_gbps, 1),
+        "roofline": {"bound": "hbm", "kernel": "attn_mfma_kernel", "achieved": round(attn_gbps, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": traffic, "algorithmic_bytes": attn_bytes},
+        "wall_s_timed_region": round(t_wall, 3),
+        "gen_s": round(t_gen, 1),
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, wl, sets[0])
+    print(json.dumps(result))
+
+
+def cpu_baseline(cfg, wl, s0):
+    """The oracle, as it stands, on the host cores: one full layer-step of the same workload
+    (score, select, split, partial attention over the resident selected blocks, merge) for every
+    pair; also a spot check of the device output against it."""
+    import oracle
+    from paper_2603_27138_amd import workload as W
+
+    host_o = s0.host_o.cpu().numpy().astype(np.float64)
+    host_m = s0.host_m.cpu().numpy().astype(np.float64)
+    host_l = s0.host_l.cpu().numpy().astype(np.float64)
+    out_dev = s0.out.view(torch_int16()).cpu().numpy().view(np.uint16)
+    out_dev = W.bf16_bits_to_f32(out_dev).astype(np.float64)
+    sel_dev = s0.sel_all.cpu().numpy()
+    digs = {p: oracle.digest(wl.K[p], int(cfg.ctx[p[0]]), cfg.S) for p in wl.K}   # not timed: an input
+    t0 = time.perf_counter()
+    worst, sel_bad = 0.0, 0
+    for (b, g), dig in digs.items():
+        qg = wl.q[b, g * cfg.G:(g + 1) * cfg.G]
+        s = oracle.decision_scores(oracle.score(qg, dig))
+        sel = oracle.select(s, cfg.k)
+        sg, ng, sh, nh = oracle.split(sel, wl.block_table[b, g])
+        same = np.array_equal(sel, sel_dev[b, g])
+        sel_bad += 0 if same else 1
+        for h in range(cfg.G):
+            hq = g * cfg.G + h
+            o, m, l = oracle.partial_attn(qg[h], wl.K[(b, g)], wl.V[(b, g)], sg, int(cfg.ctx[b]), cfg.S, cfg.sm_scale)
+            out, _ = oracle.merge(o, m, l, host_o[b, hq], host_m[b, hq], host_l[b, hq])
+            if same:
+                worst = max(worst, float(np.abs(out - out_dev[b, hq]).max()))
+    dt = time.perf_counter() - t0
+    return {"value": round(dt * 1e6, 1), "unit": "us/layer-step", "cores": 1, "kind": "oracle",
+            "sample": f"one full layer-step, all {len(digs)} (sequence, KV head) pairs, single thread",
+            "device_vs_oracle_max_abs_err": worst, "selection_mismatches": sel_bad}
+
+
+def torch_int16():
+    import torch
+    return torch.int16
+
+
+if __name__ == "__main__":
+    main()

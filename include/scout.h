@@ -1,0 +1,207 @@
+/*
+ * scout.h -- C ABI of the MI355X-native GPU side of GPU-CPU collaborative
+ * block-wise sparse decode attention (ScoutAttention, Sec. 3.2-3.4, Alg. 1).
+ *
+ * One decode step of one layer, as the paper states it (Sec. 3.2):
+ *   1. score every KV block of every sequence by the query against the
+ *      block's digest                                   -> score_blocks
+ *   2. keep the top-k blocks under the token budget and split them by
+ *      residency (Alg. 1: B_cpu = B_pred \ B_gpu)        -> select_topk
+ *   3. attend, on the GPU, to the selected blocks that are GPU-resident,
+ *      producing a partial result                        -> sparse_decode_attn
+ *   4. merge that partial with the one the host computed for the offloaded
+ *      selected blocks (FlashAttention rescaling)        -> merge_partials
+ *   and, every few steps, after the layer's attention (Sec. 3.4), plan which
+ *   offloaded blocks return to the GPU                   -> periodic_recall
+ *
+ * Conventions common to every entry point
+ *   - Every pointer except `const scout_problem*` is DEVICE memory owned by
+ *     the caller.  The library allocates nothing, frees nothing and keeps no
+ *     pointer after a call returns.  Scratch comes from the caller's
+ *     workspace (`ws`, at least scout_workspace_bytes() bytes, 256-byte
+ *     aligned).
+ *   - `stream` is a hipStream_t (NULL = the default stream).  Calls enqueue
+ *     work and return; they never synchronise.
+ *   - Arguments are validated on the host before anything is launched.  A
+ *     negative return code means nothing was launched and no output was
+ *     written.  Device-side data (ctx_len, slots, counts) cannot be checked
+ *     on the host: kernels clamp counts to their array bounds and skip slots
+ *     outside [0, n_slots), so malformed device data gives wrong numbers,
+ *     never an out-of-bounds access.
+ *   - All tensors are dense, row-major, 16-byte aligned.
+ *   - Same inputs give the same bits: no floating-point atomics anywhere.
+ *
+ * Symbols:  B sequences, Hq query heads, Hkv KV heads, G = Hq/Hkv, d head
+ * dim, S tokens per block, nb_b = ceil(ctx_len[b]/S), "pair" = one
+ * (sequence, KV head).  "e" is the element type selected by `dtype`.
+ */
+#ifndef SCOUT_H
+#define SCOUT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  SCOUT_OK = 0,
+  SCOUT_EINVAL = -1,       /* null pointer, bad shape, misaligned pointer          */
+  SCOUT_EUNSUPPORTED = -2, /* valid request outside what the kernels cover          */
+  SCOUT_EWORKSPACE = -3,   /* workspace missing, misaligned or too small            */
+  SCOUT_EHIP = -4          /* the HIP runtime reported an error at launch           */
+};
+
+enum { SCOUT_F32 = 0, SCOUT_BF16 = 1 };
+
+typedef struct scout_problem {
+  int32_t B, Hq, Hkv; /* Hq % Hkv == 0, G = Hq/Hkv <= 16                            */
+  int32_t d;          /* head dim: 64 or 128                                        */
+  int32_t S;          /* tokens per block: 16, 32 or 64                             */
+  int32_t dtype;      /* element type of q, k_pool, v_pool, digest, out             */
+  int32_t max_blocks; /* row length of scores / block_table / digest, <= 16384      */
+  int32_t k;          /* block budget per pair = token budget / S, 1 <= k <= 1024   */
+  float sm_scale;     /* softmax scale; 0 means 1/sqrt(d)                           */
+  const int32_t* ctx_len; /* DEVICE int32 [B]: tokens per sequence; blocks beyond
+                             max_blocks are ignored                                  */
+} scout_problem;
+
+/* Library version, major*100 + minor. */
+int scout_version(void);
+
+/* Short static description of an error code. */
+const char* scout_strerror(int code);
+
+/* Bytes of workspace that any entry point may use for this problem. */
+int scout_workspace_bytes(const scout_problem* p, size_t* bytes);
+
+/*
+ * Block digests (Sec. 2.2: channel-wise min and max pooling over the keys of
+ * a block).  Builds the digest cache from keys laid out block by block.
+ *   k_blocks  e  [B][Hkv][max_blocks][S][d]   keys of every block (any residency)
+ *   digest    e  [B][Hkv][max_blocks][2][d]   out: [..][0] = min, [..][1] = max
+ * Only the valid tokens of a block are pooled; rows of blocks >= nb_b are
+ * left untouched.  Min/max never round, so the result is exact.
+ */
+int build_digests(const scout_problem* p, const void* k_blocks, void* digest, void* stream);
+
+/*
+ * Block importance (Sec. 2.2, Sec. 3.2, Alg. 1 TopK argument): for each pair
+ * and block j, sum over the G query heads of the group and over channels c of
+ * max(q[c]*min_j[c], q[c]*max_j[c]).  Unscaled.  Accumulated in binary64 and
+ * rounded once to binary32.
+ *   q        e   [B][Hq][d]
+ *   digest   e   [B][Hkv][max_blocks][2][d]
+ *   scores   f32 [B][Hkv][max_blocks]          out; -inf for j >= nb_b
+ */
+int score_blocks(const scout_problem* p, const void* q, const void* digest, float* scores,
+                 void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Top-k selection and residency split (Alg. 1: TopK, then B_pred \ B_gpu).
+ * Per pair: the k_eff = min(k, nb_b) blocks that come first when ordered by
+ * (score descending, block index ascending), reported in ascending index.
+ *   scores       f32 [B][Hkv][max_blocks]
+ *   block_table  i32 [B][Hkv][max_blocks]   pool slot (>= 0) of a GPU-resident
+ *                                           block, -1 for a host-resident one
+ *   sel_all      i32 [B][Hkv][k]   out: selected block indices, then -1
+ *   sel_gpu      i32 [B][Hkv][k]   out: the resident ones, then -1
+ *   slot_gpu     i32 [B][Hkv][k]   out: their pool slots, then -1
+ *   n_gpu        i32 [B][Hkv]      out
+ *   sel_host     i32 [B][Hkv][k]   out: the offloaded ones, then -1
+ *   n_host       i32 [B][Hkv]      out
+ * Integer and comparison work only; the result is exact.  NaN scores rank
+ * below -inf.
+ */
+int select_topk(const scout_problem* p, const float* scores, const int32_t* block_table,
+                int32_t* sel_all, int32_t* sel_gpu, int32_t* slot_gpu, int32_t* n_gpu,
+                int32_t* sel_host, int32_t* n_host, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * GPU-side partial attention (Sec. 3.2; Alg. 1 GPUAttn): for every query head,
+ * softmax(sm_scale * q.K^T) V over all valid tokens of the listed resident
+ * blocks, returned as a partial result (o, m, l):  m = max logit (natural-log
+ * units), l = sum exp(logit - m), o = sum exp(logit - m) v / l.
+ * An empty list gives o = 0, m = -inf, l = 0.
+ *   q         e   [B][Hq][d]
+ *   k_pool    e   [n_slots][S][d]     one K tile per resident (pair, block)
+ *   v_pool    e   [n_slots][S][d]
+ *   sel_gpu   i32 [B][Hkv][k]         logical block index (masks a partial last block)
+ *   slot_gpu  i32 [B][Hkv][k]         pool slot of the same entry
+ *   n_gpu     i32 [B][Hkv]            entries used per pair (clamped to k)
+ *   o         f32 [B][Hq][d], m f32 [B][Hq], l f32 [B][Hq]   out
+ * Inputs are read in their stored type; products and sums are binary32 (the
+ * bf16 kernel rounds softmax weights to bf16 before the value product).
+ */
+int sparse_decode_attn(const scout_problem* p, const void* q, const void* k_pool,
+                       const void* v_pool, int64_t n_slots, const int32_t* sel_gpu,
+                       const int32_t* slot_gpu, const int32_t* n_gpu, float* o, float* m,
+                       float* l, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * First half of sparse_decode_attn on its own: the split-KV pass that streams
+ * the K/V tiles and leaves one partial per (pair, split) in the workspace.
+ * Same arguments; writes nothing but the workspace.  It exists so that the
+ * bandwidth-bound kernel can be timed without the small combine pass behind it.
+ */
+int scout_attn_partials(const scout_problem* p, const void* q, const void* k_pool,
+                        const void* v_pool, int64_t n_slots, const int32_t* sel_gpu,
+                        const int32_t* slot_gpu, const int32_t* n_gpu, void* ws, size_t ws_bytes,
+                        void* stream);
+
+/*
+ * Merge of two partial results (Alg. 1 Merge; FlashAttention rescaling):
+ *   m* = max(m_a, m_b), w_x = l_x exp(m_x - m*), out = (w_a o_a + w_b o_b)/(w_a + w_b),
+ *   lse = m* + ln(w_a + w_b).  A side with l = 0 has weight 0.
+ *   o_a, o_b  f32 [B][Hq][d];  m_*, l_*  f32 [B][Hq];  side b may be all NULL
+ *   out       e   [B][Hq][d]
+ *   lse       f32 [B][Hq]   optional (may be NULL)
+ */
+int merge_partials(const scout_problem* p, const float* o_a, const float* m_a, const float* l_a,
+                   const float* o_b, const float* m_b, const float* l_b, void* out, float* lse,
+                   void* stream);
+
+/*
+ * Periodic recall plan (Sec. 3.4): rescore all blocks with the current query,
+ * take the top-k set T, and with R the resident set of a pair:
+ *   recall = T \ R (if larger than R \ T, its best-ranked |R \ T| members),
+ *   evict  = the |recall| worst-ranked members of R \ T,
+ * both ascending by block index; the i-th recalled block takes the slot of the
+ * i-th evicted block and block_table is updated in place.  The caller copies
+ * the recalled tiles into the returned slots before the next step's attention.
+ *   block_table  i32 [B][Hkv][max_blocks]   in/out
+ *   recall_blk, recall_slot, evict_blk  i32 [B][Hkv][k]   out, padded with -1
+ *   n_recall     i32 [B][Hkv]   out
+ */
+int periodic_recall(const scout_problem* p, const void* q, const void* digest,
+                    int32_t* block_table, int32_t* recall_blk, int32_t* recall_slot,
+                    int32_t* evict_blk, int32_t* n_recall, void* ws, size_t ws_bytes,
+                    void* stream);
+
+/*
+ * One whole layer-step (Sec. 3.2, steps 1-4 above) with the fewest launches:
+ * score, select, attend, and combine the attention splits together with the
+ * host partial.  Outputs are those of the four separate calls; host_* may be
+ * all NULL (nothing offloaded).  sel_host / n_host tell the host which blocks
+ * it has to cover for this query.
+ */
+int scout_layer_step(const scout_problem* p, const void* q, const void* digest,
+                     const int32_t* block_table, const void* k_pool, const void* v_pool,
+                     int64_t n_slots, const float* host_o, const float* host_m,
+                     const float* host_l, float* scores, int32_t* sel_all, int32_t* sel_gpu,
+                     int32_t* slot_gpu, int32_t* n_gpu, int32_t* sel_host, int32_t* n_host,
+                     void* out, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Tuning knob for measurements: force the attention kernel family and split
+ * count.  family: 0 = automatic, 1 = generic vector-ALU kernel, 2 = MFMA
+ * kernel (bf16, d = 128, S = 32 only; otherwise SCOUT_EUNSUPPORTED at the
+ * call).  nsplit: 0 = automatic, else 1..64.  Process-wide, not thread-safe.
+ */
+int scout_set_attn_mode(int family, int nsplit);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCOUT_H */

@@ -1,0 +1,169 @@
+"""ctypes binding of libscout.so: argument marshalling only.
+
+Every function takes torch CUDA tensors (device memory owned by the caller),
+passes their addresses and the current HIP stream to the C ABI of
+``include/scout.h`` and raises ``ScoutError`` on a negative return code.  There
+is no CPU fallback: if the library has not been built, loading fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libscout.so")
+
+F32, BF16 = 0, 1
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
+
+EXPORTS = ["scout_version", "scout_strerror", "scout_workspace_bytes", "build_digests", "score_blocks",
+           "select_topk", "sparse_decode_attn", "merge_partials", "periodic_recall",
+           "scout_layer_step", "scout_set_attn_mode", "scout_attn_partials"]
+
+
+class ScoutError(RuntimeError):
+    def __init__(self, fn: str, code: int, msg: str):
+        super().__init__(f"{fn}: {msg} ({code})")
+        self.code = code
+
+
+class Problem(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+                ("d", ctypes.c_int32), ("S", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("max_blocks", ctypes.c_int32), ("k", ctypes.c_int32), ("sm_scale", ctypes.c_float),
+                ("ctx_len", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library (built beforehand with ``paper_2603_27138_amd.build``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it first (python -m paper_2603_27138_amd.build); "
+                "there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, i64 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int64
+        pp = ctypes.POINTER(Problem)
+        L.scout_version.restype = ctypes.c_int
+        L.scout_strerror.restype = ctypes.c_char_p
+        L.scout_strerror.argtypes = [ctypes.c_int]
+        L.scout_set_attn_mode.argtypes = [ctypes.c_int, ctypes.c_int]
+        L.scout_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
+        L.build_digests.argtypes = [pp, vp, vp, vp]
+        L.score_blocks.argtypes = [pp, vp, vp, vp, vp, sz, vp]
+        L.select_topk.argtypes = [pp] + [vp] * 9 + [sz, vp]
+        L.sparse_decode_attn.argtypes = [pp, vp, vp, vp, i64] + [vp] * 7 + [sz, vp]
+        L.merge_partials.argtypes = [pp] + [vp] * 9
+        L.scout_attn_partials.argtypes = [pp, vp, vp, vp, i64] + [vp] * 4 + [sz, vp]
+        L.periodic_recall.argtypes = [pp] + [vp] * 8 + [sz, vp]
+        L.scout_layer_step.argtypes = [pp, vp, vp, vp, vp, vp, i64] + [vp] * 13 + [sz, vp]
+        for name in EXPORTS:
+            if name not in ("scout_strerror",):
+                getattr(L, name).restype = getattr(L, name).restype or ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _check(fn: str, rc: int):
+    if rc != 0:
+        raise ScoutError(fn, rc, lib().scout_strerror(rc).decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous CUDA tensors"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported element type {t.dtype}")
+
+
+def make_problem(B, Hq, Hkv, d, S, dtype, max_blocks, k, ctx_len: torch.Tensor, sm_scale: float = 0.0):
+    assert ctx_len.dtype == torch.int32 and ctx_len.is_cuda
+    return Problem(B, Hq, Hkv, d, S, dtype, max_blocks, k, float(sm_scale), ctx_len.data_ptr())
+
+
+def version() -> int:
+    return lib().scout_version()
+
+
+def set_attn_mode(family: int = 0, nsplit: int = 0):
+    _check("scout_set_attn_mode", lib().scout_set_attn_mode(family, nsplit))
+
+
+def workspace_bytes(p: Problem) -> int:
+    n = ctypes.c_size_t(0)
+    _check("scout_workspace_bytes", lib().scout_workspace_bytes(ctypes.byref(p), ctypes.byref(n)))
+    return n.value
+
+
+def alloc_workspace(p: Problem, device="cuda") -> torch.Tensor:
+    return torch.empty(workspace_bytes(p), dtype=torch.uint8, device=device)
+
+
+def build_digests(p: Problem, k_blocks, digest):
+    _check("build_digests", lib().build_digests(ctypes.byref(p), _ptr(k_blocks), _ptr(digest), _stream()))
+
+
+def score_blocks(p: Problem, q, digest, scores, ws):
+    _check("score_blocks", lib().score_blocks(ctypes.byref(p), _ptr(q), _ptr(digest), _ptr(scores),
+                                              _ptr(ws), ws.numel(), _stream()))
+
+
+def select_topk(p: Problem, scores, block_table, sel_all, sel_gpu, slot_gpu, n_gpu, sel_host, n_host, ws):
+    _check("select_topk", lib().select_topk(ctypes.byref(p), _ptr(scores), _ptr(block_table), _ptr(sel_all),
+                                            _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu), _ptr(sel_host),
+                                            _ptr(n_host), _ptr(ws), ws.numel(), _stream()))
+
+
+def sparse_decode_attn(p: Problem, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, o, m, l, ws):
+    _check("sparse_decode_attn",
+           lib().sparse_decode_attn(ctypes.byref(p), _ptr(q), _ptr(k_pool), _ptr(v_pool), int(n_slots),
+                                    _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu), _ptr(o), _ptr(m), _ptr(l),
+                                    _ptr(ws), ws.numel(), _stream()))
+
+
+def attn_partials(p: Problem, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, ws):
+    _check("scout_attn_partials",
+           lib().scout_attn_partials(ctypes.byref(p), _ptr(q), _ptr(k_pool), _ptr(v_pool), int(n_slots),
+                                     _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu), _ptr(ws), ws.numel(),
+                                     _stream()))
+
+
+def merge_partials(p: Problem, o_a, m_a, l_a, o_b, m_b, l_b, out, lse=None):
+    _check("merge_partials", lib().merge_partials(ctypes.byref(p), _ptr(o_a), _ptr(m_a), _ptr(l_a), _ptr(o_b),
+                                                  _ptr(m_b), _ptr(l_b), _ptr(out), _ptr(lse), _stream()))
+
+
+def periodic_recall(p: Problem, q, digest, block_table, recall_blk, recall_slot, evict_blk, n_recall, ws):
+    _check("periodic_recall",
+           lib().periodic_recall(ctypes.byref(p), _ptr(q), _ptr(digest), _ptr(block_table), _ptr(recall_blk),
+                                 _ptr(recall_slot), _ptr(evict_blk), _ptr(n_recall), _ptr(ws), ws.numel(),
+                                 _stream()))
+
+
+def layer_step(p: Problem, q, digest, block_table, k_pool, v_pool, n_slots, host_o, host_m, host_l, scores,
+               sel_all, sel_gpu, slot_gpu, n_gpu, sel_host, n_host, out, lse, ws):
+    _check("scout_layer_step",
+           lib().scout_layer_step(ctypes.byref(p), _ptr(q), _ptr(digest), _ptr(block_table), _ptr(k_pool),
+                                  _ptr(v_pool), int(n_slots), _ptr(host_o), _ptr(host_m), _ptr(host_l),
+                                  _ptr(scores), _ptr(sel_all), _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu),
+                                  _ptr(sel_host), _ptr(n_host), _ptr(out), _ptr(lse), _ptr(ws), ws.numel(),
+                                  _stream()))

@@ -1,0 +1,303 @@
+// C ABI: argument validation, workspace carving, kernel-family choice.
+// Nothing here computes; every step of the path runs in the kernels.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+
+#include "common.h"
+
+namespace scout {
+
+int launch_digest(const Dims&, int, const void*, void*, hipStream_t);
+int launch_score(const Dims&, int, const void*, const void*, float*, hipStream_t);
+int launch_topk(const Dims&, const float*, const int32_t*, int32_t*, int32_t*, int32_t*, int32_t*,
+                int32_t*, int32_t*, hipStream_t);
+int launch_recall(const Dims&, const float*, int32_t*, int32_t*, int32_t*, int32_t*, int32_t*,
+                  hipStream_t);
+bool mfma_supported(const Dims&, int);
+int launch_attn(const Dims&, int, int, const void*, const void*, const void*, long long,
+                const int32_t*, const int32_t*, const int32_t*, Partials, hipStream_t);
+int launch_combine(const Dims&, int, Partials, float*, float*, float*, const float*, const float*,
+                   const float*, void*, float*, int, hipStream_t);
+int launch_merge(const Dims&, int, const float*, const float*, const float*, const float*,
+                 const float*, const float*, void*, float*, hipStream_t);
+
+constexpr int kMaxSplit = 64;
+constexpr int kValuHeadsPerWave = 4;
+constexpr int kMfmaWavesPerWg = 4;
+
+static int g_family = 0;  // 0 auto, 1 vector ALU, 2 MFMA
+static int g_nsplit = 0;  // 0 auto
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static int check_problem(const scout_problem* p, Dims* D) {
+  if (p == nullptr) return SCOUT_EINVAL;
+  if (p->B < 0 || p->Hq <= 0 || p->Hkv <= 0 || p->Hq % p->Hkv != 0) return SCOUT_EINVAL;
+  if (p->max_blocks < 1 || p->k < 1) return SCOUT_EINVAL;
+  if (p->dtype != SCOUT_F32 && p->dtype != SCOUT_BF16) return SCOUT_EINVAL;
+  if (!(p->sm_scale >= 0.0f) || std::isinf(p->sm_scale)) return SCOUT_EINVAL;
+  if (p->ctx_len == nullptr) return SCOUT_EINVAL;
+  if (p->d != 64 && p->d != 128) return SCOUT_EUNSUPPORTED;
+  if (p->S != 16 && p->S != 32 && p->S != 64) return SCOUT_EUNSUPPORTED;
+  if (p->Hq / p->Hkv > 16) return SCOUT_EUNSUPPORTED;
+  if (p->max_blocks > 16384 || p->k > 1024) return SCOUT_EUNSUPPORTED;
+  if ((long long)p->B * p->Hq > (1ll << 30)) return SCOUT_EUNSUPPORTED;
+  D->B = p->B;
+  D->Hq = p->Hq;
+  D->Hkv = p->Hkv;
+  D->G = p->Hq / p->Hkv;
+  D->d = p->d;
+  D->S = p->S;
+  D->max_blocks = p->max_blocks;
+  D->k = p->k;
+  D->sm_scale = p->sm_scale > 0.0f ? p->sm_scale : 1.0f / std::sqrt((float)p->d);
+  D->ctx_len = p->ctx_len;
+  return SCOUT_OK;
+}
+
+static size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct WsLayout {
+  size_t part_o, part_m, part_l, scores, total;
+};
+
+static WsLayout ws_layout(const Dims& D) {
+  const size_t pairs = (size_t)D.B * D.Hkv;
+  WsLayout L;
+  size_t at = 0;
+  L.part_o = at;
+  at += round256(pairs * kMaxSplit * D.G * D.d * sizeof(float));
+  L.part_m = at;
+  at += round256(pairs * kMaxSplit * D.G * sizeof(float));
+  L.part_l = at;
+  at += round256(pairs * kMaxSplit * D.G * sizeof(float));
+  L.scores = at;
+  at += round256(pairs * D.max_blocks * sizeof(float));
+  L.total = at > 0 ? at : 256;
+  return L;
+}
+
+static int check_ws(const Dims& D, void* ws, size_t ws_bytes, WsLayout* L) {
+  *L = ws_layout(D);
+  if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) & 255u) != 0 || ws_bytes < L->total)
+    return SCOUT_EWORKSPACE;
+  return SCOUT_OK;
+}
+
+// which attention kernel family and how many splits per pair
+static int plan_attn(const Dims& D, int dtype, int* family, int* nsplit) {
+  int fam = g_family;
+  if (fam == 0) fam = mfma_supported(D, dtype) ? 2 : 1;
+  if (fam == 2 && !mfma_supported(D, dtype)) return SCOUT_EUNSUPPORTED;
+  const long long pairs = (long long)D.B * D.Hkv;
+  int ns = g_nsplit;
+  if (ns == 0) {
+    // aim at about 16 waves on each of the 256 compute units
+    const long long target_waves = 256 * 16;
+    const long long waves_per_split =
+        fam == 2 ? kMfmaWavesPerWg : (D.G + kValuHeadsPerWave - 1) / kValuHeadsPerWave;
+    long long want = (target_waves + pairs * waves_per_split - 1) / (pairs > 0 ? pairs * waves_per_split : 1);
+    const int blocks_per_split_unit = fam == 2 ? kMfmaWavesPerWg : 1;
+    const long long cap = (D.k + blocks_per_split_unit - 1) / blocks_per_split_unit;
+    if (want > cap) want = cap;
+    if (want < 1) want = 1;
+    ns = (int)want;
+  }
+  if (ns < 1 || ns > kMaxSplit) ns = ns < 1 ? 1 : kMaxSplit;
+  *family = fam;
+  *nsplit = ns;
+  return SCOUT_OK;
+}
+
+static Partials carve(void* ws, const WsLayout& L, int nsplit) {
+  char* base = static_cast<char*>(ws);
+  return Partials{reinterpret_cast<float*>(base + L.part_o), reinterpret_cast<float*>(base + L.part_m),
+                  reinterpret_cast<float*>(base + L.part_l), nsplit};
+}
+
+}  // namespace scout
+
+using namespace scout;
+
+extern "C" {
+
+int scout_version(void) { return 100; }
+
+const char* scout_strerror(int code) {
+  switch (code) {
+    case SCOUT_OK: return "ok";
+    case SCOUT_EINVAL: return "invalid argument";
+    case SCOUT_EUNSUPPORTED: return "shape or type not supported by the kernels";
+    case SCOUT_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case SCOUT_EHIP: return "HIP runtime error at launch";
+    default: return "unknown error";
+  }
+}
+
+int scout_set_attn_mode(int family, int nsplit) {
+  if (family < 0 || family > 2 || nsplit < 0 || nsplit > kMaxSplit) return SCOUT_EINVAL;
+  g_family = family;
+  g_nsplit = nsplit;
+  return SCOUT_OK;
+}
+
+int scout_workspace_bytes(const scout_problem* p, size_t* bytes) {
+  Dims D;
+  if (bytes == nullptr) return SCOUT_EINVAL;
+  // ctx_len is not needed to size the workspace
+  scout_problem tmp;
+  if (p == nullptr) return SCOUT_EINVAL;
+  tmp = *p;
+  static const int32_t dummy = 0;
+  if (tmp.ctx_len == nullptr) tmp.ctx_len = &dummy;
+  const int rc = check_problem(&tmp, &D);
+  if (rc != SCOUT_OK) return rc;
+  *bytes = ws_layout(D).total;
+  return SCOUT_OK;
+}
+
+int build_digests(const scout_problem* p, const void* k_blocks, void* digest, void* stream) {
+  Dims D;
+  int rc = check_problem(p, &D);
+  if (rc != SCOUT_OK) return rc;
+  if (k_blocks == nullptr || digest == nullptr || !aligned16(k_blocks) || !aligned16(digest))
+    return SCOUT_EINVAL;
+  return launch_digest(D, p->dtype, k_blocks, digest, static_cast<hipStream_t>(stream));
+}
+
+int score_blocks(const scout_problem* p, const void* q, const void* digest, float* scores, void* ws,
+                 size_t ws_bytes, void* stream) {
+  (void)ws;
+  (void)ws_bytes;
+  Dims D;
+  int rc = check_problem(p, &D);
+  if (rc != SCOUT_OK) return rc;
+  if (q == nullptr || digest == nullptr || scores == nullptr) return SCOUT_EINVAL;
+  if (!aligned16(q) || !aligned16(digest) || !aligned16(scores)) return SCOUT_EINVAL;
+  return launch_score(D, p->dtype, q, digest, scores, static_cast<hipStream_t>(stream));
+}
+
+int select_topk(const scout_problem* p, const float* scores, const int32_t* block_table,
+                int32_t* sel_all, int32_t* sel_gpu, int32_t* slot_gpu, int32_t* n_gpu,
+                int32_t* sel_host, int32_t* n_host, void* ws, size_t ws_bytes, void* stream) {
+  (void)ws;
+  (void)ws_bytes;
+  Dims D;
+  int rc = check_problem(p, &D);
+  if (rc != SCOUT_OK) return rc;
+  if (!scores || !block_table || !sel_all || !sel_gpu || !slot_gpu || !n_gpu || !sel_host || !n_host)
+    return SCOUT_EINVAL;
+  return launch_topk(D, scores, block_table, sel_all, sel_gpu, slot_gpu, n_gpu, sel_host, n_host,
+                     static_cast<hipStream_t>(stream));
+}
+
+int scout_attn_partials(const scout_problem* p, const void* q, const void* k_pool, const void* v_pool,
+                        int64_t n_slots, const int32_t* sel_gpu, const int32_t* slot_gpu,
+                        const int32_t* n_gpu, void* ws, size_t ws_bytes, void* stream) {
+  Dims D;
+  int rc = check_problem(p, &D);
+  if (rc != SCOUT_OK) return rc;
+  if (!q || !sel_gpu || !slot_gpu || !n_gpu || n_slots < 0) return SCOUT_EINVAL;
+  if (n_slots > 0 && (!k_pool || !v_pool)) return SCOUT_EINVAL;
+  if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool)) return SCOUT_EINVAL;
+  WsLayout L;
+  rc = check_ws(D, ws, ws_bytes, &L);
+  if (rc != SCOUT_OK) return rc;
+  int family, nsplit;
+  rc = plan_attn(D, p->dtype, &family, &nsplit);
+  if (rc != SCOUT_OK) return rc;
+  return launch_attn(D, p->dtype, family, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu,
+                     carve(ws, L, nsplit), static_cast<hipStream_t>(stream));
+}
+
+int sparse_decode_attn(const scout_problem* p, const void* q, const void* k_pool, const void* v_pool,
+                       int64_t n_slots, const int32_t* sel_gpu, const int32_t* slot_gpu,
+                       const int32_t* n_gpu, float* o, float* m, float* l, void* ws, size_t ws_bytes,
+                       void* stream) {
+  Dims D;
+  int rc = check_problem(p, &D);
+  if (rc != SCOUT_OK) return rc;
+  if (!q || !sel_gpu || !slot_gpu || !n_gpu || !o || !m || !l || n_slots < 0) return SCOUT_EINVAL;
+  if (n_slots > 0 && (!k_pool || !v_pool)) return SCOUT_EINVAL;
+  if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(o)) return SCOUT_EINVAL;
+  WsLayout L;
+  rc = check_ws(D, ws, ws_bytes, &L);
+  if (rc != SCOUT_OK) return rc;
+  int family, nsplit;
+  rc = plan_attn(D, p->dtype, &family, &nsplit);
+  if (rc != SCOUT_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Partials P = carve(ws, L, nsplit);
+  rc = launch_attn(D, p->dtype, family, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, P, st);
+  if (rc != SCOUT_OK) return rc;
+  return launch_combine(D, p->dtype, P, o, m, l, nullptr, nullptr, nullptr, nullptr, nullptr, 0, st);
+}
+
+int merge_partials(const scout_problem* p, const float* o_a, const float* m_a, const float* l_a,
+                   const float* o_b, const float* m_b, const float* l_b, void* out, float* lse,
+                   void* stream) {
+  Dims D;
+  int rc = check_problem(p, &D);
+  if (rc != SCOUT_OK) return rc;
+  if (!o_a || !m_a || !l_a || !out) return SCOUT_EINVAL;
+  const bool any_b = o_b || m_b || l_b, all_b = o_b && m_b && l_b;
+  if (any_b && !all_b) return SCOUT_EINVAL;
+  return launch_merge(D, p->dtype, o_a, m_a, l_a, o_b, m_b, l_b, out, lse,
+                      static_cast<hipStream_t>(stream));
+}
+
+int periodic_recall(const scout_problem* p, const void* q, const void* digest, int32_t* block_table,
+                    int32_t* recall_blk, int32_t* recall_slot, int32_t* evict_blk, int32_t* n_recall,
+                    void* ws, size_t ws_bytes, void* stream) {
+  Dims D;
+  int rc = check_problem(p, &D);
+  if (rc != SCOUT_OK) return rc;
+  if (!q || !digest || !block_table || !recall_blk || !recall_slot || !evict_blk || !n_recall)
+    return SCOUT_EINVAL;
+  if (!aligned16(q) || !aligned16(digest)) return SCOUT_EINVAL;
+  WsLayout L;
+  rc = check_ws(D, ws, ws_bytes, &L);
+  if (rc != SCOUT_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* scores = reinterpret_cast<float*>(static_cast<char*>(ws) + L.scores);
+  rc = launch_score(D, p->dtype, q, digest, scores, st);
+  if (rc != SCOUT_OK) return rc;
+  return launch_recall(D, scores, block_table, recall_blk, recall_slot, evict_blk, n_recall, st);
+}
+
+int scout_layer_step(const scout_problem* p, const void* q, const void* digest,
+                     const int32_t* block_table, const void* k_pool, const void* v_pool,
+                     int64_t n_slots, const float* host_o, const float* host_m, const float* host_l,
+                     float* scores, int32_t* sel_all, int32_t* sel_gpu, int32_t* slot_gpu,
+                     int32_t* n_gpu, int32_t* sel_host, int32_t* n_host, void* out, float* lse, void* ws,
+                     size_t ws_bytes, void* stream) {
+  Dims D;
+  int rc = check_problem(p, &D);
+  if (rc != SCOUT_OK) return rc;
+  if (!q || !digest || !block_table || !scores || !sel_all || !sel_gpu || !slot_gpu || !n_gpu ||
+      !sel_host || !n_host || !out || n_slots < 0)
+    return SCOUT_EINVAL;
+  if (n_slots > 0 && (!k_pool || !v_pool)) return SCOUT_EINVAL;
+  const bool any_b = host_o || host_m || host_l, all_b = host_o && host_m && host_l;
+  if (any_b && !all_b) return SCOUT_EINVAL;
+  if (!aligned16(q) || !aligned16(digest) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(scores))
+    return SCOUT_EINVAL;
+  WsLayout L;
+  rc = check_ws(D, ws, ws_bytes, &L);
+  if (rc != SCOUT_OK) return rc;
+  int family, nsplit;
+  rc = plan_attn(D, p->dtype, &family, &nsplit);
+  if (rc != SCOUT_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  rc = launch_score(D, p->dtype, q, digest, scores, st);
+  if (rc != SCOUT_OK) return rc;
+  rc = launch_topk(D, scores, block_table, sel_all, sel_gpu, slot_gpu, n_gpu, sel_host, n_host, st);
+  if (rc != SCOUT_OK) return rc;
+  Partials P = carve(ws, L, nsplit);
+  rc = launch_attn(D, p->dtype, family, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, P, st);
+  if (rc != SCOUT_OK) return rc;
+  return launch_combine(D, p->dtype, P, nullptr, nullptr, nullptr, host_o, host_m, host_l, out, lse, 1, st);
+}
+
+}  // extern "C"

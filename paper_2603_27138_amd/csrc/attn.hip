@@ -1,0 +1,502 @@
+// Block-sparse paged decode attention over the selected GPU-resident blocks
+// (Sec. 3.2; Alg. 1 GPUAttn) and the merge of partial results (Alg. 1 Merge).
+//
+// A partial result of a token set is (o, m, l): m the largest logit, l the sum
+// of exp(logit - m), o the weighted value sum.  Partials of disjoint sets
+// combine exactly (FlashAttention rescaling), which is used three times: across
+// the blocks a wave walks through, across the waves / workgroups that split a
+// pair's block list, and finally with the host's partial.
+//
+// Inside the kernels logits are kept in base-2 units (x * log2(e)), so the
+// exponentials are bare v_exp_f32; m is converted back to natural-log units
+// where it leaves the library.
+//
+// Two kernel families write the same per-split partials into the workspace:
+//   attn_mfma_kernel  bf16, d = 128, S = 32: the G query heads of a KV head form
+//                     one MFMA operand, K and V tiles go from HBM straight into
+//                     MFMA operand registers (no LDS), one 16 KiB K+V tile pair
+//                     per wave iteration.
+//   attn_valu_kernel  any supported (dtype, d, S): plain vector ALU, used for
+//                     fp32 and the other shapes.
+// combine_kernel folds the splits (and optionally the host partial) together.
+#include "common.h"
+
+namespace scout {
+
+__device__ __forceinline__ float exp2_diff(float a, float b) {
+  // 2^(a-b) with the convention 2^(-inf - anything) = 0
+  return a == -INFINITY ? 0.0f : exp2f(a - b);
+}
+
+// ---------------------------------------------------------------- MFMA family
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// Pack the low (sel = 0) or high (sel = 1) bf16 of two dwords into one dword:
+// result.lo = half(a), result.hi = half(b).
+__device__ __forceinline__ uint32_t pack_halves(uint32_t a, uint32_t b, int sel) {
+  return sel ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+}
+
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+// two binary32 -> one dword of two bf16 (round to nearest even), x in the low half
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float x, float y) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){x, y}, bf16x2));
+}
+
+constexpr int kMfmaD = 128;
+constexpr int kMfmaS = 32;
+
+// One wave per (pair, split, wave-in-workgroup) walks over the pair's resident
+// selected blocks i = first, first + stride, ...  For each block:
+//   logits^T[token][head] = K[token][:] . Q[head][:]      8 x mfma 16x16x32
+//   online softmax per head (heads live in lane % 16)
+//   out^T[dim][head]    += V^T[dim][token] . P^T[token][head]   8 x mfma 16x16x32
+// Operand layout of v_mfma_f32_16x16x32_bf16: lane L supplies, for A, row L%16
+// and for B, column L%16, the 8 contraction elements of group L/16; the result
+// has column L%16 and rows 4*(L/16)+i.  The contraction index may be labelled
+// freely as long as A and B agree, which lets the logits leave the first
+// product in exactly the registers the second one needs: lane L ends up with the
+// logits of head L%16 for tokens 16*j + 4*(L/16) + i (j = 0,1; i = 0..3), so the
+// value rows are loaded in that same token order.  Element r of a lane's 16-byte
+// value chunk feeds product r, whose output row index then means channel
+// 8*row + r.
+template <int WAVES>
+__global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
+    Dims D, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_pool,
+    const uint16_t* __restrict__ v_pool, long long n_slots, const int32_t* __restrict__ sel_gpu,
+    const int32_t* __restrict__ slot_gpu, const int32_t* __restrict__ n_gpu, Partials P) {
+  // per wave: [G<=16][132] floats of o (padded rows), then m[16], l[16]
+  constexpr int ROW = kMfmaD + 4;
+  extern __shared__ float smem[];
+  const int pair = blockIdx.y, split = blockIdx.x;
+  const int b = pair / D.Hkv, g = pair % D.Hkv;
+  const int lane = lane_id(), wave = threadIdx.x / kWave;
+  const int ln = lane & 15, kg = lane >> 4;
+  const int G = D.G;
+
+  int n = n_gpu[pair];
+  n = n < 0 ? 0 : (n > D.k ? D.k : n);
+  const int ctx = D.ctx_len[b];
+  const float scale2 = D.sm_scale * kLog2e;
+
+  // B operand of the first product: Q^T, column = head ln, zero beyond G
+  u32x4 qreg[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    qreg[s] = (u32x4){0, 0, 0, 0};
+    if (ln < G) {
+      const size_t off = ((size_t)b * D.Hq + g * G + ln) * kMfmaD + s * 32 + kg * 8;
+      qreg[s] = *reinterpret_cast<const u32x4*>(q + off);
+    }
+  }
+
+  f32x4 acc[8];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) acc[r] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.0f;
+
+  const int first = split * WAVES + wave, stride = P.nsplit * WAVES;
+  for (int i = first; i < n; i += stride) {
+    // the same entry for every lane: keep it in scalar registers
+    const int j = __builtin_amdgcn_readfirstlane(sel_gpu[(size_t)pair * D.k + i]);
+    const long long slot = __builtin_amdgcn_readfirstlane(slot_gpu[(size_t)pair * D.k + i]);
+    int valid = ctx - j * kMfmaS;
+    valid = valid > kMfmaS ? kMfmaS : valid;
+    if (j < 0 || valid <= 0 || slot < 0 || slot >= n_slots) continue;  // wave-uniform
+
+    const uint16_t* kt = k_pool + (size_t)slot * (kMfmaS * kMfmaD);
+    const uint16_t* vt = v_pool + (size_t)slot * (kMfmaS * kMfmaD);
+
+    // K tile: A operand, row = token 16*jt + ln, contraction group kg of step s
+    u32x4 kreg[2][4];
+#pragma unroll
+    for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        kreg[jt][s] = *reinterpret_cast<const u32x4*>(kt + (16 * jt + ln) * kMfmaD + s * 32 + kg * 8);
+    // V tile: rows in the token order of this lane's logits, 16-byte chunk ln
+    u32x4 vreg[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int tok = 16 * (e >> 2) + 4 * kg + (e & 3);
+      vreg[e] = *reinterpret_cast<const u32x4*>(vt + tok * kMfmaD + ln * 8);
+    }
+
+    f32x4 st[2];
+#pragma unroll
+    for (int jt = 0; jt < 2; ++jt) {
+      st[jt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        st[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kreg[jt][s]), as_bf16x8(qreg[s]),
+                                                         st[jt], 0, 0, 0);
+    }
+    // st[jt][i] = logit of head ln, token 16*jt + 4*kg + i
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = st[e >> 2][e & 3] * scale2;
+    if (valid < kMfmaS) {  // partial last block of a sequence: drop the tail rows
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int tok = 16 * (e >> 2) + 4 * kg + (e & 3);
+        if (tok >= valid) {
+          x[e] = -INFINITY;
+          vreg[e] = (u32x4){0, 0, 0, 0};
+        }
+      }
+    }
+    float bm = x[0];
+#pragma unroll
+    for (int e = 1; e < 8; ++e) bm = fmaxf(bm, x[e]);
+    bm = fmaxf(bm, __shfl_xor(bm, 16));
+    bm = fmaxf(bm, __shfl_xor(bm, 32));
+    const float m_new = fmaxf(m_run, bm);  // finite: a listed block has a valid token
+    const float alpha = exp2_diff(m_run, m_new);
+    float p[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) p[e] = exp2f(x[e] - m_new);
+    // weights go into the second product as bf16; sum what is actually used
+    u32x4 preg;
+    float psum = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      preg[w] = cvt_pk_bf16(p[2 * w], p[2 * w + 1]);
+      psum += bf16_lo(preg[w]) + bf16_hi(preg[w]);
+    }
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) acc[r] *= alpha;
+
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      u32x4 a;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) a[w] = pack_halves(vreg[2 * w][r >> 1], vreg[2 * w + 1][r >> 1], r & 1);
+      acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(preg), acc[r], 0, 0, 0);
+    }
+  }
+
+  // lanes kg = 0..3 of a head saw disjoint tokens under a common maximum
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+
+  // fold the waves of the workgroup through LDS
+  float* wo = smem + (size_t)wave * (16 * ROW + 32);
+  float* wm = wo + 16 * ROW;
+  float* wl = wm + 16;
+  if (ln < G) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      // acc[r][i]: channel 8*(4*kg + i) + r
+      float* dst = wo + ln * ROW + 8 * (4 * kg + i);
+      *reinterpret_cast<float4*>(dst) = make_float4(acc[0][i], acc[1][i], acc[2][i], acc[3][i]);
+      *reinterpret_cast<float4*>(dst + 4) = make_float4(acc[4][i], acc[5][i], acc[6][i], acc[7][i]);
+    }
+    if (kg == 0) {
+      wm[ln] = m_run;
+      wl[ln] = l_run;
+    }
+  }
+  __syncthreads();
+  const size_t pbase = (size_t)pair * P.nsplit + split;
+  for (int idx = threadIdx.x; idx < G * kMfmaD; idx += WAVES * kWave) {
+    const int h = idx / kMfmaD, c = idx % kMfmaD;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) M = fmaxf(M, smem[(size_t)w * (16 * ROW + 32) + 16 * ROW + h]);
+    float o = 0.0f, l = 0.0f;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) {
+      const float* base = smem + (size_t)w * (16 * ROW + 32);
+      const float f = exp2_diff(base[16 * ROW + h], M);
+      o += f * base[h * ROW + c];
+      l += f * base[16 * ROW + 16 + h];
+    }
+    P.o[(pbase * G + h) * kMfmaD + c] = o;
+    if (c == 0) {
+      P.m[pbase * G + h] = M;
+      P.l[pbase * G + h] = l;
+    }
+  }
+}
+
+// ---------------------------------------------------------------- VALU family
+
+constexpr int kValuHeads = 4;  // query heads per wave
+
+// One wave per (pair, split, chunk of kValuHeads heads).  A token row is spread
+// over LPT = DH/8 lanes (8 channels each); the 64/LPT lane groups take different
+// tokens of a block and each keeps an online-softmax stream of its own, so the
+// block loop needs no cross-group traffic; the streams are folded at the end.
+template <int DT, int DH>
+__global__ __launch_bounds__(kWave) void attn_valu_kernel(
+    Dims D, const void* __restrict__ q, const void* __restrict__ k_pool,
+    const void* __restrict__ v_pool, long long n_slots, const int32_t* __restrict__ sel_gpu,
+    const int32_t* __restrict__ slot_gpu, const int32_t* __restrict__ n_gpu, Partials P) {
+  constexpr int LPT = DH / 8;      // lanes per token
+  constexpr int TPW = kWave / LPT; // tokens per wave pass
+  const int pair = blockIdx.y, split = blockIdx.x, h0 = blockIdx.z * kValuHeads;
+  const int b = pair / D.Hkv, g = pair % D.Hkv;
+  const int lane = lane_id();
+  const int tl = lane / LPT, c0 = (lane % LPT) * 8;
+  const int G = D.G;
+  const int nh = (G - h0) < kValuHeads ? (G - h0) : kValuHeads;
+
+  int n = n_gpu[pair];
+  n = n < 0 ? 0 : (n > D.k ? D.k : n);
+  const int ctx = D.ctx_len[b];
+  const float scale2 = D.sm_scale * kLog2e;
+
+  float qv[kValuHeads][8];
+#pragma unroll
+  for (int h = 0; h < kValuHeads; ++h) {
+    if (h < nh) {
+      load8<DT>(q, ((size_t)b * D.Hq + g * G + h0 + h) * DH + c0, qv[h]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) qv[h][i] = 0.0f;
+    }
+  }
+  float m_run[kValuHeads], l_run[kValuHeads], o[kValuHeads][8];
+#pragma unroll
+  for (int h = 0; h < kValuHeads; ++h) {
+    m_run[h] = -INFINITY;
+    l_run[h] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[h][i] = 0.0f;
+  }
+
+  for (int i = split; i < n; i += P.nsplit) {
+    const int j = sel_gpu[(size_t)pair * D.k + i];
+    const long long slot = slot_gpu[(size_t)pair * D.k + i];
+    int valid = ctx - j * D.S;
+    valid = valid > D.S ? D.S : valid;
+    if (j < 0 || valid <= 0 || slot < 0 || slot >= n_slots) continue;
+    const size_t tile = (size_t)slot * D.S * DH;
+    for (int t0 = 0; t0 < D.S; t0 += TPW) {
+      const int t = t0 + tl;
+      const bool live = t < valid;
+      float kx[8], vx[8];
+      if (live) {
+        load8<DT>(k_pool, tile + (size_t)t * DH + c0, kx);
+        load8<DT>(v_pool, tile + (size_t)t * DH + c0, vx);
+      } else {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) kx[c] = vx[c] = 0.0f;
+      }
+#pragma unroll
+      for (int h = 0; h < kValuHeads; ++h) {
+        float dot = 0.0f;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) dot = fmaf(qv[h][c], kx[c], dot);
+#pragma unroll
+        for (int off = 1; off < LPT; off <<= 1) dot += __shfl_xor(dot, off);
+        if (live) {
+          const float x = dot * scale2;
+          const float m_new = fmaxf(m_run[h], x);
+          const float a = exp2_diff(m_run[h], m_new);
+          const float pw = exp2f(x - m_new);
+          l_run[h] = l_run[h] * a + pw;
+#pragma unroll
+          for (int c = 0; c < 8; ++c) o[h][c] = fmaf(pw, vx[c], o[h][c] * a);
+          m_run[h] = m_new;
+        }
+      }
+    }
+  }
+
+  // fold the TPW token streams of the wave
+#pragma unroll
+  for (int h = 0; h < kValuHeads; ++h) {
+#pragma unroll
+    for (int off = LPT; off < kWave; off <<= 1) {
+      const float m2 = __shfl_xor(m_run[h], off), l2 = __shfl_xor(l_run[h], off);
+      const float M = fmaxf(m_run[h], m2);
+      const float fa = exp2_diff(m_run[h], M), fb = exp2_diff(m2, M);
+      l_run[h] = l_run[h] * fa + l2 * fb;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) o[h][c] = o[h][c] * fa + __shfl_xor(o[h][c], off) * fb;
+      m_run[h] = M;
+    }
+  }
+  if (tl == 0) {
+    const size_t pbase = (size_t)pair * P.nsplit + split;
+#pragma unroll
+    for (int h = 0; h < kValuHeads; ++h) {
+      if (h < nh) {
+        float* dst = P.o + (pbase * G + h0 + h) * DH + c0;
+        *reinterpret_cast<float4*>(dst) = make_float4(o[h][0], o[h][1], o[h][2], o[h][3]);
+        *reinterpret_cast<float4*>(dst + 4) = make_float4(o[h][4], o[h][5], o[h][6], o[h][7]);
+        if (c0 == 0) {
+          P.m[pbase * G + h0 + h] = m_run[h];
+          P.l[pbase * G + h0 + h] = l_run[h];
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------- combine and merge
+
+// Fold the nsplit partials of every (sequence, query head); then either export
+// the GPU partial (o, m, l) or go straight on to the merge with the host's
+// partial and write the final output.  One workgroup of d threads per head.
+template <int DT_OUT>
+__global__ void combine_kernel(Dims D, Partials P, float* __restrict__ o_out, float* __restrict__ m_out,
+                               float* __restrict__ l_out, const float* __restrict__ host_o,
+                               const float* __restrict__ host_m, const float* __restrict__ host_l,
+                               void* __restrict__ out, float* __restrict__ lse, int fuse_merge) {
+  const int bh = blockIdx.x;  // b * Hq + hq
+  const int b = bh / D.Hq, hq = bh % D.Hq;
+  const int pair = b * D.Hkv + hq / D.G, h = hq % D.G;
+  const int c = threadIdx.x;
+  const size_t p0 = (size_t)pair * P.nsplit;
+  float M = -INFINITY;
+  for (int s = 0; s < P.nsplit; ++s) M = fmaxf(M, P.m[(p0 + s) * D.G + h]);
+  float acc = 0.0f, l = 0.0f;
+  for (int s = 0; s < P.nsplit; ++s) {
+    const float f = exp2_diff(P.m[(p0 + s) * D.G + h], M);
+    acc += f * P.o[((p0 + s) * D.G + h) * D.d + c];
+    l += f * P.l[(p0 + s) * D.G + h];
+  }
+  const float m_nat = M * kLn2;  // -inf stays -inf
+  const float o_norm = l > 0.0f ? acc / l : 0.0f;
+  if (!fuse_merge) {
+    o_out[(size_t)bh * D.d + c] = o_norm;
+    if (c == 0) {
+      m_out[bh] = m_nat;
+      l_out[bh] = l;
+    }
+    return;
+  }
+  float mb = -INFINITY, lb = 0.0f, ob = 0.0f;
+  if (host_o != nullptr) {
+    mb = host_m[bh];
+    lb = host_l[bh];
+    ob = host_o[(size_t)bh * D.d + c];
+  }
+  float ms = -INFINITY;
+  if (l > 0.0f) ms = fmaxf(ms, m_nat);
+  if (lb > 0.0f) ms = fmaxf(ms, mb);
+  const float wa = l > 0.0f ? l * expf(m_nat - ms) : 0.0f;
+  const float wb = lb > 0.0f ? lb * expf(mb - ms) : 0.0f;
+  const float ls = wa + wb;
+  float r = 0.0f;
+  if (wa > 0.0f) r += wa * o_norm;
+  if (wb > 0.0f) r += wb * ob;
+  r = ls > 0.0f ? r / ls : 0.0f;
+  if (DT_OUT == SCOUT_BF16)
+    static_cast<uint16_t*>(out)[(size_t)bh * D.d + c] = (uint16_t)f32_to_bf16_bits(r);
+  else
+    static_cast<float*>(out)[(size_t)bh * D.d + c] = r;
+  if (lse != nullptr && c == 0) lse[bh] = ls > 0.0f ? ms + logf(ls) : -INFINITY;
+}
+
+// Stand-alone merge of two partials given in natural-log units (Alg. 1 Merge).
+template <int DT_OUT>
+__global__ void merge_kernel(Dims D, const float* __restrict__ o_a, const float* __restrict__ m_a,
+                             const float* __restrict__ l_a, const float* __restrict__ o_b,
+                             const float* __restrict__ m_b, const float* __restrict__ l_b,
+                             void* __restrict__ out, float* __restrict__ lse) {
+  const int bh = blockIdx.x, c = threadIdx.x;
+  const float ma = m_a[bh], la = l_a[bh];
+  float mb = -INFINITY, lb = 0.0f, ob = 0.0f;
+  if (o_b != nullptr) {
+    mb = m_b[bh];
+    lb = l_b[bh];
+    ob = o_b[(size_t)bh * D.d + c];
+  }
+  float ms = -INFINITY;
+  if (la > 0.0f) ms = fmaxf(ms, ma);
+  if (lb > 0.0f) ms = fmaxf(ms, mb);
+  const float wa = la > 0.0f ? la * expf(ma - ms) : 0.0f;
+  const float wb = lb > 0.0f ? lb * expf(mb - ms) : 0.0f;
+  const float ls = wa + wb;
+  float r = 0.0f;
+  if (wa > 0.0f) r += wa * o_a[(size_t)bh * D.d + c];
+  if (wb > 0.0f) r += wb * ob;
+  r = ls > 0.0f ? r / ls : 0.0f;
+  if (DT_OUT == SCOUT_BF16)
+    static_cast<uint16_t*>(out)[(size_t)bh * D.d + c] = (uint16_t)f32_to_bf16_bits(r);
+  else
+    static_cast<float*>(out)[(size_t)bh * D.d + c] = r;
+  if (lse != nullptr && c == 0) lse[bh] = ls > 0.0f ? ms + logf(ls) : -INFINITY;
+}
+
+// ------------------------------------------------------------ host launchers
+
+constexpr int kMfmaWaves = 4;
+
+size_t mfma_smem_bytes(int waves) { return (size_t)waves * (16 * (kMfmaD + 4) + 32) * sizeof(float); }
+
+bool mfma_supported(const Dims& D, int dtype) {
+  return dtype == SCOUT_BF16 && D.d == kMfmaD && D.S == kMfmaS && D.G <= 16;
+}
+
+int launch_attn(const Dims& D, int dtype, int family, const void* q, const void* k_pool,
+                const void* v_pool, long long n_slots, const int32_t* sel_gpu,
+                const int32_t* slot_gpu, const int32_t* n_gpu, Partials P, hipStream_t st) {
+  const int pairs = D.B * D.Hkv;
+  if (pairs == 0) return SCOUT_OK;
+  if (family == 2) {
+    dim3 grid(P.nsplit, pairs), block(kMfmaWaves * kWave);
+    hipLaunchKernelGGL((attn_mfma_kernel<kMfmaWaves>), grid, block, mfma_smem_bytes(kMfmaWaves), st, D,
+                       static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k_pool),
+                       static_cast<const uint16_t*>(v_pool), n_slots, sel_gpu, slot_gpu, n_gpu, P);
+  } else {
+    dim3 grid(P.nsplit, pairs, (D.G + kValuHeads - 1) / kValuHeads), block(kWave);
+    if (dtype == SCOUT_BF16 && D.d == 128)
+      hipLaunchKernelGGL((attn_valu_kernel<SCOUT_BF16, 128>), grid, block, 0, st, D, q, k_pool, v_pool,
+                         n_slots, sel_gpu, slot_gpu, n_gpu, P);
+    else if (dtype == SCOUT_BF16 && D.d == 64)
+      hipLaunchKernelGGL((attn_valu_kernel<SCOUT_BF16, 64>), grid, block, 0, st, D, q, k_pool, v_pool,
+                         n_slots, sel_gpu, slot_gpu, n_gpu, P);
+    else if (dtype == SCOUT_F32 && D.d == 128)
+      hipLaunchKernelGGL((attn_valu_kernel<SCOUT_F32, 128>), grid, block, 0, st, D, q, k_pool, v_pool,
+                         n_slots, sel_gpu, slot_gpu, n_gpu, P);
+    else if (dtype == SCOUT_F32 && D.d == 64)
+      hipLaunchKernelGGL((attn_valu_kernel<SCOUT_F32, 64>), grid, block, 0, st, D, q, k_pool, v_pool,
+                         n_slots, sel_gpu, slot_gpu, n_gpu, P);
+    else
+      return SCOUT_EUNSUPPORTED;
+  }
+  return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
+}
+
+int launch_combine(const Dims& D, int dtype_out, Partials P, float* o, float* m, float* l,
+                   const float* host_o, const float* host_m, const float* host_l, void* out,
+                   float* lse, int fuse_merge, hipStream_t st) {
+  dim3 grid(D.B * D.Hq), block(D.d);
+  if (grid.x == 0) return SCOUT_OK;
+  if (dtype_out == SCOUT_BF16)
+    hipLaunchKernelGGL(combine_kernel<SCOUT_BF16>, grid, block, 0, st, D, P, o, m, l, host_o, host_m,
+                       host_l, out, lse, fuse_merge);
+  else
+    hipLaunchKernelGGL(combine_kernel<SCOUT_F32>, grid, block, 0, st, D, P, o, m, l, host_o, host_m,
+                       host_l, out, lse, fuse_merge);
+  return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
+}
+
+int launch_merge(const Dims& D, int dtype_out, const float* o_a, const float* m_a, const float* l_a,
+                 const float* o_b, const float* m_b, const float* l_b, void* out, float* lse,
+                 hipStream_t st) {
+  dim3 grid(D.B * D.Hq), block(D.d);
+  if (grid.x == 0) return SCOUT_OK;
+  if (dtype_out == SCOUT_BF16)
+    hipLaunchKernelGGL(merge_kernel<SCOUT_BF16>, grid, block, 0, st, D, o_a, m_a, l_a, o_b, m_b, l_b, out,
+                       lse);
+  else
+    hipLaunchKernelGGL(merge_kernel<SCOUT_F32>, grid, block, 0, st, D, o_a, m_a, l_a, o_b, m_b, l_b, out,
+                       lse);
+  return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
+}
+
+}  // namespace scout

@@ -1,0 +1,88 @@
+// Shared device helpers for the gfx950 kernels (wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "scout.h"
+
+namespace scout {
+
+constexpr int kWave = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Internal launch parameters derived once on the host from scout_problem.
+struct Dims {
+  int B, Hq, Hkv, G, d, S, max_blocks, k;
+  float sm_scale;
+  const int32_t* ctx_len;
+};
+
+// Per-split partial results in the workspace, per pair and split:
+//   o [pairs][nsplit][G][d]  unnormalised weighted value sums
+//   m [pairs][nsplit][G]     maximum logit in base-2 units
+//   l [pairs][nsplit][G]     sum of 2^(logit - m)
+struct Partials {
+  float* o;
+  float* m;
+  float* l;
+  int nsplit;
+};
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t hi16) {
+  return __uint_as_float(hi16 << 16);
+}
+// low / high half of a dword that packs two bf16 values
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// binary32 -> bf16 bits, round to nearest even (finite inputs; NaN stays NaN)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float x) {
+  uint32_t u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
+
+__device__ __forceinline__ int num_blocks_of(const Dims& D, int b) {
+  int ctx = D.ctx_len[b];
+  if (ctx < 0) ctx = 0;
+  int nb = (ctx + D.S - 1) / D.S;
+  return nb < D.max_blocks ? nb : D.max_blocks;
+}
+
+// number of lanes below this one whose bit is set in a 64-bit wave mask
+__device__ __forceinline__ int mbcnt64(uint64_t mask) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                   __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
+}
+
+// Load 8 consecutive elements of storage type as binary32.
+template <int DT>
+__device__ __forceinline__ void load8(const void* base, size_t elem_off, float (&x)[8]);
+
+template <>
+__device__ __forceinline__ void load8<SCOUT_BF16>(const void* base, size_t elem_off, float (&x)[8]) {
+  const uint4 w = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(base) + elem_off);
+  x[0] = bf16_lo(w.x); x[1] = bf16_hi(w.x);
+  x[2] = bf16_lo(w.y); x[3] = bf16_hi(w.y);
+  x[4] = bf16_lo(w.z); x[5] = bf16_hi(w.z);
+  x[6] = bf16_lo(w.w); x[7] = bf16_hi(w.w);
+}
+template <>
+__device__ __forceinline__ void load8<SCOUT_F32>(const void* base, size_t elem_off, float (&x)[8]) {
+  const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(base) + elem_off);
+  const float4 a = p[0], b = p[1];
+  x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+  x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+
+template <int DT>
+__device__ __forceinline__ float load1(const void* base, size_t elem_off) {
+  if (DT == SCOUT_BF16) return bf16_bits_to_f32(static_cast<const uint16_t*>(base)[elem_off]);
+  return static_cast<const float*>(base)[elem_off];
+}
+
+}  // namespace scout

@@ -1,0 +1,104 @@
+"""The C-ABI library loads, exports every declared symbol and rejects bad arguments on the host.
+
+Runs without a GPU: every call here must fail validation before anything is launched
+(pointers are fake, never dereferenced).
+"""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2603_27138_amd import build
+    if not os.path.exists(build.LIB):
+        build.build()
+    from paper_2603_27138_amd import binding
+    return binding
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "scout.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(?:int|const char\*)\s+(\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    syms = declared_symbols()
+    assert {"score_blocks", "select_topk", "sparse_decode_attn", "merge_partials", "periodic_recall"} <= set(syms)
+    L = lib.lib()
+    for s in syms:
+        assert hasattr(L, s), s
+    assert sorted(lib.EXPORTS) == syms
+    assert L.scout_version() >= 100
+    assert L.scout_strerror(-1) == b"invalid argument"
+
+
+def _problem(lib, **kw):
+    base = dict(B=2, Hq=8, Hkv=2, d=128, S=32, dtype=lib.BF16, max_blocks=64, k=8, sm_scale=0.0, ctx_len=0x1000)
+    base.update(kw)
+    return lib.Problem(**base)
+
+
+FAKE = ctypes.c_void_p(0x10000)   # 16-byte aligned, never dereferenced
+
+
+def test_workspace_bytes(lib):
+    n = ctypes.c_size_t(0)
+    assert lib.lib().scout_workspace_bytes(ctypes.byref(_problem(lib)), ctypes.byref(n)) == 0
+    assert n.value > 0 and n.value % 256 == 0
+    assert lib.lib().scout_workspace_bytes(None, ctypes.byref(n)) == lib.EINVAL
+    assert lib.lib().scout_workspace_bytes(ctypes.byref(_problem(lib)), None) == lib.EINVAL
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(Hq=7), -1), (dict(Hkv=0), -1), (dict(B=-1), -1), (dict(k=0), -1), (dict(max_blocks=0), -1),
+    (dict(dtype=5), -1), (dict(sm_scale=-1.0), -1), (dict(ctx_len=None), -1),
+    (dict(d=96), -2), (dict(S=8), -2), (dict(Hq=64, Hkv=2), -2), (dict(k=5000), -2), (dict(max_blocks=1 << 20), -2),
+])
+def test_bad_problem_is_rejected_before_launch(lib, kw, code):
+    p = _problem(lib, **kw)
+    L = lib.lib()
+    assert L.score_blocks(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == code
+    assert L.merge_partials(ctypes.byref(p), FAKE, FAKE, FAKE, None, None, None, FAKE, None, None) == code
+    assert L.build_digests(ctypes.byref(p), FAKE, FAKE, None) == code
+
+
+def test_null_misaligned_and_workspace_errors(lib):
+    p = _problem(lib)
+    L = lib.lib()
+    odd = ctypes.c_void_p(0x10004)
+    assert L.score_blocks(ctypes.byref(p), None, FAKE, FAKE, FAKE, 1 << 30, None) == lib.EINVAL
+    assert L.score_blocks(ctypes.byref(p), odd, FAKE, FAKE, FAKE, 1 << 30, None) == lib.EINVAL
+    assert L.select_topk(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, FAKE, 1 << 30, None) == lib.EINVAL
+    args = [FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE]
+    assert L.sparse_decode_attn(ctypes.byref(p), *args, None, 0, None) == lib.EWORKSPACE
+    assert L.sparse_decode_attn(ctypes.byref(p), *args, FAKE, 16, None) == lib.EWORKSPACE
+    assert L.sparse_decode_attn(ctypes.byref(p), *args, ctypes.c_void_p(0x10010), 1 << 30, None) == lib.EWORKSPACE
+    args[3] = -1
+    assert L.sparse_decode_attn(ctypes.byref(p), *args, FAKE, 1 << 30, None) == lib.EINVAL
+    # host partial must be given completely or not at all
+    assert L.merge_partials(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, None, None, FAKE, None, None) == lib.EINVAL
+    assert L.periodic_recall(ctypes.byref(p), FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == lib.EINVAL
+    assert L.scout_set_attn_mode(3, 0) == lib.EINVAL and L.scout_set_attn_mode(0, 0) == 0
+    # MFMA family forced on a shape it does not cover
+    p32 = _problem(lib, dtype=lib.F32)
+    assert L.scout_set_attn_mode(2, 0) == 0
+    try:
+        args[3] = 10
+        assert L.sparse_decode_attn(ctypes.byref(p32), *args, FAKE, 1 << 30, None) == lib.EUNSUPPORTED
+    finally:
+        L.scout_set_attn_mode(0, 0)
+
+
+def test_product_package_does_not_touch_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2603_27138_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "scout_oracle" not in text, f
