@@ -37,6 +37,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-family", type=int, default=0)
     ap.add_argument("--nsplit", type=int, default=0)
+    ap.add_argument("--waves", type=int, default=0)
     return ap.parse_args()
 
 
@@ -63,7 +64,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     B.lib()   # fail loudly if the HIP library is missing
-    B.set_attn_mode(args.attn_family, args.nsplit)
+    B.set_attn_mode(args.attn_family, args.nsplit, args.waves)
 
     cfg = W.qwen3_32b(B=args.batch, ctx=args.ctx)
     t0 = time.time()
@@ -153,11 +154,17 @@ def main():
     us_step = timed(step, args.steps)
     t_wall = time.time() - t_wall0
 
-    # per-kernel figures on the same stream, same rotation: the attention split pass alone, the scoring
-    # pass alone (HIP events around `steps` back-to-back launches)
+    # per-kernel figures on the same stream, same rotation: sparse_decode_attn alone (one launch of the
+    # attention kernel per call), the scoring pass alone, the selection alone (HIP events around `steps`
+    # back-to-back launches)
+    part_o = torch.empty(cfg.B, cfg.Hq, cfg.d, **f32)
+    part_m = torch.empty(cfg.B, cfg.Hq, **f32)
+    part_l = torch.empty(cfg.B, cfg.Hq, **f32)
+
     def attn_only(i):
         s, p = sets[i % len(sets)], probs[i % len(sets)]
-        B.attn_partials(p, s.q, s.k_pool, s.v_pool, wl.n_slots, s.sel_gpu, s.slot_gpu, s.n_gpu, ws)
+        B.sparse_decode_attn(p, s.q, s.k_pool, s.v_pool, wl.n_slots, s.sel_gpu, s.slot_gpu, s.n_gpu, part_o,
+                             part_m, part_l, ws)
 
     def score_only(i):
         s, p = sets[i % len(sets)], probs[i % len(sets)]
@@ -205,7 +212,7 @@ def main():
                    "host_resident": cfg.p_host, "layer_copies": len(sets), "gpu_blocks_per_step": n_blocks},
         "kv_gbps": round(attn_gbps, 1),
         "kernels_us": {"score_blocks": round(us_score, 3), "select_topk": round(us_select, 3),
-                       "attn_split_pass": round(us_attn, 3)},
+                       "sparse_decode_attn": round(us_attn, 3)},
         "score_gbps": round(score_gbps, 1),
         "roofline": {"bound": "hbm", "kernel": "attn_mfma_kernel", "achieved": round(attn_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),

@@ -140,17 +140,6 @@ int sparse_decode_attn(const scout_problem* p, const void* q, const void* k_pool
                        float* l, void* ws, size_t ws_bytes, void* stream);
 
 /*
- * First half of sparse_decode_attn on its own: the split-KV pass that streams
- * the K/V tiles and leaves one partial per (pair, split) in the workspace.
- * Same arguments; writes nothing but the workspace.  It exists so that the
- * bandwidth-bound kernel can be timed without the small combine pass behind it.
- */
-int scout_attn_partials(const scout_problem* p, const void* q, const void* k_pool,
-                        const void* v_pool, int64_t n_slots, const int32_t* sel_gpu,
-                        const int32_t* slot_gpu, const int32_t* n_gpu, void* ws, size_t ws_bytes,
-                        void* stream);
-
-/*
  * Merge of two partial results (Alg. 1 Merge; FlashAttention rescaling):
  *   m* = max(m_a, m_b), w_x = l_x exp(m_x - m*), out = (w_a o_a + w_b o_b)/(w_a + w_b),
  *   lse = m* + ln(w_a + w_b).  A side with l = 0 has weight 0.
@@ -194,12 +183,14 @@ int scout_layer_step(const scout_problem* p, const void* q, const void* digest,
                      void* out, float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /*
- * Tuning knob for measurements: force the attention kernel family and split
- * count.  family: 0 = automatic, 1 = generic vector-ALU kernel, 2 = MFMA
- * kernel (bf16, d = 128, S = 32 only; otherwise SCOUT_EUNSUPPORTED at the
- * call).  nsplit: 0 = automatic, else 1..64.  Process-wide, not thread-safe.
+ * Tuning knob for measurements: force the attention kernel family, the split
+ * count per pair and the workgroup size.  family: 0 = automatic, 1 = generic
+ * vector-ALU kernel, 2 = MFMA kernel (bf16, d = 128, S = 32 only; otherwise
+ * SCOUT_EUNSUPPORTED at the call).  nsplit: 0 = automatic, else 1..64.
+ * waves: 0 = automatic, else 4, 8 or 16 waves per workgroup (MFMA family).
+ * Process-wide, not thread-safe.
  */
-int scout_set_attn_mode(int family, int nsplit);
+int scout_set_attn_mode(int family, int nsplit, int waves);
 
 #ifdef __cplusplus
 }

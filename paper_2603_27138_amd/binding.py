@@ -21,7 +21,7 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 
 EXPORTS = ["scout_version", "scout_strerror", "scout_workspace_bytes", "build_digests", "score_blocks",
            "select_topk", "sparse_decode_attn", "merge_partials", "periodic_recall",
-           "scout_layer_step", "scout_set_attn_mode", "scout_attn_partials"]
+           "scout_layer_step", "scout_set_attn_mode"]
 
 
 class ScoutError(RuntimeError):
@@ -54,14 +54,13 @@ def lib():
         L.scout_version.restype = ctypes.c_int
         L.scout_strerror.restype = ctypes.c_char_p
         L.scout_strerror.argtypes = [ctypes.c_int]
-        L.scout_set_attn_mode.argtypes = [ctypes.c_int, ctypes.c_int]
+        L.scout_set_attn_mode.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
         L.scout_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
         L.build_digests.argtypes = [pp, vp, vp, vp]
         L.score_blocks.argtypes = [pp, vp, vp, vp, vp, sz, vp]
         L.select_topk.argtypes = [pp] + [vp] * 9 + [sz, vp]
         L.sparse_decode_attn.argtypes = [pp, vp, vp, vp, i64] + [vp] * 7 + [sz, vp]
         L.merge_partials.argtypes = [pp] + [vp] * 9
-        L.scout_attn_partials.argtypes = [pp, vp, vp, vp, i64] + [vp] * 4 + [sz, vp]
         L.periodic_recall.argtypes = [pp] + [vp] * 8 + [sz, vp]
         L.scout_layer_step.argtypes = [pp, vp, vp, vp, vp, vp, i64] + [vp] * 13 + [sz, vp]
         for name in EXPORTS:
@@ -104,8 +103,8 @@ def version() -> int:
     return lib().scout_version()
 
 
-def set_attn_mode(family: int = 0, nsplit: int = 0):
-    _check("scout_set_attn_mode", lib().scout_set_attn_mode(family, nsplit))
+def set_attn_mode(family: int = 0, nsplit: int = 0, waves: int = 0):
+    _check("scout_set_attn_mode", lib().scout_set_attn_mode(family, nsplit, waves))
 
 
 def workspace_bytes(p: Problem) -> int:
@@ -138,13 +137,6 @@ def sparse_decode_attn(p: Problem, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu
            lib().sparse_decode_attn(ctypes.byref(p), _ptr(q), _ptr(k_pool), _ptr(v_pool), int(n_slots),
                                     _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu), _ptr(o), _ptr(m), _ptr(l),
                                     _ptr(ws), ws.numel(), _stream()))
-
-
-def attn_partials(p: Problem, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, ws):
-    _check("scout_attn_partials",
-           lib().scout_attn_partials(ctypes.byref(p), _ptr(q), _ptr(k_pool), _ptr(v_pool), int(n_slots),
-                                     _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu), _ptr(ws), ws.numel(),
-                                     _stream()))
 
 
 def merge_partials(p: Problem, o_a, m_a, l_a, o_b, m_b, l_b, out, lse=None):

@@ -15,10 +15,9 @@ int launch_topk(const Dims&, const float*, const int32_t*, int32_t*, int32_t*, i
 int launch_recall(const Dims&, const float*, int32_t*, int32_t*, int32_t*, int32_t*, int32_t*,
                   hipStream_t);
 bool mfma_supported(const Dims&, int);
-int launch_attn(const Dims&, int, int, const void*, const void*, const void*, long long,
-                const int32_t*, const int32_t*, const int32_t*, Partials, hipStream_t);
-int launch_combine(const Dims&, int, Partials, float*, float*, float*, const float*, const float*,
-                   const float*, void*, float*, int, hipStream_t);
+int launch_attn(const Dims&, int, int, int, const void*, const void*, const void*, long long,
+                const int32_t*, const int32_t*, const int32_t*, Partials, Epilogue, hipStream_t);
+int launch_combine(const Dims&, Partials, Epilogue, hipStream_t);
 int launch_merge(const Dims&, int, const float*, const float*, const float*, const float*,
                  const float*, const float*, void*, float*, hipStream_t);
 
@@ -28,6 +27,7 @@ constexpr int kMfmaWavesPerWg = 4;
 
 static int g_family = 0;  // 0 auto, 1 vector ALU, 2 MFMA
 static int g_nsplit = 0;  // 0 auto
+static int g_waves = 0;   // 0 auto; MFMA family only
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -85,35 +85,70 @@ static int check_ws(const Dims& D, void* ws, size_t ws_bytes, WsLayout* L) {
   return SCOUT_OK;
 }
 
-// which attention kernel family and how many splits per pair
-static int plan_attn(const Dims& D, int dtype, int* family, int* nsplit) {
+// Which attention kernel family, how many splits per pair, how many waves per workgroup.
+struct AttnPlan {
+  int family, nsplit, waves;
+};
+
+static int plan_attn(const Dims& D, int dtype, AttnPlan* out) {
   int fam = g_family;
   if (fam == 0) fam = mfma_supported(D, dtype) ? 2 : 1;
   if (fam == 2 && !mfma_supported(D, dtype)) return SCOUT_EUNSUPPORTED;
   const long long pairs = (long long)D.B * D.Hkv;
-  int ns = g_nsplit;
-  if (ns == 0) {
-    // aim at about 16 waves on each of the 256 compute units
-    const long long target_waves = 256 * 16;
-    const long long waves_per_split =
-        fam == 2 ? kMfmaWavesPerWg : (D.G + kValuHeadsPerWave - 1) / kValuHeadsPerWave;
-    long long want = (target_waves + pairs * waves_per_split - 1) / (pairs > 0 ? pairs * waves_per_split : 1);
-    const int blocks_per_split_unit = fam == 2 ? kMfmaWavesPerWg : 1;
-    const long long cap = (D.k + blocks_per_split_unit - 1) / blocks_per_split_unit;
-    if (want > cap) want = cap;
-    if (want < 1) want = 1;
-    ns = (int)want;
+  int ns = g_nsplit, waves = 1;
+  if (fam == 2) {
+    // Eight waves per workgroup, two tiles in flight per wave.  With at least ~100 pairs one
+    // workgroup per pair keeps enough tiles in flight and finishes the pair without a second pass;
+    // with fewer pairs the block list is split over several workgroups.
+    waves = g_waves ? g_waves : 8;
+    if (ns == 0) {
+      if (pairs >= 96) {
+        ns = 1;
+      } else {
+        long long want = (256 + pairs - 1) / (pairs > 0 ? pairs : 1);
+        const long long cap = (D.k + waves - 1) / waves;
+        ns = (int)(want > cap ? cap : want);
+      }
+    }
+  } else if (ns == 0) {
+    const long long chunks = (D.G + kValuHeadsPerWave - 1) / kValuHeadsPerWave;
+    long long want = (4096 + pairs * chunks - 1) / (pairs > 0 ? pairs * chunks : 1);
+    ns = (int)(want > D.k ? D.k : want);
   }
-  if (ns < 1 || ns > kMaxSplit) ns = ns < 1 ? 1 : kMaxSplit;
-  *family = fam;
-  *nsplit = ns;
+  if (ns < 1) ns = 1;
+  if (ns > kMaxSplit) ns = kMaxSplit;
+  out->family = fam;
+  out->nsplit = ns;
+  out->waves = waves;
   return SCOUT_OK;
 }
+
+// Attention over the listed blocks, then what E asks for.  One launch when a single MFMA workgroup
+// covers a pair, otherwise the split pass followed by the combine pass.
+static int run_attn(const Dims& D, int dtype, const AttnPlan& A, const void* q, const void* k_pool,
+                    const void* v_pool, long long n_slots, const int32_t* sel_gpu,
+                    const int32_t* slot_gpu, const int32_t* n_gpu, void* ws, const WsLayout& L,
+                    Epilogue E, hipStream_t st);
 
 static Partials carve(void* ws, const WsLayout& L, int nsplit) {
   char* base = static_cast<char*>(ws);
   return Partials{reinterpret_cast<float*>(base + L.part_o), reinterpret_cast<float*>(base + L.part_m),
                   reinterpret_cast<float*>(base + L.part_l), nsplit};
+}
+
+static int run_attn(const Dims& D, int dtype, const AttnPlan& A, const void* q, const void* k_pool,
+                    const void* v_pool, long long n_slots, const int32_t* sel_gpu,
+                    const int32_t* slot_gpu, const int32_t* n_gpu, void* ws, const WsLayout& L,
+                    Epilogue E, hipStream_t st) {
+  Partials P = carve(ws, L, A.nsplit);
+  if (A.family == 2 && A.nsplit == 1)  // one workgroup per pair finishes the pair itself
+    return launch_attn(D, dtype, 2, A.waves, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, P, E, st);
+  Epilogue part{};
+  part.mode = 0;
+  int rc = launch_attn(D, dtype, A.family, A.waves, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, P,
+                       part, st);
+  if (rc != SCOUT_OK) return rc;
+  return launch_combine(D, P, E, st);
 }
 
 }  // namespace scout
@@ -135,10 +170,12 @@ const char* scout_strerror(int code) {
   }
 }
 
-int scout_set_attn_mode(int family, int nsplit) {
+int scout_set_attn_mode(int family, int nsplit, int waves) {
   if (family < 0 || family > 2 || nsplit < 0 || nsplit > kMaxSplit) return SCOUT_EINVAL;
+  if (waves != 0 && waves != 4 && waves != 8 && waves != 16) return SCOUT_EINVAL;
   g_family = family;
   g_nsplit = nsplit;
+  g_waves = waves;
   return SCOUT_OK;
 }
 
@@ -192,25 +229,6 @@ int select_topk(const scout_problem* p, const float* scores, const int32_t* bloc
                      static_cast<hipStream_t>(stream));
 }
 
-int scout_attn_partials(const scout_problem* p, const void* q, const void* k_pool, const void* v_pool,
-                        int64_t n_slots, const int32_t* sel_gpu, const int32_t* slot_gpu,
-                        const int32_t* n_gpu, void* ws, size_t ws_bytes, void* stream) {
-  Dims D;
-  int rc = check_problem(p, &D);
-  if (rc != SCOUT_OK) return rc;
-  if (!q || !sel_gpu || !slot_gpu || !n_gpu || n_slots < 0) return SCOUT_EINVAL;
-  if (n_slots > 0 && (!k_pool || !v_pool)) return SCOUT_EINVAL;
-  if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool)) return SCOUT_EINVAL;
-  WsLayout L;
-  rc = check_ws(D, ws, ws_bytes, &L);
-  if (rc != SCOUT_OK) return rc;
-  int family, nsplit;
-  rc = plan_attn(D, p->dtype, &family, &nsplit);
-  if (rc != SCOUT_OK) return rc;
-  return launch_attn(D, p->dtype, family, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu,
-                     carve(ws, L, nsplit), static_cast<hipStream_t>(stream));
-}
-
 int sparse_decode_attn(const scout_problem* p, const void* q, const void* k_pool, const void* v_pool,
                        int64_t n_slots, const int32_t* sel_gpu, const int32_t* slot_gpu,
                        const int32_t* n_gpu, float* o, float* m, float* l, void* ws, size_t ws_bytes,
@@ -224,14 +242,16 @@ int sparse_decode_attn(const scout_problem* p, const void* q, const void* k_pool
   WsLayout L;
   rc = check_ws(D, ws, ws_bytes, &L);
   if (rc != SCOUT_OK) return rc;
-  int family, nsplit;
-  rc = plan_attn(D, p->dtype, &family, &nsplit);
+  AttnPlan A;
+  rc = plan_attn(D, p->dtype, &A);
   if (rc != SCOUT_OK) return rc;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  Partials P = carve(ws, L, nsplit);
-  rc = launch_attn(D, p->dtype, family, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, P, st);
-  if (rc != SCOUT_OK) return rc;
-  return launch_combine(D, p->dtype, P, o, m, l, nullptr, nullptr, nullptr, nullptr, nullptr, 0, st);
+  Epilogue E{};
+  E.mode = 1;
+  E.o = o;
+  E.m = m;
+  E.l = l;
+  return run_attn(D, p->dtype, A, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, ws, L, E,
+                  static_cast<hipStream_t>(stream));
 }
 
 int merge_partials(const scout_problem* p, const float* o_a, const float* m_a, const float* l_a,
@@ -286,18 +306,23 @@ int scout_layer_step(const scout_problem* p, const void* q, const void* digest,
   WsLayout L;
   rc = check_ws(D, ws, ws_bytes, &L);
   if (rc != SCOUT_OK) return rc;
-  int family, nsplit;
-  rc = plan_attn(D, p->dtype, &family, &nsplit);
+  AttnPlan A;
+  rc = plan_attn(D, p->dtype, &A);
   if (rc != SCOUT_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   rc = launch_score(D, p->dtype, q, digest, scores, st);
   if (rc != SCOUT_OK) return rc;
   rc = launch_topk(D, scores, block_table, sel_all, sel_gpu, slot_gpu, n_gpu, sel_host, n_host, st);
   if (rc != SCOUT_OK) return rc;
-  Partials P = carve(ws, L, nsplit);
-  rc = launch_attn(D, p->dtype, family, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, P, st);
-  if (rc != SCOUT_OK) return rc;
-  return launch_combine(D, p->dtype, P, nullptr, nullptr, nullptr, host_o, host_m, host_l, out, lse, 1, st);
+  Epilogue E{};
+  E.mode = 2;
+  E.host_o = host_o;
+  E.host_m = host_m;
+  E.host_l = host_l;
+  E.out = out;
+  E.lse = lse;
+  E.dtype_out = p->dtype;
+  return run_attn(D, p->dtype, A, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, ws, L, E, st);
 }
 
 }  // extern "C"

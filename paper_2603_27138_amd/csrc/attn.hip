@@ -23,9 +23,12 @@
 
 namespace scout {
 
+// bare v_exp_f32: results below 2^-126 flush to zero, which is what a softmax weight wants
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 __device__ __forceinline__ float exp2_diff(float a, float b) {
   // 2^(a-b) with the convention 2^(-inf - anything) = 0
-  return a == -INFINITY ? 0.0f : exp2f(a - b);
+  return a == -INFINITY ? 0.0f : fast_exp2(a - b);
 }
 
 // ---------------------------------------------------------------- MFMA family
@@ -53,6 +56,42 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float x, float y) {
 constexpr int kMfmaD = 128;
 constexpr int kMfmaS = 32;
 
+// acc: unnormalised weighted value sum of channel c, l: weight sum, M2: base-2 maximum
+__device__ __forceinline__ void finish(const Dims& D, const Epilogue& E, int bh, int c, float acc,
+                                       float l, float M2) {
+  const float m_nat = M2 * kLn2;  // -inf stays -inf
+  const float o_norm = l > 0.0f ? acc / l : 0.0f;
+  if (E.mode == 1) {
+    E.o[(size_t)bh * D.d + c] = o_norm;
+    if (c == 0) {
+      E.m[bh] = m_nat;
+      E.l[bh] = l;
+    }
+    return;
+  }
+  float mb = -INFINITY, lb = 0.0f, ob = 0.0f;
+  if (E.host_o != nullptr) {
+    mb = E.host_m[bh];
+    lb = E.host_l[bh];
+    ob = E.host_o[(size_t)bh * D.d + c];
+  }
+  float ms = -INFINITY;
+  if (l > 0.0f) ms = fmaxf(ms, m_nat);
+  if (lb > 0.0f) ms = fmaxf(ms, mb);
+  const float wa = l > 0.0f ? l * expf(m_nat - ms) : 0.0f;
+  const float wb = lb > 0.0f ? lb * expf(mb - ms) : 0.0f;
+  const float ls = wa + wb;
+  float r = 0.0f;
+  if (wa > 0.0f) r += wa * o_norm;
+  if (wb > 0.0f) r += wb * ob;
+  r = ls > 0.0f ? r / ls : 0.0f;
+  if (E.dtype_out == SCOUT_BF16)
+    static_cast<uint16_t*>(E.out)[(size_t)bh * D.d + c] = (uint16_t)f32_to_bf16_bits(r);
+  else
+    static_cast<float*>(E.out)[(size_t)bh * D.d + c] = r;
+  if (E.lse != nullptr && c == 0) E.lse[bh] = ls > 0.0f ? ms + logf(ls) : -INFINITY;
+}
+
 // One wave per (pair, split, wave-in-workgroup) walks over the pair's resident
 // selected blocks i = first, first + stride, ...  For each block:
 //   logits^T[token][head] = K[token][:] . Q[head][:]      8 x mfma 16x16x32
@@ -67,20 +106,145 @@ constexpr int kMfmaS = 32;
 // value rows are loaded in that same token order.  Element r of a lane's 16-byte
 // value chunk feeds product r, whose output row index then means channel
 // 8*row + r.
+//
+// The waves of a workgroup fold their partials through LDS; with one split per
+// pair the workgroup finishes the pair itself (Epilogue modes 1 and 2), so the
+// whole attention is one launch and nothing goes through the workspace.
+// K and V tile of one block in MFMA operand registers (64 VGPRs).
+struct TileRegs {
+  u32x4 k[2][4];  // [token half][contraction step]: row = token 16*jt + ln, group kg
+  u32x4 v[8];     // rows in the token order of this lane's logits, 16-byte chunk ln
+};
+
+// One list entry of a pair, checked: pool slot and number of valid tokens (0 = nothing to read).
+struct Entry {
+  long long slot;
+  int valid;
+};
+
+__device__ __forceinline__ Entry read_entry(const int32_t* __restrict__ sel_gpu,
+                                            const int32_t* __restrict__ slot_gpu, size_t list0, int i,
+                                            int n, int ctx, long long n_slots) {
+  Entry e{0, 0};
+  if (i < n) {  // wave-uniform: scalar loads
+    const int j = sel_gpu[list0 + i];
+    const long long slot = slot_gpu[list0 + i];
+    int valid = ctx - j * kMfmaS;
+    valid = valid > kMfmaS ? kMfmaS : valid;
+    if (j >= 0 && valid > 0 && slot >= 0 && slot < n_slots) {
+      e.slot = slot;
+      e.valid = valid;
+    }
+  }
+  return e;
+}
+
+constexpr int kTileBytes = kMfmaS * kMfmaD * 2;
+
+// Request a tile.  The loads go through a buffer descriptor that covers exactly the tile, or
+// nothing when the entry is void: then every lane gets zeros without touching memory.  That keeps
+// the issue path free of branches, so the compiler can count outstanding loads exactly and a wave
+// can wait for one tile while the next is still in flight.
+__device__ __forceinline__ void issue_tile(TileRegs& T, const uint16_t* __restrict__ k_pool,
+                                           const uint16_t* __restrict__ v_pool, const Entry& e, int ln,
+                                           int kg) {
+  const int bytes = e.valid > 0 ? kTileBytes : 0;
+  const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(k_pool + (size_t)e.slot * (kMfmaS * kMfmaD)), 0, bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(v_pool + (size_t)e.slot * (kMfmaS * kMfmaD)), 0, bytes, 0x00020000);
+  const int koff = ln * 256 + kg * 16;   // row 16*jt + ln, 16-byte chunk 4*s + kg
+  const int voff = kg * 1024 + ln * 16;  // row 16*(e/4) + 4*kg + e%4, chunk ln
+#pragma unroll
+  for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      T.k[jt][s] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(kr, koff + s * 64, jt * 4096, 0));
+#pragma unroll
+  for (int e8 = 0; e8 < 8; ++e8)
+    T.v[e8] = __builtin_bit_cast(
+        u32x4, __builtin_amdgcn_raw_buffer_load_b128(vr, voff + (e8 & 3) * 256, (e8 >> 2) * 4096, 0));
+}
+
+// Online-softmax state of one wave: head ln, channels 8*(4*kg + i) + r in acc[r][i].
+struct WaveState {
+  f32x4 acc[8];
+  float m, l;
+};
+
+// Fold one tile into the wave's state.  `valid` tokens of the tile count (0: the tile is void and
+// leaves the state as it is), so this too runs without a branch.
+__device__ __forceinline__ void consume_tile(WaveState& W, TileRegs& T, const u32x4 (&qreg)[4], int valid,
+                                             float scale2, int kg) {
+  f32x4 st[2];
+#pragma unroll
+  for (int jt = 0; jt < 2; ++jt) {
+    st[jt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      st[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(T.k[jt][s]), as_bf16x8(qreg[s]), st[jt],
+                                                       0, 0, 0);
+  }
+  // st[jt][i] = logit of head ln, token 16*jt + 4*kg + i; tokens beyond `valid` (the tail of a
+  // sequence's last block) are dropped, their value rows zeroed
+  float x[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int tok = 16 * (e >> 2) + 4 * kg + (e & 3);
+    const bool live = tok < valid;
+    x[e] = live ? st[e >> 2][e & 3] * scale2 : -INFINITY;
+    if (valid < kMfmaS && !live) T.v[e] = (u32x4){0, 0, 0, 0};
+  }
+  float bm = x[0];
+#pragma unroll
+  for (int e = 1; e < 8; ++e) bm = fmaxf(bm, x[e]);
+  bm = fmaxf(bm, __shfl_xor(bm, 16));
+  bm = fmaxf(bm, __shfl_xor(bm, 32));
+  const float m_new = fmaxf(W.m, bm);
+  const float m_sub = m_new == -INFINITY ? 0.0f : m_new;  // nothing seen yet: weights are 2^-inf = 0
+  const float alpha = exp2_diff(W.m, m_new);
+  float p[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) p[e] = fast_exp2(x[e] - m_sub);
+  // weights go into the second product as bf16; sum what is actually used
+  u32x4 preg;
+  float psum = 0.0f;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    preg[w] = cvt_pk_bf16(p[2 * w], p[2 * w + 1]);
+    psum += bf16_lo(preg[w]) + bf16_hi(preg[w]);
+  }
+  W.l = W.l * alpha + psum;
+  W.m = m_new;
+#pragma unroll
+  for (int r = 0; r < 8; ++r) W.acc[r] *= alpha;
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    u32x4 a;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) a[w] = pack_halves(T.v[2 * w][r >> 1], T.v[2 * w + 1][r >> 1], r & 1);
+    W.acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(preg), W.acc[r], 0, 0, 0);
+  }
+}
+
 template <int WAVES>
 __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
     Dims D, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_pool,
     const uint16_t* __restrict__ v_pool, long long n_slots, const int32_t* __restrict__ sel_gpu,
-    const int32_t* __restrict__ slot_gpu, const int32_t* __restrict__ n_gpu, Partials P) {
-  // per wave: [G<=16][132] floats of o (padded rows), then m[16], l[16]
+    const int32_t* __restrict__ slot_gpu, const int32_t* __restrict__ n_gpu, Partials P, Epilogue E) {
+  // per wave: [G][132] floats of o (padded rows), then m[16], l[16]
   constexpr int ROW = kMfmaD + 4;
   extern __shared__ float smem[];
   const int pair = blockIdx.y, split = blockIdx.x;
   const int b = pair / D.Hkv, g = pair % D.Hkv;
-  const int lane = lane_id(), wave = threadIdx.x / kWave;
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int ln = lane & 15, kg = lane >> 4;
   const int G = D.G;
+  const int wstride = G * ROW + 32;  // floats of LDS per wave
 
+  const int first = split * WAVES + wave, stride = P.nsplit * WAVES;
+  const size_t list0 = (size_t)pair * D.k;
   int n = n_gpu[pair];
   n = n < 0 ? 0 : (n > D.k ? D.k : n);
   const int ctx = D.ctx_len[b];
@@ -88,109 +252,63 @@ __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
 
   // B operand of the first product: Q^T, column = head ln, zero beyond G
   u32x4 qreg[4];
+  {
+    const int hsafe = ln < G ? ln : G - 1;
+    const uint16_t* qrow = q + ((size_t)b * D.Hq + g * G + hsafe) * kMfmaD + kg * 8;
 #pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    qreg[s] = (u32x4){0, 0, 0, 0};
-    if (ln < G) {
-      const size_t off = ((size_t)b * D.Hq + g * G + ln) * kMfmaD + s * 32 + kg * 8;
-      qreg[s] = *reinterpret_cast<const u32x4*>(q + off);
-    }
+    for (int s = 0; s < 4; ++s) qreg[s] = *reinterpret_cast<const u32x4*>(qrow + s * 32);
+    const uint32_t keep = ln < G ? 0xffffffffu : 0u;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) qreg[s] &= keep;
   }
 
-  f32x4 acc[8];
+  WaveState W;
 #pragma unroll
-  for (int r = 0; r < 8; ++r) acc[r] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY, l_run = 0.0f;
+  for (int r = 0; r < 8; ++r) W.acc[r] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  W.m = -INFINITY;
+  W.l = 0.0f;
 
-  const int first = split * WAVES + wave, stride = P.nsplit * WAVES;
-  for (int i = first; i < n; i += stride) {
-    // the same entry for every lane: keep it in scalar registers
-    const int j = __builtin_amdgcn_readfirstlane(sel_gpu[(size_t)pair * D.k + i]);
-    const long long slot = __builtin_amdgcn_readfirstlane(slot_gpu[(size_t)pair * D.k + i]);
-    int valid = ctx - j * kMfmaS;
-    valid = valid > kMfmaS ? kMfmaS : valid;
-    if (j < 0 || valid <= 0 || slot < 0 || slot >= n_slots) continue;  // wave-uniform
-
-    const uint16_t* kt = k_pool + (size_t)slot * (kMfmaS * kMfmaD);
-    const uint16_t* vt = v_pool + (size_t)slot * (kMfmaS * kMfmaD);
-
-    // K tile: A operand, row = token 16*jt + ln, contraction group kg of step s
-    u32x4 kreg[2][4];
-#pragma unroll
-    for (int jt = 0; jt < 2; ++jt)
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
-        kreg[jt][s] = *reinterpret_cast<const u32x4*>(kt + (16 * jt + ln) * kMfmaD + s * 32 + kg * 8);
-    // V tile: rows in the token order of this lane's logits, 16-byte chunk ln
-    u32x4 vreg[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int tok = 16 * (e >> 2) + 4 * kg + (e & 3);
-      vreg[e] = *reinterpret_cast<const u32x4*>(vt + tok * kMfmaD + ln * 8);
+  if (n_slots <= 0) n = 0;
+  if constexpr (WAVES <= 8) {
+    // Two tiles are kept in flight per wave (the register file allows it at two waves per SIMD):
+    // the loads of tile t+1 are issued before tile t is consumed, so a wave with two tiles has
+    // everything requested up front.
+    TileRegs A, Bt;
+    Entry ea = read_entry(sel_gpu, slot_gpu, list0, first, n, ctx, n_slots);
+    Entry eb = read_entry(sel_gpu, slot_gpu, list0, first + stride, n, ctx, n_slots);
+    issue_tile(A, k_pool, v_pool, ea, ln, kg);
+    issue_tile(Bt, k_pool, v_pool, eb, ln, kg);
+    for (int i = first; i < n; i += 2 * stride) {
+      const Entry na = read_entry(sel_gpu, slot_gpu, list0, i + 2 * stride, n, ctx, n_slots);
+      const Entry nb = read_entry(sel_gpu, slot_gpu, list0, i + 3 * stride, n, ctx, n_slots);
+      consume_tile(W, A, qreg, ea.valid, scale2, kg);
+      ea = na;
+      issue_tile(A, k_pool, v_pool, ea, ln, kg);
+      consume_tile(W, Bt, qreg, eb.valid, scale2, kg);
+      eb = nb;
+      issue_tile(Bt, k_pool, v_pool, eb, ln, kg);
     }
-
-    f32x4 st[2];
-#pragma unroll
-    for (int jt = 0; jt < 2; ++jt) {
-      st[jt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
-        st[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kreg[jt][s]), as_bf16x8(qreg[s]),
-                                                         st[jt], 0, 0, 0);
-    }
-    // st[jt][i] = logit of head ln, token 16*jt + 4*kg + i
-    float x[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) x[e] = st[e >> 2][e & 3] * scale2;
-    if (valid < kMfmaS) {  // partial last block of a sequence: drop the tail rows
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int tok = 16 * (e >> 2) + 4 * kg + (e & 3);
-        if (tok >= valid) {
-          x[e] = -INFINITY;
-          vreg[e] = (u32x4){0, 0, 0, 0};
-        }
-      }
-    }
-    float bm = x[0];
-#pragma unroll
-    for (int e = 1; e < 8; ++e) bm = fmaxf(bm, x[e]);
-    bm = fmaxf(bm, __shfl_xor(bm, 16));
-    bm = fmaxf(bm, __shfl_xor(bm, 32));
-    const float m_new = fmaxf(m_run, bm);  // finite: a listed block has a valid token
-    const float alpha = exp2_diff(m_run, m_new);
-    float p[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) p[e] = exp2f(x[e] - m_new);
-    // weights go into the second product as bf16; sum what is actually used
-    u32x4 preg;
-    float psum = 0.0f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      preg[w] = cvt_pk_bf16(p[2 * w], p[2 * w + 1]);
-      psum += bf16_lo(preg[w]) + bf16_hi(preg[w]);
-    }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-#pragma unroll
-    for (int r = 0; r < 8; ++r) acc[r] *= alpha;
-
-#pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      u32x4 a;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) a[w] = pack_halves(vreg[2 * w][r >> 1], vreg[2 * w + 1][r >> 1], r & 1);
-      acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(preg), acc[r], 0, 0, 0);
+  } else {
+    // Sixteen waves share the register file four to a SIMD: one tile in flight per wave.
+    TileRegs A;
+    Entry ea = read_entry(sel_gpu, slot_gpu, list0, first, n, ctx, n_slots);
+    for (int i = first; i < n; i += stride) {
+      const Entry na = read_entry(sel_gpu, slot_gpu, list0, i + stride, n, ctx, n_slots);
+      issue_tile(A, k_pool, v_pool, ea, ln, kg);
+      consume_tile(W, A, qreg, ea.valid, scale2, kg);
+      ea = na;
     }
   }
+  f32x4(&acc)[8] = W.acc;
+  float m_run = W.m, l_run = W.l;
 
   // lanes kg = 0..3 of a head saw disjoint tokens under a common maximum
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
 
   // fold the waves of the workgroup through LDS
-  float* wo = smem + (size_t)wave * (16 * ROW + 32);
-  float* wm = wo + 16 * ROW;
+  float* wo = smem + (size_t)wave * wstride;
+  float* wm = wo + G * ROW;
   float* wl = wm + 16;
   if (ln < G) {
 #pragma unroll
@@ -211,19 +329,23 @@ __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
     const int h = idx / kMfmaD, c = idx % kMfmaD;
     float M = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < WAVES; ++w) M = fmaxf(M, smem[(size_t)w * (16 * ROW + 32) + 16 * ROW + h]);
+    for (int w = 0; w < WAVES; ++w) M = fmaxf(M, smem[(size_t)w * wstride + G * ROW + h]);
     float o = 0.0f, l = 0.0f;
 #pragma unroll
     for (int w = 0; w < WAVES; ++w) {
-      const float* base = smem + (size_t)w * (16 * ROW + 32);
-      const float f = exp2_diff(base[16 * ROW + h], M);
+      const float* base = smem + (size_t)w * wstride;
+      const float f = exp2_diff(base[G * ROW + h], M);
       o += f * base[h * ROW + c];
-      l += f * base[16 * ROW + 16 + h];
+      l += f * base[G * ROW + 16 + h];
     }
-    P.o[(pbase * G + h) * kMfmaD + c] = o;
-    if (c == 0) {
-      P.m[pbase * G + h] = M;
-      P.l[pbase * G + h] = l;
+    if (E.mode == 0) {
+      P.o[(pbase * G + h) * kMfmaD + c] = o;
+      if (c == 0) {
+        P.m[pbase * G + h] = M;
+        P.l[pbase * G + h] = l;
+      }
+    } else {
+      finish(D, E, b * D.Hq + g * G + h, c, o, l, M);
     }
   }
 }
@@ -346,14 +468,10 @@ __global__ __launch_bounds__(kWave) void attn_valu_kernel(
 
 // ------------------------------------------------------- combine and merge
 
-// Fold the nsplit partials of every (sequence, query head); then either export
-// the GPU partial (o, m, l) or go straight on to the merge with the host's
-// partial and write the final output.  One workgroup of d threads per head.
-template <int DT_OUT>
-__global__ void combine_kernel(Dims D, Partials P, float* __restrict__ o_out, float* __restrict__ m_out,
-                               float* __restrict__ l_out, const float* __restrict__ host_o,
-                               const float* __restrict__ host_m, const float* __restrict__ host_l,
-                               void* __restrict__ out, float* __restrict__ lse, int fuse_merge) {
+// Fold the nsplit partials of every (sequence, query head), then export the GPU
+// partial or go straight on to the merge with the host's partial (Epilogue modes
+// 1 and 2).  One workgroup of d threads per head.
+__global__ void combine_kernel(Dims D, Partials P, Epilogue E) {
   const int bh = blockIdx.x;  // b * Hq + hq
   const int b = bh / D.Hq, hq = bh % D.Hq;
   const int pair = b * D.Hkv + hq / D.G, h = hq % D.G;
@@ -367,37 +485,7 @@ __global__ void combine_kernel(Dims D, Partials P, float* __restrict__ o_out, fl
     acc += f * P.o[((p0 + s) * D.G + h) * D.d + c];
     l += f * P.l[(p0 + s) * D.G + h];
   }
-  const float m_nat = M * kLn2;  // -inf stays -inf
-  const float o_norm = l > 0.0f ? acc / l : 0.0f;
-  if (!fuse_merge) {
-    o_out[(size_t)bh * D.d + c] = o_norm;
-    if (c == 0) {
-      m_out[bh] = m_nat;
-      l_out[bh] = l;
-    }
-    return;
-  }
-  float mb = -INFINITY, lb = 0.0f, ob = 0.0f;
-  if (host_o != nullptr) {
-    mb = host_m[bh];
-    lb = host_l[bh];
-    ob = host_o[(size_t)bh * D.d + c];
-  }
-  float ms = -INFINITY;
-  if (l > 0.0f) ms = fmaxf(ms, m_nat);
-  if (lb > 0.0f) ms = fmaxf(ms, mb);
-  const float wa = l > 0.0f ? l * expf(m_nat - ms) : 0.0f;
-  const float wb = lb > 0.0f ? lb * expf(mb - ms) : 0.0f;
-  const float ls = wa + wb;
-  float r = 0.0f;
-  if (wa > 0.0f) r += wa * o_norm;
-  if (wb > 0.0f) r += wb * ob;
-  r = ls > 0.0f ? r / ls : 0.0f;
-  if (DT_OUT == SCOUT_BF16)
-    static_cast<uint16_t*>(out)[(size_t)bh * D.d + c] = (uint16_t)f32_to_bf16_bits(r);
-  else
-    static_cast<float*>(out)[(size_t)bh * D.d + c] = r;
-  if (lse != nullptr && c == 0) lse[bh] = ls > 0.0f ? ms + logf(ls) : -INFINITY;
+  finish(D, E, bh, c, acc, l, M);
 }
 
 // Stand-alone merge of two partials given in natural-log units (Alg. 1 Merge).
@@ -433,25 +521,40 @@ __global__ void merge_kernel(Dims D, const float* __restrict__ o_a, const float*
 
 // ------------------------------------------------------------ host launchers
 
-constexpr int kMfmaWaves = 4;
-
-size_t mfma_smem_bytes(int waves) { return (size_t)waves * (16 * (kMfmaD + 4) + 32) * sizeof(float); }
-
 bool mfma_supported(const Dims& D, int dtype) {
   return dtype == SCOUT_BF16 && D.d == kMfmaD && D.S == kMfmaS && D.G <= 16;
 }
 
-int launch_attn(const Dims& D, int dtype, int family, const void* q, const void* k_pool,
+size_t mfma_smem_bytes(const Dims& D, int waves) {
+  return (size_t)waves * (D.G * (kMfmaD + 4) + 32) * sizeof(float);
+}
+
+// family 2: MFMA kernel with `waves` waves per workgroup (4, 8 or 16); family 1: vector ALU.
+// E.mode != 0 requires P.nsplit == 1 and family 2 (the workgroup finishes the pair itself).
+int launch_attn(const Dims& D, int dtype, int family, int waves, const void* q, const void* k_pool,
                 const void* v_pool, long long n_slots, const int32_t* sel_gpu,
-                const int32_t* slot_gpu, const int32_t* n_gpu, Partials P, hipStream_t st) {
+                const int32_t* slot_gpu, const int32_t* n_gpu, Partials P, Epilogue E, hipStream_t st) {
   const int pairs = D.B * D.Hkv;
   if (pairs == 0) return SCOUT_OK;
   if (family == 2) {
-    dim3 grid(P.nsplit, pairs), block(kMfmaWaves * kWave);
-    hipLaunchKernelGGL((attn_mfma_kernel<kMfmaWaves>), grid, block, mfma_smem_bytes(kMfmaWaves), st, D,
-                       static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k_pool),
-                       static_cast<const uint16_t*>(v_pool), n_slots, sel_gpu, slot_gpu, n_gpu, P);
+    dim3 grid(P.nsplit, pairs), block(waves * kWave);
+    const size_t lds = mfma_smem_bytes(D, waves);
+    const uint16_t* q16 = static_cast<const uint16_t*>(q);
+    const uint16_t* k16 = static_cast<const uint16_t*>(k_pool);
+    const uint16_t* v16 = static_cast<const uint16_t*>(v_pool);
+    if (waves == 16)
+      hipLaunchKernelGGL((attn_mfma_kernel<16>), grid, block, lds, st, D, q16, k16, v16, n_slots, sel_gpu,
+                         slot_gpu, n_gpu, P, E);
+    else if (waves == 8)
+      hipLaunchKernelGGL((attn_mfma_kernel<8>), grid, block, lds, st, D, q16, k16, v16, n_slots, sel_gpu,
+                         slot_gpu, n_gpu, P, E);
+    else if (waves == 4)
+      hipLaunchKernelGGL((attn_mfma_kernel<4>), grid, block, lds, st, D, q16, k16, v16, n_slots, sel_gpu,
+                         slot_gpu, n_gpu, P, E);
+    else
+      return SCOUT_EINVAL;
   } else {
+    if (E.mode != 0) return SCOUT_EINVAL;
     dim3 grid(P.nsplit, pairs, (D.G + kValuHeads - 1) / kValuHeads), block(kWave);
     if (dtype == SCOUT_BF16 && D.d == 128)
       hipLaunchKernelGGL((attn_valu_kernel<SCOUT_BF16, 128>), grid, block, 0, st, D, q, k_pool, v_pool,
@@ -471,17 +574,10 @@ int launch_attn(const Dims& D, int dtype, int family, const void* q, const void*
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
 }
 
-int launch_combine(const Dims& D, int dtype_out, Partials P, float* o, float* m, float* l,
-                   const float* host_o, const float* host_m, const float* host_l, void* out,
-                   float* lse, int fuse_merge, hipStream_t st) {
+int launch_combine(const Dims& D, Partials P, Epilogue E, hipStream_t st) {
   dim3 grid(D.B * D.Hq), block(D.d);
   if (grid.x == 0) return SCOUT_OK;
-  if (dtype_out == SCOUT_BF16)
-    hipLaunchKernelGGL(combine_kernel<SCOUT_BF16>, grid, block, 0, st, D, P, o, m, l, host_o, host_m,
-                       host_l, out, lse, fuse_merge);
-  else
-    hipLaunchKernelGGL(combine_kernel<SCOUT_F32>, grid, block, 0, st, D, P, o, m, l, host_o, host_m,
-                       host_l, out, lse, fuse_merge);
+  hipLaunchKernelGGL(combine_kernel, grid, block, 0, st, D, P, E);
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
 }
 

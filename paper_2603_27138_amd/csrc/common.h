@@ -29,6 +29,23 @@ struct Partials {
   int nsplit;
 };
 
+// What happens to a finished (sequence, query head) result.
+//   mode 0: the workgroup's partial goes to the workspace (several splits per pair)
+//   mode 1: export the GPU partial (o, m, l), m in natural-log units
+//   mode 2: merge with the host's partial (Alg. 1 Merge) and write the final output
+struct Epilogue {
+  int mode;
+  float* o;
+  float* m;
+  float* l;
+  const float* host_o;
+  const float* host_m;
+  const float* host_l;
+  void* out;
+  float* lse;
+  int dtype_out;
+};
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t hi16) {
   return __uint_as_float(hi16 << 16);
 }

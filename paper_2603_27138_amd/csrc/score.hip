@@ -71,93 +71,147 @@ __global__ __launch_bounds__(256) void digest_kernel(Dims D, const void* __restr
 
 // ------------------------------------------------------------------- score
 
-constexpr int kScoreBlocksPerWave = 16;
-constexpr int kScoreWaves = 4;
-constexpr int kScoreBlocksPerWg = kScoreBlocksPerWave * kScoreWaves;
+constexpr int kScoreWaves = 4;      // waves per workgroup
+constexpr int kScoreBatch = 8;      // wave-wide loads per batch
+constexpr int kScoreBatches = 4;    // batches per wave
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 // One digest entry (min row + max row = 2*DH elements) is spread over LPB
 // consecutive lanes, 16 bytes per lane, so that each wave-wide load reads one
-// contiguous kilobyte of the digest cache.
+// contiguous kilobyte of the digest cache.  A wave walks over kScoreBatches
+// batches of kScoreBatch such loads and keeps two batches in flight.  The loads
+// go through a buffer descriptor that ends at the pair's last valid block:
+// blocks beyond it read as zero without touching memory, so the issue path has
+// no branches.  Per batch every lane ends up with kScoreBatch partial sums (one
+// per load) that still have to be added across the LPB lanes of an entry; the
+// first three reduction steps exchange half of the remaining sums each, so the
+// batch needs 4+2+1 exchanges plus log2(LPB)-3 plain ones instead of
+// kScoreBatch*log2(LPB).
 template <int DT, int DH>
-__global__ __launch_bounds__(kScoreWaves * kWave) void score_kernel(
+__global__ __launch_bounds__(kScoreWaves* kWave) void score_kernel(
     Dims D, const void* __restrict__ q, const void* __restrict__ digest, float* __restrict__ scores) {
   constexpr int EPL = (DT == SCOUT_BF16) ? 8 : 4;  // elements per 16-byte load
+  constexpr int ESZ = (DT == SCOUT_BF16) ? 2 : 4;
   constexpr int LPB = 2 * DH / EPL;                // lanes per block
   constexpr int BPW = kWave / LPB;                 // blocks per wave-wide load
-  constexpr int ITERS = kScoreBlocksPerWave / BPW;
-  static_assert(LPB <= kWave && ITERS >= 1, "layout");
+  constexpr int BLK_PER_WAVE = BPW * kScoreBatch * kScoreBatches;
+  static_assert(LPB >= 8 && LPB <= kWave, "layout");
 
   const int pair = blockIdx.y;
   const int b = pair / D.Hkv, g = pair % D.Hkv;
-  const int lane = lane_id(), wave = threadIdx.x / kWave;
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int nb = num_blocks_of(D, b);
-  const int j_wave = blockIdx.x * kScoreBlocksPerWg + wave * kScoreBlocksPerWave;
+  const int j_wave = (blockIdx.x * kScoreWaves + wave) * BLK_PER_WAVE;
   if (j_wave >= D.max_blocks) return;
 
-  const int sub = lane % LPB;          // position inside the digest entry
-  const int e0 = sub * EPL;            // first element: [0, DH) min row, [DH, 2DH) max row
+  const int sub = lane % LPB;  // position inside the digest entry
+  const int grp = lane / LPB;  // which of the BPW blocks of a load
+  const int e0 = sub * EPL;    // first element: [0, DH) min row, [DH, 2DH) max row
   const bool is_max = e0 >= DH;
   const int c0 = e0 % DH;
 
-  // issue the digest loads first, fold the query group while they are in flight
-  uint4 raw[ITERS];
-  const char* dbase = static_cast<const char*>(digest);
-  constexpr size_t ESZ = (DT == SCOUT_BF16) ? 2 : 4;
+  // the group's queries first, so that they arrive before the digest stream
+  u32x4 qraw[16];
+  const char* qbase = static_cast<const char*>(q) + (((size_t)b * D.Hq + g * D.G) * DH + c0) * ESZ;
 #pragma unroll
-  for (int it = 0; it < ITERS; ++it) {
-    const int j = j_wave + it * BPW + lane / LPB;
-    raw[it] = make_uint4(0, 0, 0, 0);
-    if (j < nb) {
-      const size_t off = (((size_t)pair * D.max_blocks + j) * 2 * DH + e0) * ESZ;
-      raw[it] = *reinterpret_cast<const uint4*>(dbase + off);
-    }
+  for (int h = 0; h < 16; ++h) {  // rows beyond the group re-read its last row and are ignored below
+    const int hs = h < D.G ? h : D.G - 1;
+    qraw[h] = *reinterpret_cast<const u32x4*>(qbase + (size_t)hs * DH * ESZ);
   }
 
+  const char* dpair = static_cast<const char*>(digest) + (size_t)pair * D.max_blocks * 2 * DH * ESZ;
+  const __amdgpu_buffer_rsrc_t rs =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(dpair), 0, nb * 2 * DH * ESZ, 0x00020000);
+  const int voff0 = ((j_wave + grp) * 2 * DH + e0) * ESZ;
+  constexpr int LOAD_STRIDE = BPW * 2 * DH * ESZ;  // bytes between consecutive loads of a wave (1 KiB)
+
+  u32x4 raw[2][kScoreBatch];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int it = 0; it < kScoreBatch; ++it)
+      raw[t][it] = __builtin_bit_cast(
+          u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff0 + (t * kScoreBatch + it) * LOAD_STRIDE, 0, 0));
+
+  // fold the query group: P_c = sum of positive parts (pairs with the max row),
+  // N_c = sum of negative parts (pairs with the min row)
   double coef[EPL];
 #pragma unroll
   for (int i = 0; i < EPL; ++i) coef[i] = 0.0;
-  for (int h = 0; h < D.G; ++h) {
-    const size_t qoff = (((size_t)b * D.Hq + g * D.G + h) * DH + c0) * ESZ;
-    const uint4 w = *reinterpret_cast<const uint4*>(static_cast<const char*>(q) + qoff);
+#pragma unroll
+  for (int h = 0; h < 16; ++h) {
     float qv[8];
     if (DT == SCOUT_BF16) {
-      qv[0] = bf16_lo(w.x); qv[1] = bf16_hi(w.x); qv[2] = bf16_lo(w.y); qv[3] = bf16_hi(w.y);
-      qv[4] = bf16_lo(w.z); qv[5] = bf16_hi(w.z); qv[6] = bf16_lo(w.w); qv[7] = bf16_hi(w.w);
+      qv[0] = bf16_lo(qraw[h][0]); qv[1] = bf16_hi(qraw[h][0]); qv[2] = bf16_lo(qraw[h][1]); qv[3] = bf16_hi(qraw[h][1]);
+      qv[4] = bf16_lo(qraw[h][2]); qv[5] = bf16_hi(qraw[h][2]); qv[6] = bf16_lo(qraw[h][3]); qv[7] = bf16_hi(qraw[h][3]);
     } else {
-      qv[0] = __uint_as_float(w.x); qv[1] = __uint_as_float(w.y);
-      qv[2] = __uint_as_float(w.z); qv[3] = __uint_as_float(w.w);
+      qv[0] = __uint_as_float(qraw[h][0]); qv[1] = __uint_as_float(qraw[h][1]);
+      qv[2] = __uint_as_float(qraw[h][2]); qv[3] = __uint_as_float(qraw[h][3]);
       qv[4] = qv[5] = qv[6] = qv[7] = 0.0f;
     }
+    if (h < D.G) {
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) {
-      const float part = is_max ? fmaxf(qv[i], 0.0f) : fminf(qv[i], 0.0f);
-      coef[i] += (double)part;
+      for (int i = 0; i < EPL; ++i) coef[i] += (double)(is_max ? fmaxf(qv[i], 0.0f) : fminf(qv[i], 0.0f));
     }
   }
 
+  const bool hiA = (sub & (LPB / 2)) != 0, hiB = (sub & (LPB / 4)) != 0, hiC = (sub & (LPB / 8)) != 0;
+  const int my_it = (hiA ? 4 : 0) + (hiB ? 2 : 0) + (hiC ? 1 : 0);
+  const bool writer = (sub & (LPB / 8 - 1)) == 0;
+
 #pragma unroll
-  for (int it = 0; it < ITERS; ++it) {
-    const int j = j_wave + it * BPW + lane / LPB;
-    double acc = 0.0;
-    if (DT == SCOUT_BF16) {
-      acc = fma(coef[0], (double)bf16_lo(raw[it].x), acc);
-      acc = fma(coef[1], (double)bf16_hi(raw[it].x), acc);
-      acc = fma(coef[2 % EPL], (double)bf16_lo(raw[it].y), acc);
-      acc = fma(coef[3 % EPL], (double)bf16_hi(raw[it].y), acc);
-      acc = fma(coef[4 % EPL], (double)bf16_lo(raw[it].z), acc);
-      acc = fma(coef[5 % EPL], (double)bf16_hi(raw[it].z), acc);
-      acc = fma(coef[6 % EPL], (double)bf16_lo(raw[it].w), acc);
-      acc = fma(coef[7 % EPL], (double)bf16_hi(raw[it].w), acc);
-    } else {
-      acc = fma(coef[0], (double)__uint_as_float(raw[it].x), acc);
-      acc = fma(coef[1], (double)__uint_as_float(raw[it].y), acc);
-      acc = fma(coef[2], (double)__uint_as_float(raw[it].z), acc);
-      acc = fma(coef[3], (double)__uint_as_float(raw[it].w), acc);
+  for (int t = 0; t < kScoreBatches; ++t) {
+    u32x4(&cur)[kScoreBatch] = raw[t & 1];
+    double a[kScoreBatch];
+#pragma unroll
+    for (int it = 0; it < kScoreBatch; ++it) {
+      double acc = 0.0;
+      if (DT == SCOUT_BF16) {
+        acc = fma(coef[0], (double)bf16_lo(cur[it][0]), acc);
+        acc = fma(coef[1], (double)bf16_hi(cur[it][0]), acc);
+        acc = fma(coef[2 % EPL], (double)bf16_lo(cur[it][1]), acc);
+        acc = fma(coef[3 % EPL], (double)bf16_hi(cur[it][1]), acc);
+        acc = fma(coef[4 % EPL], (double)bf16_lo(cur[it][2]), acc);
+        acc = fma(coef[5 % EPL], (double)bf16_hi(cur[it][2]), acc);
+        acc = fma(coef[6 % EPL], (double)bf16_lo(cur[it][3]), acc);
+        acc = fma(coef[7 % EPL], (double)bf16_hi(cur[it][3]), acc);
+      } else {
+        acc = fma(coef[0], (double)__uint_as_float(cur[it][0]), acc);
+        acc = fma(coef[1], (double)__uint_as_float(cur[it][1]), acc);
+        acc = fma(coef[2], (double)__uint_as_float(cur[it][2]), acc);
+        acc = fma(coef[3], (double)__uint_as_float(cur[it][3]), acc);
+      }
+      a[it] = acc;
+    }
+    // the batch after next takes over this buffer
+    if (t + 2 < kScoreBatches) {
+#pragma unroll
+      for (int it = 0; it < kScoreBatch; ++it)
+        cur[it] = __builtin_bit_cast(
+            u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff0 + ((t + 2) * kScoreBatch + it) * LOAD_STRIDE, 0, 0));
+    }
+    // exchange-and-halve reduction across the LPB lanes of an entry
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const double keep = hiA ? a[i + 4] : a[i], send = hiA ? a[i] : a[i + 4];
+      a[i] = keep + __shfl_xor(send, LPB / 2);
     }
 #pragma unroll
-    for (int off = 1; off < LPB; off <<= 1) acc += __shfl_xor(acc, off);
-    if (sub == 0 && j < D.max_blocks)
-      scores[(size_t)pair * D.max_blocks + j] = j < nb ? (float)acc : -INFINITY;
+    for (int i = 0; i < 2; ++i) {
+      const double keep = hiB ? a[i + 2] : a[i], send = hiB ? a[i] : a[i + 2];
+      a[i] = keep + __shfl_xor(send, LPB / 4);
+    }
+    {
+      const double keep = hiC ? a[1] : a[0], send = hiC ? a[0] : a[1];
+      a[0] = keep + __shfl_xor(send, LPB / 8);
+    }
+#pragma unroll
+    for (int off = LPB / 16; off >= 1; off >>= 1) a[0] += __shfl_xor(a[0], off);
+    // a[0]: score of the block that load my_it of this batch brought to this lane group
+    const int j = j_wave + (t * kScoreBatch + my_it) * BPW + grp;
+    if (writer && j < D.max_blocks) scores[(size_t)pair * D.max_blocks + j] = j < nb ? (float)a[0] : -INFINITY;
   }
 }
 
@@ -177,7 +231,9 @@ int launch_digest(const Dims& D, int dtype, const void* k_blocks, void* digest, 
 
 int launch_score(const Dims& D, int dtype, const void* q, const void* digest, float* scores,
                  hipStream_t st) {
-  dim3 grid((D.max_blocks + kScoreBlocksPerWg - 1) / kScoreBlocksPerWg, D.B * D.Hkv);
+  const int epl = dtype == SCOUT_BF16 ? 8 : 4;
+  const int blocks_per_wg = (kWave / (2 * D.d / epl)) * kScoreBatch * kScoreBatches * kScoreWaves;
+  dim3 grid((D.max_blocks + blocks_per_wg - 1) / blocks_per_wg, D.B * D.Hkv);
   dim3 block(kScoreWaves * kWave);
   if (grid.x == 0 || grid.y == 0) return SCOUT_OK;
   if (dtype == SCOUT_BF16 && D.d == 128)

@@ -125,13 +125,26 @@ struct Selector {
   }
 };
 
+// Keys and table entries of a pair.  Every load is issued unconditionally (the index is clamped
+// into the row, the value masked afterwards) so that all of them are in flight together.
 template <int WAVES, int KPL>
-__device__ __forceinline__ void load_keys(const Dims& D, const float* scores, int pair, int nb,
-                                          int wave, int lane, uint32_t (&key)[KPL]) {
+__device__ __forceinline__ void load_keys(const Dims& D, const float* __restrict__ scores,
+                                          const int32_t* __restrict__ table, int pair, int nb, int wave,
+                                          int lane, uint32_t (&key)[KPL], int (&slot)[KPL]) {
+  const size_t row = (size_t)pair * D.max_blocks;
+  float sc[KPL];
 #pragma unroll
   for (int r = 0; r < KPL; ++r) {
     const int i = (wave * KPL + r) * kWave + lane;
-    key[r] = i < nb ? score_key(scores[(size_t)pair * D.max_blocks + i]) : 0u;
+    const int ic = i < D.max_blocks ? i : D.max_blocks - 1;
+    sc[r] = scores[row + ic];
+    slot[r] = table[row + ic];
+  }
+#pragma unroll
+  for (int r = 0; r < KPL; ++r) {
+    const int i = (wave * KPL + r) * kWave + lane;
+    key[r] = i < nb ? score_key(sc[r]) : 0u;
+    slot[r] = i < nb ? slot[r] : -1;
   }
 }
 
@@ -142,28 +155,22 @@ __global__ __launch_bounds__(WAVES* kWave) void topk_kernel(
     int32_t* __restrict__ n_gpu, int32_t* __restrict__ sel_host, int32_t* __restrict__ n_host) {
   __shared__ int lds[2 * WAVES];
   const int pair = blockIdx.x, b = pair / D.Hkv;
-  const int lane = lane_id(), wave = threadIdx.x / kWave;
+  const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int nb = num_blocks_of(D, b);
   const int k_eff = D.k < nb ? D.k : nb;
 
   uint32_t key[KPL];
-  load_keys<WAVES, KPL>(D, scores, pair, nb, wave, lane, key);
+  int slot[KPL];
+  load_keys<WAVES, KPL>(D, scores, table, pair, nb, wave, lane, key, slot);
   Selector<WAVES, KPL> S{lds, 0, wave};
 
   uint32_t sel = 0;
   if (k_eff > 0) sel = S.best(key, k_eff, false);
 
   uint32_t gpu = 0;
-  int slot[KPL];
 #pragma unroll
-  for (int r = 0; r < KPL; ++r) {
-    slot[r] = -1;
-    if ((sel >> r) & 1u) {
-      const int i = (wave * KPL + r) * kWave + lane;
-      slot[r] = table[(size_t)pair * D.max_blocks + i];
-      if (slot[r] >= 0) gpu |= 1u << r;
-    }
-  }
+  for (int r = 0; r < KPL; ++r)
+    if (((sel >> r) & 1u) && slot[r] >= 0) gpu |= 1u << r;
   int pos_all[KPL], pos_gpu[KPL];
   S.positions(sel, pos_all);
   const int ng = S.positions(gpu, pos_gpu);
@@ -206,25 +213,22 @@ __global__ __launch_bounds__(WAVES* kWave) void recall_kernel(
   __shared__ int lds[2 * WAVES];
   __shared__ int freed[kMaxK];  // slots of the evicted blocks, in ascending block order
   const int pair = blockIdx.x, b = pair / D.Hkv;
-  const int lane = lane_id(), wave = threadIdx.x / kWave;
+  const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int nb = num_blocks_of(D, b);
   const int k_eff = D.k < nb ? D.k : nb;
 
   uint32_t key[KPL];
-  load_keys<WAVES, KPL>(D, scores, pair, nb, wave, lane, key);
+  int slot[KPL];
+  load_keys<WAVES, KPL>(D, scores, table, pair, nb, wave, lane, key, slot);
   Selector<WAVES, KPL> S{lds, 0, wave};
 
   uint32_t top = 0;
   if (k_eff > 0) top = S.best(key, k_eff, false);
 
   uint32_t res = 0;
-  int slot[KPL];
 #pragma unroll
-  for (int r = 0; r < KPL; ++r) {
-    const int i = (wave * KPL + r) * kWave + lane;
-    slot[r] = i < nb ? table[(size_t)pair * D.max_blocks + i] : -1;
+  for (int r = 0; r < KPL; ++r)
     if (slot[r] >= 0) res |= 1u << r;
-  }
   const uint32_t missing = top & ~res;  // important now, but in host memory
   const uint32_t spare = res & ~top;    // resident, not in the current top-k
   const int n_missing = S.count(missing);

@@ -156,21 +156,22 @@ def test_sparse_decode_attn(cfg, family):
     wl, res, dev = setup(cfg)
     if family == 2 and not (cfg.dtype == "bf16" and cfg.d == 128 and cfg.S == 32):
         with pytest.raises(B.ScoutError) as ei:
-            B.set_attn_mode(2, 0)
+            B.set_attn_mode(2, 0, 0)
             try:
                 dev.attn()
             finally:
-                B.set_attn_mode(0, 0)
+                B.set_attn_mode(0, 0, 0)
         assert ei.value.code == B.EUNSUPPORTED
         return
     dev.set_selection_from_oracle(res)
-    for nsplit in (0, 1, 3):
-        B.set_attn_mode(family, nsplit)
+    modes = [(0, 0), (1, 0), (3, 0)] if family == 1 else [(0, 0), (1, 16), (1, 8), (1, 4), (3, 8), (2, 4), (5, 16)]
+    for nsplit, waves in modes:
+        B.set_attn_mode(family, nsplit, waves)
         try:
             dev.o.fill_(float("nan")); dev.m.fill_(float("nan")); dev.l.fill_(float("nan"))
             dev.attn()
         finally:
-            B.set_attn_mode(0, 0)
+            B.set_attn_mode(0, 0, 0)
         o, m, l = dev.o.cpu().numpy(), dev.m.cpu().numpy(), dev.l.cpu().numpy()
         worst = 0.0
         for (b, g), op in res.items():
@@ -185,7 +186,7 @@ def test_sparse_decode_attn(cfg, family):
                 assert err <= TOL[cfg.dtype], (b, g, h, nsplit, err)
                 lse = m[b, hq] + np.log(l[b, hq])
                 assert abs(lse - (wm + np.log(wl_))) <= LSE_TOL[cfg.dtype] * max(1.0, abs(wm)), (b, g, h)
-        print(f"{cfg.name} family {family} nsplit {nsplit}: max |o - oracle| = {worst:.3e}")
+        print(f"{cfg.name} family {family} nsplit {nsplit} waves {waves}: max |o - oracle| = {worst:.3e}")
 
 
 def test_merge_partials(cfg):
@@ -220,24 +221,30 @@ def test_layer_step_end_to_end(cfg):
     wl, res, dev = setup(cfg)
     dev.set_digest_from_oracle(res)
     dev.set_host_partials_from_oracle(res)
-    dev.out.zero_()
-    dev.layer_step()
-    sel_all = dev.sel_all.cpu().numpy()
-    out = _f64(to_np(dev.out))
-    lse = dev.lse.cpu().numpy()
-    worst = 0.0
-    for (b, g), op in res.items():
-        if not np.array_equal(sel_all[b, g], op.sel):
-            assert harness.boundary_gap(op, cfg.k) < 1e-6
-            continue   # a different (excused) selection has different host partials
-        for h in range(cfg.G):
-            hq = g * cfg.G + h
-            want, wlse = op.out[h]
-            err = np.abs(out[b, hq] - want).max()
-            worst = max(worst, err)
-            assert err <= TOL[cfg.dtype], (b, g, h, err)
-            assert abs(lse[b, hq] - wlse) <= LSE_TOL[cfg.dtype] * max(1.0, abs(wlse))
-    print(f"{cfg.name}: layer step max |out - oracle| = {worst:.3e}")
+    mfma = cfg.dtype == "bf16" and cfg.d == 128 and cfg.S == 32
+    for mode in ([(0, 0, 0), (2, 1, 16), (2, 4, 4), (2, 2, 8), (2, 3, 8), (1, 2, 0)] if mfma else [(0, 0, 0), (1, 2, 0)]):
+        dev.out.zero_(); dev.lse.fill_(float("nan"))
+        B.set_attn_mode(*mode)
+        try:
+            dev.layer_step()
+        finally:
+            B.set_attn_mode(0, 0, 0)
+        sel_all = dev.sel_all.cpu().numpy()
+        out = _f64(to_np(dev.out))
+        lse = dev.lse.cpu().numpy()
+        worst = 0.0
+        for (b, g), op in res.items():
+            if not np.array_equal(sel_all[b, g], op.sel):
+                assert harness.boundary_gap(op, cfg.k) < 1e-6
+                continue   # a different (excused) selection has different host partials
+            for h in range(cfg.G):
+                hq = g * cfg.G + h
+                want, wlse = op.out[h]
+                err = np.abs(out[b, hq] - want).max()
+                worst = max(worst, err)
+                assert err <= TOL[cfg.dtype], (b, g, h, err, mode)
+                assert abs(lse[b, hq] - wlse) <= LSE_TOL[cfg.dtype] * max(1.0, abs(wlse))
+        print(f"{cfg.name} mode {mode}: layer step max |out - oracle| = {worst:.3e}")
 
 
 def test_periodic_recall_plan_bit_exact(cfg):
@@ -318,3 +325,4 @@ def test_determinism_same_bits_on_repeat():
         dev.layer_step()
         assert torch.equal(dev.out, a[0]) and torch.equal(dev.lse, a[1])
         assert torch.equal(dev.sel_all, a[2]) and torch.equal(dev.scores, a[3])
+
