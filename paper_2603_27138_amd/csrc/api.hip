@@ -18,6 +18,10 @@ bool mfma_supported(const Dims&, int);
 int launch_attn(const Dims&, int, int, int, const void*, const void*, const void*, long long,
                 const int32_t*, const int32_t*, const int32_t*, Partials, Epilogue, hipStream_t);
 int launch_combine(const Dims&, Partials, Epilogue, hipStream_t);
+bool select_attend_supported(const Dims&, int);
+int launch_select_attend(const Dims&, const void*, const float*, const int32_t*, const void*, const void*,
+                         long long, int32_t*, int32_t*, int32_t*, int32_t*, int32_t*, int32_t*, Partials,
+                         Epilogue, hipStream_t);
 int launch_merge(const Dims&, int, const float*, const float*, const float*, const float*,
                  const float*, const float*, void*, float*, hipStream_t);
 
@@ -28,6 +32,7 @@ constexpr int kMfmaWavesPerWg = 4;
 static int g_family = 0;  // 0 auto, 1 vector ALU, 2 MFMA
 static int g_nsplit = 0;  // 0 auto
 static int g_waves = 0;   // 0 auto; MFMA family only
+static int g_fuse_select = 1;  // scout_layer_step: selection inside the attention launch
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -171,6 +176,9 @@ const char* scout_strerror(int code) {
 }
 
 int scout_set_attn_mode(int family, int nsplit, int waves) {
+  // family 3 = MFMA family with select_topk as a launch of its own inside scout_layer_step
+  g_fuse_select = family != 3;
+  if (family == 3) family = 2;
   if (family < 0 || family > 2 || nsplit < 0 || nsplit > kMaxSplit) return SCOUT_EINVAL;
   if (waves != 0 && waves != 4 && waves != 8 && waves != 16) return SCOUT_EINVAL;
   g_family = family;
@@ -312,8 +320,6 @@ int scout_layer_step(const scout_problem* p, const void* q, const void* digest,
   hipStream_t st = static_cast<hipStream_t>(stream);
   rc = launch_score(D, p->dtype, q, digest, scores, st);
   if (rc != SCOUT_OK) return rc;
-  rc = launch_topk(D, scores, block_table, sel_all, sel_gpu, slot_gpu, n_gpu, sel_host, n_host, st);
-  if (rc != SCOUT_OK) return rc;
   Epilogue E{};
   E.mode = 2;
   E.host_o = host_o;
@@ -322,6 +328,21 @@ int scout_layer_step(const scout_problem* p, const void* q, const void* digest,
   E.out = out;
   E.lse = lse;
   E.dtype_out = p->dtype;
+  if (g_fuse_select && A.family == 2 && A.waves == 8 && select_attend_supported(D, p->dtype)) {
+    // selection rides in the head of the attention kernel: two launches for the whole step
+    Partials P = carve(ws, L, A.nsplit);
+    if (A.nsplit == 1)
+      return launch_select_attend(D, q, scores, block_table, k_pool, v_pool, n_slots, sel_all, sel_gpu,
+                                  slot_gpu, n_gpu, sel_host, n_host, P, E, st);
+    Epilogue part{};
+    part.mode = 0;
+    rc = launch_select_attend(D, q, scores, block_table, k_pool, v_pool, n_slots, sel_all, sel_gpu, slot_gpu,
+                              n_gpu, sel_host, n_host, P, part, st);
+    if (rc != SCOUT_OK) return rc;
+    return launch_combine(D, P, E, st);
+  }
+  rc = launch_topk(D, scores, block_table, sel_all, sel_gpu, slot_gpu, n_gpu, sel_host, n_host, st);
+  if (rc != SCOUT_OK) return rc;
   return run_attn(D, p->dtype, A, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, ws, L, E, st);
 }
 

@@ -19,7 +19,7 @@
 //   attn_valu_kernel  any supported (dtype, d, S): plain vector ALU, used for
 //                     fp32 and the other shapes.
 // combine_kernel folds the splits (and optionally the host partial) together.
-#include "common.h"
+#include "select.h"
 
 namespace scout {
 
@@ -40,9 +40,10 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // Pack the low (sel = 0) or high (sel = 1) bf16 of two dwords into one dword:
-// result.lo = half(a), result.hi = half(b).
+// result.lo = half(a), result.hi = half(b).  One v_perm_b32: its selector bytes
+// 0-3 address the second source operand, 4-7 the first.
 __device__ __forceinline__ uint32_t pack_halves(uint32_t a, uint32_t b, int sel) {
-  return sel ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+  return sel ? __builtin_amdgcn_perm(b, a, 0x07060302u) : __builtin_amdgcn_perm(b, a, 0x05040100u);
 }
 
 typedef __attribute__((ext_vector_type(2))) float f32x2;
@@ -122,13 +123,13 @@ struct Entry {
   int valid;
 };
 
-__device__ __forceinline__ Entry read_entry(const int32_t* __restrict__ sel_gpu,
-                                            const int32_t* __restrict__ slot_gpu, size_t list0, int i,
-                                            int n, int ctx, long long n_slots) {
+// sel / slot point at the pair's list (global memory or LDS); i is wave-uniform.
+__device__ __forceinline__ Entry read_entry(const int32_t* sel, const int32_t* slot_list, int i, int n,
+                                            int ctx, long long n_slots) {
   Entry e{0, 0};
-  if (i < n) {  // wave-uniform: scalar loads
-    const int j = sel_gpu[list0 + i];
-    const long long slot = slot_gpu[list0 + i];
+  if (i < n) {
+    const int j = __builtin_amdgcn_readfirstlane(sel[i]);
+    const long long slot = __builtin_amdgcn_readfirstlane(slot_list[i]);
     int valid = ctx - j * kMfmaS;
     valid = valid > kMfmaS ? kMfmaS : valid;
     if (j >= 0 && valid > 0 && slot >= 0 && slot < n_slots) {
@@ -185,15 +186,20 @@ __device__ __forceinline__ void consume_tile(WaveState& W, TileRegs& T, const u3
       st[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(T.k[jt][s]), as_bf16x8(qreg[s]), st[jt],
                                                        0, 0, 0);
   }
-  // st[jt][i] = logit of head ln, token 16*jt + 4*kg + i; tokens beyond `valid` (the tail of a
-  // sequence's last block) are dropped, their value rows zeroed
+  // st[jt][i] = logit of head ln, token 16*jt + 4*kg + i
   float x[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int tok = 16 * (e >> 2) + 4 * kg + (e & 3);
-    const bool live = tok < valid;
-    x[e] = live ? st[e >> 2][e & 3] * scale2 : -INFINITY;
-    if (valid < kMfmaS && !live) T.v[e] = (u32x4){0, 0, 0, 0};
+  for (int e = 0; e < 8; ++e) x[e] = st[e >> 2][e & 3] * scale2;
+  if (valid < kMfmaS) {  // wave-uniform and rare: a void tile, or the partly filled last block of a
+                         // sequence; the tokens beyond `valid` are dropped, their value rows zeroed
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int tok = 16 * (e >> 2) + 4 * kg + (e & 3);
+      if (tok >= valid) {
+        x[e] = -INFINITY;
+        T.v[e] = (u32x4){0, 0, 0, 0};
+      }
+    }
   }
   float bm = x[0];
 #pragma unroll
@@ -202,10 +208,16 @@ __device__ __forceinline__ void consume_tile(WaveState& W, TileRegs& T, const u3
   bm = fmaxf(bm, __shfl_xor(bm, 32));
   const float m_new = fmaxf(W.m, bm);
   const float m_sub = m_new == -INFINITY ? 0.0f : m_new;  // nothing seen yet: weights are 2^-inf = 0
-  const float alpha = exp2_diff(W.m, m_new);
   float p[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) p[e] = fast_exp2(x[e] - m_sub);
+  if (__ballot(m_new != W.m) != 0) {  // some head's maximum moved: rescale what has been gathered
+    const float alpha = exp2_diff(W.m, m_new);
+    W.l *= alpha;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) W.acc[r] *= alpha;
+    W.m = m_new;
+  }
   // weights go into the second product as bf16; sum what is actually used
   u32x4 preg;
   float psum = 0.0f;
@@ -214,10 +226,7 @@ __device__ __forceinline__ void consume_tile(WaveState& W, TileRegs& T, const u3
     preg[w] = cvt_pk_bf16(p[2 * w], p[2 * w + 1]);
     psum += bf16_lo(preg[w]) + bf16_hi(preg[w]);
   }
-  W.l = W.l * alpha + psum;
-  W.m = m_new;
-#pragma unroll
-  for (int r = 0; r < 8; ++r) W.acc[r] *= alpha;
+  W.l += psum;
 #pragma unroll
   for (int r = 0; r < 8; ++r) {
     u32x4 a;
@@ -227,15 +236,29 @@ __device__ __forceinline__ void consume_tile(WaveState& W, TileRegs& T, const u3
   }
 }
 
+// B operand of the first product: Q^T, column = head ln, zero beyond G
+__device__ __forceinline__ void load_q(u32x4 (&qreg)[4], const Dims& D, const uint16_t* __restrict__ q, int b,
+                                       int g, int ln, int kg) {
+  const int G = D.G;
+  const int hsafe = ln < G ? ln : G - 1;
+  const uint16_t* qrow = q + ((size_t)b * D.Hq + g * G + hsafe) * kMfmaD + kg * 8;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) qreg[s] = *reinterpret_cast<const u32x4*>(qrow + s * 32);
+  const uint32_t keep = ln < G ? 0xffffffffu : 0u;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) qreg[s] &= keep;
+}
+
+// The attention of one workgroup: its share (split) of the pair's list, folded over the waves
+// through LDS, then the epilogue.  sel / slot_list: the pair's list in global memory or LDS.
 template <int WAVES>
-__global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
-    Dims D, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_pool,
-    const uint16_t* __restrict__ v_pool, long long n_slots, const int32_t* __restrict__ sel_gpu,
-    const int32_t* __restrict__ slot_gpu, const int32_t* __restrict__ n_gpu, Partials P, Epilogue E) {
+__device__ __forceinline__ void attend_pair(const Dims& D, int pair, int split, const u32x4 (&qreg)[4],
+                                            const uint16_t* __restrict__ k_pool,
+                                            const uint16_t* __restrict__ v_pool, long long n_slots,
+                                            const int32_t* sel, const int32_t* slot_list, int n,
+                                            const Partials& P, const Epilogue& E, float* smem) {
   // per wave: [G][132] floats of o (padded rows), then m[16], l[16]
   constexpr int ROW = kMfmaD + 4;
-  extern __shared__ float smem[];
-  const int pair = blockIdx.y, split = blockIdx.x;
   const int b = pair / D.Hkv, g = pair % D.Hkv;
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -244,23 +267,10 @@ __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
   const int wstride = G * ROW + 32;  // floats of LDS per wave
 
   const int first = split * WAVES + wave, stride = P.nsplit * WAVES;
-  const size_t list0 = (size_t)pair * D.k;
-  int n = n_gpu[pair];
   n = n < 0 ? 0 : (n > D.k ? D.k : n);
+  if (n_slots <= 0) n = 0;
   const int ctx = D.ctx_len[b];
   const float scale2 = D.sm_scale * kLog2e;
-
-  // B operand of the first product: Q^T, column = head ln, zero beyond G
-  u32x4 qreg[4];
-  {
-    const int hsafe = ln < G ? ln : G - 1;
-    const uint16_t* qrow = q + ((size_t)b * D.Hq + g * G + hsafe) * kMfmaD + kg * 8;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) qreg[s] = *reinterpret_cast<const u32x4*>(qrow + s * 32);
-    const uint32_t keep = ln < G ? 0xffffffffu : 0u;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) qreg[s] &= keep;
-  }
 
   WaveState W;
 #pragma unroll
@@ -268,19 +278,18 @@ __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
   W.m = -INFINITY;
   W.l = 0.0f;
 
-  if (n_slots <= 0) n = 0;
   if constexpr (WAVES <= 8) {
     // Two tiles are kept in flight per wave (the register file allows it at two waves per SIMD):
     // the loads of tile t+1 are issued before tile t is consumed, so a wave with two tiles has
     // everything requested up front.
     TileRegs A, Bt;
-    Entry ea = read_entry(sel_gpu, slot_gpu, list0, first, n, ctx, n_slots);
-    Entry eb = read_entry(sel_gpu, slot_gpu, list0, first + stride, n, ctx, n_slots);
+    Entry ea = read_entry(sel, slot_list, first, n, ctx, n_slots);
+    Entry eb = read_entry(sel, slot_list, first + stride, n, ctx, n_slots);
     issue_tile(A, k_pool, v_pool, ea, ln, kg);
     issue_tile(Bt, k_pool, v_pool, eb, ln, kg);
     for (int i = first; i < n; i += 2 * stride) {
-      const Entry na = read_entry(sel_gpu, slot_gpu, list0, i + 2 * stride, n, ctx, n_slots);
-      const Entry nb = read_entry(sel_gpu, slot_gpu, list0, i + 3 * stride, n, ctx, n_slots);
+      const Entry na = read_entry(sel, slot_list, i + 2 * stride, n, ctx, n_slots);
+      const Entry nb = read_entry(sel, slot_list, i + 3 * stride, n, ctx, n_slots);
       consume_tile(W, A, qreg, ea.valid, scale2, kg);
       ea = na;
       issue_tile(A, k_pool, v_pool, ea, ln, kg);
@@ -291,9 +300,9 @@ __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
   } else {
     // Sixteen waves share the register file four to a SIMD: one tile in flight per wave.
     TileRegs A;
-    Entry ea = read_entry(sel_gpu, slot_gpu, list0, first, n, ctx, n_slots);
+    Entry ea = read_entry(sel, slot_list, first, n, ctx, n_slots);
     for (int i = first; i < n; i += stride) {
-      const Entry na = read_entry(sel_gpu, slot_gpu, list0, i + stride, n, ctx, n_slots);
+      const Entry na = read_entry(sel, slot_list, i + stride, n, ctx, n_slots);
       issue_tile(A, k_pool, v_pool, ea, ln, kg);
       consume_tile(W, A, qreg, ea.valid, scale2, kg);
       ea = na;
@@ -348,6 +357,100 @@ __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
       finish(D, E, b * D.Hq + g * G + h, c, o, l, M);
     }
   }
+}
+
+template <int WAVES>
+__global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
+    Dims D, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_pool,
+    const uint16_t* __restrict__ v_pool, long long n_slots, const int32_t* __restrict__ sel_gpu,
+    const int32_t* __restrict__ slot_gpu, const int32_t* __restrict__ n_gpu, Partials P, Epilogue E) {
+  extern __shared__ float smem[];
+  const int pair = blockIdx.y, split = blockIdx.x;
+  const int lane = lane_id();
+  u32x4 qreg[4];
+  load_q(qreg, D, q, pair / D.Hkv, pair % D.Hkv, lane & 15, lane >> 4);
+  const size_t list0 = (size_t)pair * D.k;
+  attend_pair<WAVES>(D, pair, split, qreg, k_pool, v_pool, n_slots, sel_gpu + list0, slot_gpu + list0,
+                     n_gpu[pair], P, E, smem);
+}
+
+// Selection and attention of a pair in one launch (the non-pipelined description of Sec. 3.2:
+// identify the top-k blocks, then attend to the resident ones).  Every workgroup of the pair
+// repeats the cheap selection from the scores (integer work on 4 KiB of keys), keeps the resident
+// list in LDS and goes straight on to its share of the tiles; split 0 also writes the lists out,
+// because the host needs to know which selected blocks are its own.
+template <int KPL>
+__global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
+    Dims D, const uint16_t* __restrict__ q, const float* __restrict__ scores,
+    const int32_t* __restrict__ table, const uint16_t* __restrict__ k_pool,
+    const uint16_t* __restrict__ v_pool, long long n_slots, int32_t* __restrict__ sel_all,
+    int32_t* __restrict__ sel_gpu, int32_t* __restrict__ slot_gpu, int32_t* __restrict__ n_gpu,
+    int32_t* __restrict__ sel_host, int32_t* __restrict__ n_host, Partials P, Epilogue E) {
+  constexpr int WAVES = 8;
+  extern __shared__ float smem[];
+  const int pair = blockIdx.y, split = blockIdx.x;
+  const int b = pair / D.Hkv;
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  // LDS after the fold area: resident list (block, slot), then the selector's exchange words
+  int* l_sel = reinterpret_cast<int*>(smem + WAVES * (D.G * (kMfmaD + 4) + 32));
+  int* l_slot = l_sel + D.k;
+  int* l_x = l_slot + D.k;
+
+  u32x4 qreg[4];
+  load_q(qreg, D, q, b, pair % D.Hkv, lane & 15, lane >> 4);
+
+  const int nb = num_blocks_of(D, b);
+  const int k_eff = D.k < nb ? D.k : nb;
+  uint32_t key[KPL];
+  int slot[KPL];
+  load_keys<WAVES, KPL>(D, scores, table, pair, nb, wave, lane, key, slot);
+  Selector<WAVES, KPL> S{l_x, 0, wave};
+  uint32_t sel = 0;
+  if (k_eff > 0) sel = S.best(key, k_eff, false);
+  uint32_t gpu = 0;
+#pragma unroll
+  for (int r = 0; r < KPL; ++r)
+    if (((sel >> r) & 1u) && slot[r] >= 0) gpu |= 1u << r;
+  int pos_all[KPL], pos_gpu[KPL];
+  S.positions(sel, pos_all);
+  const int ng = S.positions(gpu, pos_gpu);
+  const int nh = k_eff - ng;
+  const size_t out0 = (size_t)pair * D.k;
+  const bool writer = split == 0;
+#pragma unroll
+  for (int r = 0; r < KPL; ++r) {
+    if ((sel >> r) & 1u) {
+      const int i = (wave * KPL + r) * kWave + lane;
+      if (writer) sel_all[out0 + pos_all[r]] = i;
+      if ((gpu >> r) & 1u) {
+        l_sel[pos_gpu[r]] = i;
+        l_slot[pos_gpu[r]] = slot[r];
+        if (writer) {
+          sel_gpu[out0 + pos_gpu[r]] = i;
+          slot_gpu[out0 + pos_gpu[r]] = slot[r];
+        }
+      } else if (writer) {
+        sel_host[out0 + pos_all[r] - pos_gpu[r]] = i;
+      }
+    }
+  }
+  if (writer) {
+    for (int t = threadIdx.x; t < D.k; t += WAVES * kWave) {
+      if (t >= k_eff) sel_all[out0 + t] = -1;
+      if (t >= ng) {
+        sel_gpu[out0 + t] = -1;
+        slot_gpu[out0 + t] = -1;
+      }
+      if (t >= nh) sel_host[out0 + t] = -1;
+    }
+    if (threadIdx.x == 0) {
+      n_gpu[pair] = ng;
+      n_host[pair] = nh;
+    }
+  }
+  __syncthreads();
+  attend_pair<WAVES>(D, pair, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, ng, P, E, smem);
 }
 
 // ---------------------------------------------------------------- VALU family
@@ -571,6 +674,40 @@ int launch_attn(const Dims& D, int dtype, int family, int waves, const void* q, 
     else
       return SCOUT_EUNSUPPORTED;
   }
+  return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
+}
+
+bool select_attend_supported(const Dims& D, int dtype) {
+  return mfma_supported(D, dtype) && D.max_blocks <= 8 * kWave * 16;
+}
+
+// Selection fused into the head of the MFMA attention kernel (8 waves per workgroup).
+int launch_select_attend(const Dims& D, const void* q, const float* scores, const int32_t* table,
+                         const void* k_pool, const void* v_pool, long long n_slots, int32_t* sel_all,
+                         int32_t* sel_gpu, int32_t* slot_gpu, int32_t* n_gpu, int32_t* sel_host,
+                         int32_t* n_host, Partials P, Epilogue E, hipStream_t st) {
+  const int pairs = D.B * D.Hkv;
+  if (pairs == 0) return SCOUT_OK;
+  dim3 grid(P.nsplit, pairs), block(8 * kWave);
+  const size_t lds = mfma_smem_bytes(D, 8) + (2 * (size_t)D.k + selector_lds_ints<8>()) * sizeof(int);
+  const uint16_t* q16 = static_cast<const uint16_t*>(q);
+  const uint16_t* k16 = static_cast<const uint16_t*>(k_pool);
+  const uint16_t* v16 = static_cast<const uint16_t*>(v_pool);
+#define SCOUT_SA(KPL)                                                                                    \
+  hipLaunchKernelGGL((select_attend_kernel<KPL>), grid, block, lds, st, D, q16, scores, table, k16, v16, \
+                     n_slots, sel_all, sel_gpu, slot_gpu, n_gpu, sel_host, n_host, P, E)
+  const int per_lane = (D.max_blocks + 8 * kWave - 1) / (8 * kWave);
+  if (per_lane <= 2)
+    SCOUT_SA(2);
+  else if (per_lane <= 4)
+    SCOUT_SA(4);
+  else if (per_lane <= 8)
+    SCOUT_SA(8);
+  else if (per_lane <= 16)
+    SCOUT_SA(16);
+  else
+    return SCOUT_EUNSUPPORTED;
+#undef SCOUT_SA
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
 }
 

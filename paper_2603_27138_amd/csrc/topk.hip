@@ -1,159 +1,16 @@
-// Top-k block selection, residency split and the recall plan.
-//
-// Selection (Alg. 1, TopK): the k best blocks of a pair under the total order
-// (score descending, block index ascending).  Integer work only: scores are
-// mapped to order-preserving 32-bit keys, the k-th largest key is found by a
-// bit-by-bit threshold search whose counts are wave ballots and scalar
-// population counts (no sort, no shared-memory traffic for one wave), and the
-// winners are written in ascending index order by a ballot prefix count.
-// Residency split (Alg. 1: predicted blocks minus resident blocks) and the
-// recall plan (Sec. 3.4) reuse the same machinery.
-//
-// Element i of a pair lives in wave i / (64*KPL), register (i / 64) % KPL,
-// lane i % 64: loads are coalesced and index order is (wave, register, lane).
-#include "common.h"
+// Top-k block selection with residency split (Alg. 1: TopK, then predicted
+// blocks minus resident blocks) and the recall plan (Sec. 3.4), one workgroup
+// per (sequence, KV head) pair.
+#include "select.h"
 
 namespace scout {
-
-// binary32 -> key with  a < b  <=>  key(a) < key(b);  -0 and +0 share a key;
-// NaN -> 1 (below -inf); 0 is reserved for "not a candidate".
-__device__ __forceinline__ uint32_t score_key(float s) {
-  uint32_t u = __float_as_uint(s);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return 1u;
-  if ((u << 1) == 0u) u = 0u;
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-// Sum a wave-uniform value over the waves of the workgroup; also the sum over
-// the waves before this one.  lds holds 2*WAVES ints, used alternately so one
-// barrier per call is enough.
-template <int WAVES>
-__device__ __forceinline__ void wg_exchange(int v, int* lds, int& phase, int wave, int& total,
-                                            int& before) {
-  if (WAVES == 1) {
-    total = v;
-    before = 0;
-    return;
-  }
-  int* buf = lds + (phase & 1) * WAVES;
-  if (lane_id() == 0) buf[wave] = v;
-  __syncthreads();
-  total = 0;
-  before = 0;
-#pragma unroll
-  for (int w = 0; w < WAVES; ++w) {
-    const int x = buf[w];
-    total += x;
-    before += (w < wave) ? x : 0;
-  }
-  ++phase;
-}
-
-template <int WAVES, int KPL>
-struct Selector {
-  int* lds;
-  int phase;
-  int wave;
-
-  // number of keys >= cand over the whole workgroup
-  __device__ __forceinline__ int count_ge(const uint32_t (&key)[KPL], uint32_t cand) {
-    int c = 0;
-#pragma unroll
-    for (int r = 0; r < KPL; ++r) c += __popcll(__ballot(key[r] >= cand));
-    int total, before;
-    wg_exchange<WAVES>(c, lds, phase, wave, total, before);
-    return total;
-  }
-
-  // total number of set bits of a per-lane register mask, and (per element) the
-  // number of set elements that precede it in index order
-  __device__ __forceinline__ int positions(uint32_t bits, int (&pos)[KPL]) {
-    int c = 0;
-#pragma unroll
-    for (int r = 0; r < KPL; ++r) c += __popcll(__ballot((bits >> r) & 1u));
-    int total, off;
-    wg_exchange<WAVES>(c, lds, phase, wave, total, off);
-#pragma unroll
-    for (int r = 0; r < KPL; ++r) {
-      const uint64_t m = __ballot((bits >> r) & 1u);
-      pos[r] = off + mbcnt64(m);
-      off += __popcll(m);
-    }
-    return total;
-  }
-
-  __device__ __forceinline__ int count(uint32_t bits) {
-    int c = 0;
-#pragma unroll
-    for (int r = 0; r < KPL; ++r) c += __popcll(__ballot((bits >> r) & 1u));
-    int total, before;
-    wg_exchange<WAVES>(c, lds, phase, wave, total, before);
-    return total;
-  }
-
-  // Bits of the kk best candidates (key > 0) under (key descending, then index
-  // ascending, or descending when high_index_first).  Needs 1 <= kk <= number
-  // of candidates.
-  __device__ __forceinline__ uint32_t best(const uint32_t (&key)[KPL], int kk, bool high_index_first) {
-    // the largest T with  count(key >= T) >= kk  is the kk-th largest key
-    uint32_t T = 0;
-    for (int bit = 31; bit >= 0; --bit) {
-      const uint32_t cand = T | (1u << bit);
-      const int c = count_ge(key, cand);
-      if (c >= kk) T = cand;
-      if (c == kk) break;  // {key >= cand} is exactly the answer; lower bits cannot matter
-    }
-    uint32_t gt = 0, eq = 0;
-#pragma unroll
-    for (int r = 0; r < KPL; ++r) {
-      gt |= (key[r] > T ? 1u : 0u) << r;
-      eq |= (key[r] == T ? 1u : 0u) << r;
-    }
-    // after an early break T may lie between two keys: then everything >= T is taken
-    int rank[KPL];
-    const int n_eq = positions(eq, rank);
-    const int n_gt = count(gt);
-    int need = kk - n_gt;
-    // keys above T but counted as ">= cand" at the break: those are all in gt already
-    uint32_t out = gt;
-#pragma unroll
-    for (int r = 0; r < KPL; ++r) {
-      const int rk = high_index_first ? (n_eq - 1 - rank[r]) : rank[r];
-      if (((eq >> r) & 1u) && rk < need) out |= 1u << r;
-    }
-    return out;
-  }
-};
-
-// Keys and table entries of a pair.  Every load is issued unconditionally (the index is clamped
-// into the row, the value masked afterwards) so that all of them are in flight together.
-template <int WAVES, int KPL>
-__device__ __forceinline__ void load_keys(const Dims& D, const float* __restrict__ scores,
-                                          const int32_t* __restrict__ table, int pair, int nb, int wave,
-                                          int lane, uint32_t (&key)[KPL], int (&slot)[KPL]) {
-  const size_t row = (size_t)pair * D.max_blocks;
-  float sc[KPL];
-#pragma unroll
-  for (int r = 0; r < KPL; ++r) {
-    const int i = (wave * KPL + r) * kWave + lane;
-    const int ic = i < D.max_blocks ? i : D.max_blocks - 1;
-    sc[r] = scores[row + ic];
-    slot[r] = table[row + ic];
-  }
-#pragma unroll
-  for (int r = 0; r < KPL; ++r) {
-    const int i = (wave * KPL + r) * kWave + lane;
-    key[r] = i < nb ? score_key(sc[r]) : 0u;
-    slot[r] = i < nb ? slot[r] : -1;
-  }
-}
 
 template <int WAVES, int KPL>
 __global__ __launch_bounds__(WAVES* kWave) void topk_kernel(
     Dims D, const float* __restrict__ scores, const int32_t* __restrict__ table,
     int32_t* __restrict__ sel_all, int32_t* __restrict__ sel_gpu, int32_t* __restrict__ slot_gpu,
     int32_t* __restrict__ n_gpu, int32_t* __restrict__ sel_host, int32_t* __restrict__ n_host) {
-  __shared__ int lds[2 * WAVES];
+  __shared__ int lds[4 * WAVES];
   const int pair = blockIdx.x, b = pair / D.Hkv;
   const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int nb = num_blocks_of(D, b);
@@ -210,7 +67,7 @@ __global__ __launch_bounds__(WAVES* kWave) void recall_kernel(
     Dims D, const float* __restrict__ scores, int32_t* __restrict__ table,
     int32_t* __restrict__ recall_blk, int32_t* __restrict__ recall_slot,
     int32_t* __restrict__ evict_blk, int32_t* __restrict__ n_recall) {
-  __shared__ int lds[2 * WAVES];
+  __shared__ int lds[4 * WAVES];
   __shared__ int freed[kMaxK];  // slots of the evicted blocks, in ascending block order
   const int pair = blockIdx.x, b = pair / D.Hkv;
   const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);

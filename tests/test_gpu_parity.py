@@ -222,14 +222,24 @@ def test_layer_step_end_to_end(cfg):
     dev.set_digest_from_oracle(res)
     dev.set_host_partials_from_oracle(res)
     mfma = cfg.dtype == "bf16" and cfg.d == 128 and cfg.S == 32
-    for mode in ([(0, 0, 0), (2, 1, 16), (2, 4, 4), (2, 2, 8), (2, 3, 8), (1, 2, 0)] if mfma else [(0, 0, 0), (1, 2, 0)]):
+    for mode in ([(0, 0, 0), (2, 1, 16), (2, 4, 4), (2, 1, 8), (2, 3, 8), (3, 1, 8), (3, 2, 8), (1, 2, 0)] if mfma else [(0, 0, 0), (1, 2, 0)]):
         dev.out.zero_(); dev.lse.fill_(float("nan"))
+        for t_ in (dev.sel_all, dev.sel_gpu, dev.slot_gpu, dev.sel_host, dev.n_gpu, dev.n_host):
+            t_.fill_(-7)
         B.set_attn_mode(*mode)
         try:
             dev.layer_step()
         finally:
             B.set_attn_mode(0, 0, 0)
         sel_all = dev.sel_all.cpu().numpy()
+        sel_gpu, slot_gpu, sel_host = dev.sel_gpu.cpu().numpy(), dev.slot_gpu.cpu().numpy(), dev.sel_host.cpu().numpy()
+        n_gpu, n_host = dev.n_gpu.cpu().numpy(), dev.n_host.cpu().numpy()
+        for (b, g), op in res.items():      # the lists the step hands back are the selection's
+            if np.array_equal(sel_all[b, g], op.sel):
+                assert np.array_equal(sel_gpu[b, g], op.sel_gpu) and np.array_equal(sel_host[b, g], op.sel_host)
+                assert n_gpu[b, g] == op.n_gpu and n_host[b, g] == op.n_host
+                assert np.array_equal(slot_gpu[b, g, :op.n_gpu], wl.block_table[b, g, op.sel_gpu[:op.n_gpu]])
+                assert (slot_gpu[b, g, op.n_gpu:] == -1).all()
         out = _f64(to_np(dev.out))
         lse = dev.lse.cpu().numpy()
         worst = 0.0
