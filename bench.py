@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--attn-family", type=int, default=0)
     ap.add_argument("--nsplit", type=int, default=0)
     ap.add_argument("--waves", type=int, default=0)
+    ap.add_argument("--pmc-calib", action="store_true",
+                    help="also run a plain 256 MiB device copy (a known-size reference for HBM byte counters)")
     return ap.parse_args()
 
 
@@ -146,6 +148,14 @@ def main():
         e1.record(stream)
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) * 1e3 / n     # microseconds per call
+
+    if args.pmc_calib:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            B.calib_copy(src, dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     for i in range(args.warmup):
         step(i)

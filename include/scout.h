@@ -194,6 +194,14 @@ int scout_layer_step(const scout_problem* p, const void* q, const void* digest,
  */
 int scout_set_attn_mode(int family, int nsplit, int waves);
 
+/*
+ * Measurement aid, not part of the method: copy `bytes` (a multiple of 16) of
+ * device memory with one 16-byte load and store per element.  Profiling runs
+ * read the HBM byte counters of this copy of known size to scale the counters
+ * of the other kernels.
+ */
+int scout_calib_copy(const void* src, void* dst, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 
 EXPORTS = ["scout_version", "scout_strerror", "scout_workspace_bytes", "build_digests", "score_blocks",
            "select_topk", "sparse_decode_attn", "merge_partials", "periodic_recall",
-           "scout_layer_step", "scout_set_attn_mode"]
+           "scout_layer_step", "scout_set_attn_mode", "scout_calib_copy"]
 
 
 class ScoutError(RuntimeError):
@@ -62,6 +62,7 @@ def lib():
         L.sparse_decode_attn.argtypes = [pp, vp, vp, vp, i64] + [vp] * 7 + [sz, vp]
         L.merge_partials.argtypes = [pp] + [vp] * 9
         L.periodic_recall.argtypes = [pp] + [vp] * 8 + [sz, vp]
+        L.scout_calib_copy.argtypes = [vp, vp, sz, vp]
         L.scout_layer_step.argtypes = [pp, vp, vp, vp, vp, vp, i64] + [vp] * 13 + [sz, vp]
         for name in EXPORTS:
             if name not in ("scout_strerror",):
@@ -115,6 +116,11 @@ def workspace_bytes(p: Problem) -> int:
 
 def alloc_workspace(p: Problem, device="cuda") -> torch.Tensor:
     return torch.empty(workspace_bytes(p), dtype=torch.uint8, device=device)
+
+
+def calib_copy(src: torch.Tensor, dst: torch.Tensor):
+    n = src.numel() * src.element_size()
+    _check("scout_calib_copy", lib().scout_calib_copy(_ptr(src), _ptr(dst), n, _stream()))
 
 
 def build_digests(p: Problem, k_blocks, digest):

@@ -156,6 +156,13 @@ static int run_attn(const Dims& D, int dtype, const AttnPlan& A, const void* q, 
   return launch_combine(D, P, E, st);
 }
 
+// Reference for HBM byte counters: a plain copy with the same 16-byte accesses the kernels use.
+__global__ __launch_bounds__(256) void calib_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                         size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
 }  // namespace scout
 
 using namespace scout;
@@ -185,6 +192,14 @@ int scout_set_attn_mode(int family, int nsplit, int waves) {
   g_nsplit = nsplit;
   g_waves = waves;
   return SCOUT_OK;
+}
+
+int scout_calib_copy(const void* src, void* dst, size_t bytes, void* stream) {
+  if (!src || !dst || !aligned16(src) || !aligned16(dst) || bytes % 16 != 0) return SCOUT_EINVAL;
+  if (bytes == 0) return SCOUT_OK;
+  hipLaunchKernelGGL(calib_copy_kernel, dim3(4096), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const uint4*>(src), static_cast<uint4*>(dst), bytes / 16);
+  return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
 }
 
 int scout_workspace_bytes(const scout_problem* p, size_t* bytes) {
