@@ -26,7 +26,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 
 
-def parse():
+def parse(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
@@ -40,7 +40,7 @@ def parse():
     ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--pmc-calib", action="store_true",
                     help="also run a plain 256 MiB device copy (a known-size reference for HBM byte counters)")
-    return ap.parse_args()
+    return ap.parse_args(argv)
 
 
 class LayerSet:
@@ -52,12 +52,11 @@ class LayerSet:
                 setattr(self, k, v.clone() if hasattr(v, "clone") else v)
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build measures one GPU only; every (sequence, KV head) pair is independent, so "
-              "more GPUs would each run this same path on their share. Run with --gpus 1.", file=sys.stderr)
-        sys.exit(2)
+class State:
+    """Everything the timed loops need: config, host workload, layer copies, problems, workspace."""
+
+
+def setup(args) -> State:
     import torch
 
     from paper_2603_27138_amd import binding as B
@@ -68,10 +67,12 @@ def main():
     B.lib()   # fail loudly if the HIP library is missing
     B.set_attn_mode(args.attn_family, args.nsplit, args.waves)
 
-    cfg = W.qwen3_32b(B=args.batch, ctx=args.ctx)
+    st = State()
+    st.B, st.torch = B, torch
+    cfg = st.cfg = W.qwen3_32b(B=args.batch, ctx=args.ctx)
     t0 = time.time()
-    wl = W.generate(cfg, workers=16)
-    t_gen = time.time() - t0
+    wl = st.wl = W.generate(cfg, workers=16)
+    st.gen_s = time.time() - t0
 
     def dev(a):
         if a.dtype == np.uint16:
@@ -79,6 +80,8 @@ def main():
         return torch.from_numpy(a).cuda()
 
     pairs = (cfg.B, cfg.Hkv)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    f32 = st.f32 = dict(dtype=torch.float32, device="cuda")
     L0 = LayerSet()
     L0.ctx_len = torch.from_numpy(wl.ctx_len).cuda()
     L0.q = dev(wl.q)
@@ -86,7 +89,8 @@ def main():
     L0.k_pool, L0.v_pool = dev(wl.k_pool), dev(wl.v_pool)
     L0.digest = torch.zeros(*pairs, cfg.max_blocks, 2, cfg.d, dtype=torch.bfloat16, device="cuda")
     p0 = B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, B.BF16, cfg.max_blocks, cfg.k, L0.ctx_len)
-    ws = B.alloc_workspace(p0)
+    st.ws = B.alloc_workspace(p0)
+    st.ws2 = B.alloc_workspace(p0)
 
     # digest cache from the keys of every block (device kernel), then drop the full key tensor
     kb = np.empty((cfg.B, cfg.Hkv, cfg.max_blocks, cfg.S, cfg.d), dtype=np.uint16)
@@ -97,8 +101,6 @@ def main():
     k_all, v_all = dev(kb), dev(vb)
     B.build_digests(p0, k_all, L0.digest)
 
-    i32 = dict(dtype=torch.int32, device="cuda")
-    f32 = dict(dtype=torch.float32, device="cuda")
     L0.scores = torch.empty(*pairs, cfg.max_blocks, **f32)
     L0.sel_all = torch.empty(*pairs, cfg.k, **i32)
     L0.sel_gpu = torch.empty(*pairs, cfg.k, **i32)
@@ -117,37 +119,71 @@ def main():
     L0.host_l = torch.zeros(cfg.B, cfg.Hq, **f32)
     all_slots = torch.arange(cfg.B * cfg.Hkv * cfg.max_blocks, **i32).view(*pairs, cfg.max_blocks)
     host_table = torch.where(L0.block_table < 0, all_slots, torch.full_like(all_slots, -1))
-    B.score_blocks(p0, L0.q, L0.digest, L0.scores, ws)
+    B.score_blocks(p0, L0.q, L0.digest, L0.scores, st.ws)
     B.select_topk(p0, L0.scores, host_table, L0.sel_all, L0.sel_gpu, L0.slot_gpu, L0.n_gpu, L0.sel_host,
-                  L0.n_host, ws)
+                  L0.n_host, st.ws)
     B.sparse_decode_attn(p0, L0.q, k_all.view(-1, cfg.S, cfg.d), v_all.view(-1, cfg.S, cfg.d),
                          cfg.B * cfg.Hkv * cfg.max_blocks, L0.sel_gpu, L0.slot_gpu, L0.n_gpu, L0.host_o,
-                         L0.host_m, L0.host_l, ws)
+                         L0.host_m, L0.host_l, st.ws)
     torch.cuda.synchronize()
     del k_all, v_all, kb, vb, host_table, all_slots
     torch.cuda.empty_cache()
 
-    sets = [L0] + [LayerSet(L0) for _ in range(args.layers - 1)]
-    probs = [B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, B.BF16, cfg.max_blocks, cfg.k, s.ctx_len)
-             for s in sets]
+    st.sets = [L0] + [LayerSet(L0) for _ in range(args.layers - 1)]
+    st.probs = [B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, B.BF16, cfg.max_blocks, cfg.k, s.ctx_len)
+                for s in st.sets]
+    st.part_o = torch.empty(cfg.B, cfg.Hq, cfg.d, **f32)
+    st.part_m = torch.empty(cfg.B, cfg.Hq, **f32)
+    st.part_l = torch.empty(cfg.B, cfg.Hq, **f32)
+    return st
 
-    def step(i):
-        s, p = sets[i % len(sets)], probs[i % len(sets)]
-        B.layer_step(p, s.q, s.digest, s.block_table, s.k_pool, s.v_pool, wl.n_slots, s.host_o, s.host_m,
-                     s.host_l, s.scores, s.sel_all, s.sel_gpu, s.slot_gpu, s.n_gpu, s.sel_host, s.n_host,
-                     s.out, s.lse, ws)
 
+def step(st, i, ws=None):
+    s, p = st.sets[i % len(st.sets)], st.probs[i % len(st.sets)]
+    st.B.layer_step(p, s.q, s.digest, s.block_table, s.k_pool, s.v_pool, st.wl.n_slots, s.host_o, s.host_m,
+                    s.host_l, s.scores, s.sel_all, s.sel_gpu, s.slot_gpu, s.n_gpu, s.sel_host, s.n_host,
+                    s.out, s.lse, st.ws if ws is None else ws)
+
+
+def attn_only(st, i):
+    s, p = st.sets[i % len(st.sets)], st.probs[i % len(st.sets)]
+    st.B.sparse_decode_attn(p, s.q, s.k_pool, s.v_pool, st.wl.n_slots, s.sel_gpu, s.slot_gpu, s.n_gpu,
+                            st.part_o, st.part_m, st.part_l, st.ws)
+
+
+def score_only(st, i):
+    s, p = st.sets[i % len(st.sets)], st.probs[i % len(st.sets)]
+    st.B.score_blocks(p, s.q, s.digest, s.scores, st.ws)
+
+
+def select_only(st, i):
+    s, p = st.sets[i % len(st.sets)], st.probs[i % len(st.sets)]
+    st.B.select_topk(p, s.scores, s.block_table, s.sel_all, s.sel_gpu, s.slot_gpu, s.n_gpu, s.sel_host,
+                     s.n_host, st.ws)
+
+
+def timed(st, fn, n):
+    """Microseconds per call: HIP events on the stream the kernels are launched on."""
+    torch = st.torch
     stream = torch.cuda.current_stream()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(stream)
+    for i in range(n):
+        fn(st, i)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / n
 
-    def timed(fn, n):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record(stream)
-        for i in range(n):
-            fn(i)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / n     # microseconds per call
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only; every (sequence, KV head) pair is independent, so "
+              "more GPUs would each run this same path on their share. Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    st = setup(args)
+    torch, B, cfg, wl = st.torch, st.B, st.cfg, st.wl
 
     if args.pmc_calib:
         src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
@@ -158,41 +194,23 @@ def main():
         del src, dst
 
     for i in range(args.warmup):
-        step(i)
+        step(st, i)
     torch.cuda.synchronize()
     t_wall0 = time.time()
-    us_step = timed(step, args.steps)
+    us_step = timed(st, step, args.steps)
     t_wall = time.time() - t_wall0
 
     # per-kernel figures on the same stream, same rotation: sparse_decode_attn alone (one launch of the
     # attention kernel per call), the scoring pass alone, the selection alone (HIP events around `steps`
     # back-to-back launches)
-    part_o = torch.empty(cfg.B, cfg.Hq, cfg.d, **f32)
-    part_m = torch.empty(cfg.B, cfg.Hq, **f32)
-    part_l = torch.empty(cfg.B, cfg.Hq, **f32)
-
-    def attn_only(i):
-        s, p = sets[i % len(sets)], probs[i % len(sets)]
-        B.sparse_decode_attn(p, s.q, s.k_pool, s.v_pool, wl.n_slots, s.sel_gpu, s.slot_gpu, s.n_gpu, part_o,
-                             part_m, part_l, ws)
-
-    def score_only(i):
-        s, p = sets[i % len(sets)], probs[i % len(sets)]
-        B.score_blocks(p, s.q, s.digest, s.scores, ws)
-
-    def select_only(i):
-        s, p = sets[i % len(sets)], probs[i % len(sets)]
-        B.select_topk(p, s.scores, s.block_table, s.sel_all, s.sel_gpu, s.slot_gpu, s.n_gpu, s.sel_host,
-                      s.n_host, ws)
-
     for i in range(args.warmup):
-        attn_only(i)
-    us_attn = timed(attn_only, args.steps)
-    us_score = timed(score_only, args.steps)
-    us_select = timed(select_only, args.steps)
+        attn_only(st, i)
+    us_attn = timed(st, attn_only, args.steps)
+    us_score = timed(st, score_only, args.steps)
+    us_select = timed(st, select_only, args.steps)
 
     tile_bytes = 2 * cfg.S * cfg.d * 2                       # K + V tile of one block, bf16
-    n_blocks = int(sets[0].n_gpu.sum().item())
+    n_blocks = int(st.sets[0].n_gpu.sum().item())
     attn_bytes = n_blocks * tile_bytes                       # algorithmic bytes of one attention launch
     digest_bytes = cfg.B * cfg.Hkv * cfg.max_blocks * 2 * cfg.d * 2
     attn_gbps = attn_bytes / us_attn * 1e-3
@@ -219,7 +237,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "C3 qwen3-32b-shaped single layer", "batch": cfg.B, "q_heads": cfg.Hq,
                    "kv_heads": cfg.Hkv, "head_dim": cfg.d, "context": args.ctx, "block": cfg.S, "k_blocks": cfg.k,
-                   "host_resident": cfg.p_host, "layer_copies": len(sets), "gpu_blocks_per_step": n_blocks},
+                   "host_resident": cfg.p_host, "layer_copies": len(st.sets), "gpu_blocks_per_step": n_blocks},
         "kv_gbps": round(attn_gbps, 1),
         "kernels_us": {"score_blocks": round(us_score, 3), "select_topk": round(us_select, 3),
                        "sparse_decode_attn": round(us_attn, 3)},
@@ -228,26 +246,26 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
                      "traffic": traffic, "algorithmic_bytes": attn_bytes},
         "wall_s_timed_region": round(t_wall, 3),
-        "gen_s": round(t_gen, 1),
+        "gen_s": round(st.gen_s, 1),
     }
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, wl, sets[0])
+        result["cpu_baseline"] = cpu_baseline(st)
     print(json.dumps(result))
 
 
-def cpu_baseline(cfg, wl, s0):
+def cpu_baseline(st):
     """The oracle, as it stands, on the host cores: one full layer-step of the same workload
     (score, select, split, partial attention over the resident selected blocks, merge) for every
-    pair; also a spot check of the device output against it."""
+    pair; also a check of the device output against it."""
     import oracle
     from paper_2603_27138_amd import workload as W
 
+    cfg, wl, s0, torch = st.cfg, st.wl, st.sets[0], st.torch
     host_o = s0.host_o.cpu().numpy().astype(np.float64)
     host_m = s0.host_m.cpu().numpy().astype(np.float64)
     host_l = s0.host_l.cpu().numpy().astype(np.float64)
-    out_dev = s0.out.view(torch_int16()).cpu().numpy().view(np.uint16)
-    out_dev = W.bf16_bits_to_f32(out_dev).astype(np.float64)
+    out_dev = W.bf16_bits_to_f32(s0.out.view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
     sel_dev = s0.sel_all.cpu().numpy()
     digs = {p: oracle.digest(wl.K[p], int(cfg.ctx[p[0]]), cfg.S) for p in wl.K}   # not timed: an input
     t0 = time.perf_counter()
@@ -269,11 +287,6 @@ def cpu_baseline(cfg, wl, s0):
     return {"value": round(dt * 1e6, 1), "unit": "us/layer-step", "cores": 1, "kind": "oracle",
             "sample": f"one full layer-step, all {len(digs)} (sequence, KV head) pairs, single thread",
             "device_vs_oracle_max_abs_err": worst, "selection_mismatches": sel_bad}
-
-
-def torch_int16():
-    import torch
-    return torch.int16
 
 
 if __name__ == "__main__":

@@ -185,11 +185,11 @@ int scout_layer_step(const scout_problem* p, const void* q, const void* digest,
 /*
  * Tuning knob for measurements: force the attention kernel family, the split
  * count per pair and the workgroup size.  family: 0 = automatic, 1 = generic
- * vector-ALU kernel, 2 = MFMA kernel (bf16, d = 128, S = 32 only; otherwise
+ * vector-ALU kernel, 2 = MFMA kernel (bf16 and d = 128 only; otherwise
  * SCOUT_EUNSUPPORTED at the call), 3 = as 2, but scout_layer_step launches the
  * selection on its own instead of inside the attention kernel.
  * nsplit: 0 = automatic, else 1..64.
- * waves: 0 = automatic, else 4, 8 or 16 waves per workgroup (MFMA family).
+ * waves: 0 = automatic, else 8 or 16 waves per workgroup (MFMA family).
  * Process-wide, not thread-safe.
  */
 int scout_set_attn_mode(int family, int nsplit, int waves);

@@ -102,16 +102,17 @@ static int plan_attn(const Dims& D, int dtype, AttnPlan* out) {
   const long long pairs = (long long)D.B * D.Hkv;
   int ns = g_nsplit, waves = 1;
   if (fam == 2) {
-    // Eight waves per workgroup, two tiles in flight per wave.  With at least ~100 pairs one
-    // workgroup per pair keeps enough tiles in flight and finishes the pair without a second pass;
-    // with fewer pairs the block list is split over several workgroups.
+    // Eight waves per workgroup, four 16-token units in flight per wave.  A compute unit sustains
+    // only a fraction of the HBM rate on its own, so the launch should cover all 256 of them: a
+    // pair's units are split over ceil(256 / pairs) workgroups (folded by the small combine pass)
+    // unless the pairs alone nearly fill the chip.
     waves = g_waves ? g_waves : 8;
     if (ns == 0) {
-      if (pairs >= 96) {
+      if (pairs >= 192) {
         ns = 1;
       } else {
         long long want = (256 + pairs - 1) / (pairs > 0 ? pairs : 1);
-        const long long cap = (D.k + waves - 1) / waves;
+        const long long cap = ((long long)D.k * (D.S / 16) + waves - 1) / waves;
         ns = (int)(want > cap ? cap : want);
       }
     }
@@ -187,7 +188,7 @@ int scout_set_attn_mode(int family, int nsplit, int waves) {
   g_fuse_select = family != 3;
   if (family == 3) family = 2;
   if (family < 0 || family > 2 || nsplit < 0 || nsplit > kMaxSplit) return SCOUT_EINVAL;
-  if (waves != 0 && waves != 4 && waves != 8 && waves != 16) return SCOUT_EINVAL;
+  if (waves != 0 && waves != 8 && waves != 16) return SCOUT_EINVAL;
   g_family = family;
   g_nsplit = nsplit;
   g_waves = waves;

@@ -12,10 +12,9 @@
 // where it leaves the library.
 //
 // Two kernel families write the same per-split partials into the workspace:
-//   attn_mfma_kernel  bf16, d = 128, S = 32: the G query heads of a KV head form
-//                     one MFMA operand, K and V tiles go from HBM straight into
-//                     MFMA operand registers (no LDS), one 16 KiB K+V tile pair
-//                     per wave iteration.
+//   attn_mfma_kernel  bf16, d = 128: the G query heads of a KV head form one MFMA
+//                     operand, K and V rows go from HBM straight into MFMA operand
+//                     registers (no LDS), in units of 16 tokens.
 //   attn_valu_kernel  any supported (dtype, d, S): plain vector ALU, used for
 //                     fp32 and the other shapes.
 // combine_kernel folds the splits (and optionally the host partial) together.
@@ -55,11 +54,26 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float x, float y) {
 }
 
 constexpr int kMfmaD = 128;
-constexpr int kMfmaS = 32;
+
+// The host's partial for one output element (mode 2 only); loaded ahead of the point of use so
+// that its latency hides behind the fold.
+struct HostPart {
+  float o, m, l;
+};
+
+__device__ __forceinline__ HostPart load_host(const Dims& D, const Epilogue& E, int bh, int c) {
+  HostPart hp{0.0f, -INFINITY, 0.0f};
+  if (E.mode == 2 && E.host_o != nullptr) {
+    hp.m = E.host_m[bh];
+    hp.l = E.host_l[bh];
+    hp.o = E.host_o[(size_t)bh * D.d + c];
+  }
+  return hp;
+}
 
 // acc: unnormalised weighted value sum of channel c, l: weight sum, M2: base-2 maximum
 __device__ __forceinline__ void finish(const Dims& D, const Epilogue& E, int bh, int c, float acc,
-                                       float l, float M2) {
+                                       float l, float M2, const HostPart& hp) {
   const float m_nat = M2 * kLn2;  // -inf stays -inf
   const float o_norm = l > 0.0f ? acc / l : 0.0f;
   if (E.mode == 1) {
@@ -70,12 +84,7 @@ __device__ __forceinline__ void finish(const Dims& D, const Epilogue& E, int bh,
     }
     return;
   }
-  float mb = -INFINITY, lb = 0.0f, ob = 0.0f;
-  if (E.host_o != nullptr) {
-    mb = E.host_m[bh];
-    lb = E.host_l[bh];
-    ob = E.host_o[(size_t)bh * D.d + c];
-  }
+  const float mb = hp.m, lb = hp.l, ob = hp.o;
   float ms = -INFINITY;
   if (l > 0.0f) ms = fmaxf(ms, m_nat);
   if (lb > 0.0f) ms = fmaxf(ms, mb);
@@ -93,78 +102,81 @@ __device__ __forceinline__ void finish(const Dims& D, const Epilogue& E, int bh,
   if (E.lse != nullptr && c == 0) E.lse[bh] = ls > 0.0f ? ms + logf(ls) : -INFINITY;
 }
 
-// One wave per (pair, split, wave-in-workgroup) walks over the pair's resident
-// selected blocks i = first, first + stride, ...  For each block:
-//   logits^T[token][head] = K[token][:] . Q[head][:]      8 x mfma 16x16x32
+// The work of a pair is cut into units of 16 tokens (a block of S tokens is S/16 units; a unit's K
+// rows and V rows are 4 KiB each, contiguous).  The pair's units are dealt to the waves that share
+// the pair (all waves of all its workgroups) in contiguous ranges whose lengths differ by at most
+// one, so no wave waits for a neighbour that got a whole block more.  For each unit:
+//   logits^T[token][head] = K[token][:] . Q[head][:]            4 x mfma 16x16x32
 //   online softmax per head (heads live in lane % 16)
-//   out^T[dim][head]    += V^T[dim][token] . P^T[token][head]   8 x mfma 16x16x32
-// Operand layout of v_mfma_f32_16x16x32_bf16: lane L supplies, for A, row L%16
-// and for B, column L%16, the 8 contraction elements of group L/16; the result
-// has column L%16 and rows 4*(L/16)+i.  The contraction index may be labelled
-// freely as long as A and B agree, which lets the logits leave the first
-// product in exactly the registers the second one needs: lane L ends up with the
-// logits of head L%16 for tokens 16*j + 4*(L/16) + i (j = 0,1; i = 0..3), so the
-// value rows are loaded in that same token order.  Element r of a lane's 16-byte
-// value chunk feeds product r, whose output row index then means channel
-// 8*row + r.
+//   out^T[dim][head]    += V^T[dim][token] . P^T[token][head]   8 x mfma 16x16x16
+// Operand layout of the 16x16 MFMAs: lane L supplies, for A, row L%16 and for B, column L%16, the
+// contraction elements of group L/16 (8 of them for x32, 4 for x16); the result has column L%16 and
+// rows 4*(L/16)+i.  The contraction index may be labelled freely as long as A and B agree, which
+// lets the logits leave the first product in exactly the registers the second one needs: lane L
+// ends up with the logits of head L%16 for tokens 4*(L/16) + i (i = 0..3), so the value rows are
+// loaded in that same token order.  Element r of a lane's 16-byte value chunk feeds product r, whose
+// output row index then means channel 8*row + r.
 //
-// The waves of a workgroup fold their partials through LDS; with one split per
-// pair the workgroup finishes the pair itself (Epilogue modes 1 and 2), so the
-// whole attention is one launch and nothing goes through the workspace.
-// K and V tile of one block in MFMA operand registers (64 VGPRs).
-struct TileRegs {
-  u32x4 k[2][4];  // [token half][contraction step]: row = token 16*jt + ln, group kg
-  u32x4 v[8];     // rows in the token order of this lane's logits, 16-byte chunk ln
+// The waves of a workgroup fold their partials through LDS; with one split per pair the workgroup
+// finishes the pair itself (Epilogue modes 1 and 2), so the whole attention is one launch and
+// nothing goes through the workspace.
+
+constexpr int kUnitTokens = 16;
+constexpr int kUnitBytes = kUnitTokens * kMfmaD * 2;  // of K, and of V
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+// K and V rows of one unit in MFMA operand registers (32 VGPRs).
+struct UnitRegs {
+  u32x4 k[4];  // contraction step s: row = token ln, 16-byte chunk 4*s + kg
+  u32x4 v[4];  // row = token 4*kg + i, 16-byte chunk ln
 };
 
-// One list entry of a pair, checked: pool slot and number of valid tokens (0 = nothing to read).
+// One unit, checked: where it starts in the pools (element offset) and how many of its tokens
+// count (0 = nothing to read).
 struct Entry {
-  long long slot;
+  size_t elem_off;
   int valid;
 };
 
-// sel / slot point at the pair's list (global memory or LDS); i is wave-uniform.
-__device__ __forceinline__ Entry read_entry(const int32_t* sel, const int32_t* slot_list, int i, int n,
-                                            int ctx, long long n_slots) {
+// sel / slot_list point at the pair's list (global memory or LDS); u is wave-uniform.
+__device__ __forceinline__ Entry read_entry(const int32_t* sel, const int32_t* slot_list, int u, int u_end,
+                                            int upb, int S, int ctx, long long n_slots) {
   Entry e{0, 0};
-  if (i < n) {
+  if (u < u_end) {
+    const int i = u / upb, sub = u - i * upb;
     const int j = __builtin_amdgcn_readfirstlane(sel[i]);
     const long long slot = __builtin_amdgcn_readfirstlane(slot_list[i]);
-    int valid = ctx - j * kMfmaS;
-    valid = valid > kMfmaS ? kMfmaS : valid;
+    int valid = ctx - j * S - sub * kUnitTokens;
+    valid = valid > kUnitTokens ? kUnitTokens : valid;
     if (j >= 0 && valid > 0 && slot >= 0 && slot < n_slots) {
-      e.slot = slot;
+      e.elem_off = ((size_t)slot * S + sub * kUnitTokens) * kMfmaD;
       e.valid = valid;
     }
   }
   return e;
 }
 
-constexpr int kTileBytes = kMfmaS * kMfmaD * 2;
-
-// Request a tile.  The loads go through a buffer descriptor that covers exactly the tile, or
-// nothing when the entry is void: then every lane gets zeros without touching memory.  That keeps
-// the issue path free of branches, so the compiler can count outstanding loads exactly and a wave
-// can wait for one tile while the next is still in flight.
-__device__ __forceinline__ void issue_tile(TileRegs& T, const uint16_t* __restrict__ k_pool,
+// Request a unit.  The loads go through a buffer descriptor that covers exactly the unit, or nothing
+// when the entry is void: then every lane gets zeros without touching memory.  That keeps the issue
+// path free of branches, so the compiler can count outstanding loads exactly and a wave can wait for
+// one unit while the next ones are still in flight.
+__device__ __forceinline__ void issue_unit(UnitRegs& T, const uint16_t* __restrict__ k_pool,
                                            const uint16_t* __restrict__ v_pool, const Entry& e, int ln,
                                            int kg) {
-  const int bytes = e.valid > 0 ? kTileBytes : 0;
-  const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint16_t*>(k_pool + (size_t)e.slot * (kMfmaS * kMfmaD)), 0, bytes, 0x00020000);
-  const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<uint16_t*>(v_pool + (size_t)e.slot * (kMfmaS * kMfmaD)), 0, bytes, 0x00020000);
-  const int koff = ln * 256 + kg * 16;   // row 16*jt + ln, 16-byte chunk 4*s + kg
-  const int voff = kg * 1024 + ln * 16;  // row 16*(e/4) + 4*kg + e%4, chunk ln
+  const int bytes = e.valid > 0 ? kUnitBytes : 0;
+  const __amdgpu_buffer_rsrc_t kr =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(k_pool + e.elem_off), 0, bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t vr =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(v_pool + e.elem_off), 0, bytes, 0x00020000);
+  const int koff = ln * 256 + kg * 16;   // row ln, 16-byte chunk 4*s + kg
+  const int voff = kg * 1024 + ln * 16;  // row 4*kg + i, chunk ln
 #pragma unroll
-  for (int jt = 0; jt < 2; ++jt)
+  for (int s = 0; s < 4; ++s)
+    T.k[s] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(kr, koff + s * 64, 0, 0));
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
-      T.k[jt][s] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(kr, koff + s * 64, jt * 4096, 0));
-#pragma unroll
-  for (int e8 = 0; e8 < 8; ++e8)
-    T.v[e8] = __builtin_bit_cast(
-        u32x4, __builtin_amdgcn_raw_buffer_load_b128(vr, voff + (e8 & 3) * 256, (e8 >> 2) * 4096, 0));
+  for (int i = 0; i < 4; ++i)
+    T.v[i] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(vr, voff + i * 256, 0, 0));
 }
 
 // Online-softmax state of one wave: head ln, channels 8*(4*kg + i) + r in acc[r][i].
@@ -173,44 +185,36 @@ struct WaveState {
   float m, l;
 };
 
-// Fold one tile into the wave's state.  `valid` tokens of the tile count (0: the tile is void and
-// leaves the state as it is), so this too runs without a branch.
-__device__ __forceinline__ void consume_tile(WaveState& W, TileRegs& T, const u32x4 (&qreg)[4], int valid,
+// Fold one unit into the wave's state.  `valid` tokens of the unit count (0: the unit is void and
+// leaves the state as it is), so this too runs without a data-dependent branch around loads.
+__device__ __forceinline__ void consume_unit(WaveState& W, UnitRegs& T, const u32x4 (&qreg)[4], int valid,
                                              float scale2, int kg) {
-  f32x4 st[2];
+  f32x4 st = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int jt = 0; jt < 2; ++jt) {
-    st[jt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < 4; ++s)
+    st = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(T.k[s]), as_bf16x8(qreg[s]), st, 0, 0, 0);
+  // st[i] = logit of head ln, token 4*kg + i
+  float x[4];
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
-      st[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(T.k[jt][s]), as_bf16x8(qreg[s]), st[jt],
-                                                       0, 0, 0);
-  }
-  // st[jt][i] = logit of head ln, token 16*jt + 4*kg + i
-  float x[8];
+  for (int i = 0; i < 4; ++i) x[i] = st[i] * scale2;
+  if (valid < kUnitTokens) {  // wave-uniform and rare: a void unit, or the partly filled last block
+                              // of a sequence; tokens beyond `valid` are dropped, their value rows zeroed
 #pragma unroll
-  for (int e = 0; e < 8; ++e) x[e] = st[e >> 2][e & 3] * scale2;
-  if (valid < kMfmaS) {  // wave-uniform and rare: a void tile, or the partly filled last block of a
-                         // sequence; the tokens beyond `valid` are dropped, their value rows zeroed
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int tok = 16 * (e >> 2) + 4 * kg + (e & 3);
-      if (tok >= valid) {
-        x[e] = -INFINITY;
-        T.v[e] = (u32x4){0, 0, 0, 0};
+    for (int i = 0; i < 4; ++i) {
+      if (4 * kg + i >= valid) {
+        x[i] = -INFINITY;
+        T.v[i] = (u32x4){0, 0, 0, 0};
       }
     }
   }
-  float bm = x[0];
-#pragma unroll
-  for (int e = 1; e < 8; ++e) bm = fmaxf(bm, x[e]);
+  float bm = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
   bm = fmaxf(bm, __shfl_xor(bm, 16));
   bm = fmaxf(bm, __shfl_xor(bm, 32));
   const float m_new = fmaxf(W.m, bm);
   const float m_sub = m_new == -INFINITY ? 0.0f : m_new;  // nothing seen yet: weights are 2^-inf = 0
-  float p[8];
+  float p[4];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) p[e] = fast_exp2(x[e] - m_sub);
+  for (int i = 0; i < 4; ++i) p[i] = fast_exp2(x[i] - m_sub);
   if (__ballot(m_new != W.m) != 0) {  // some head's maximum moved: rescale what has been gathered
     const float alpha = exp2_diff(W.m, m_new);
     W.l *= alpha;
@@ -219,20 +223,15 @@ __device__ __forceinline__ void consume_tile(WaveState& W, TileRegs& T, const u3
     W.m = m_new;
   }
   // weights go into the second product as bf16; sum what is actually used
-  u32x4 preg;
-  float psum = 0.0f;
-#pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    preg[w] = cvt_pk_bf16(p[2 * w], p[2 * w + 1]);
-    psum += bf16_lo(preg[w]) + bf16_hi(preg[w]);
-  }
-  W.l += psum;
+  const uint32_t p01 = cvt_pk_bf16(p[0], p[1]), p23 = cvt_pk_bf16(p[2], p[3]);
+  W.l += (bf16_lo(p01) + bf16_hi(p01)) + (bf16_lo(p23) + bf16_hi(p23));
+  const s16x4 preg = __builtin_bit_cast(s16x4, (uint2){p01, p23});
 #pragma unroll
   for (int r = 0; r < 8; ++r) {
-    u32x4 a;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) a[w] = pack_halves(T.v[2 * w][r >> 1], T.v[2 * w + 1][r >> 1], r & 1);
-    W.acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(a), as_bf16x8(preg), W.acc[r], 0, 0, 0);
+    const uint32_t a01 = pack_halves(T.v[0][r >> 1], T.v[1][r >> 1], r & 1);
+    const uint32_t a23 = pack_halves(T.v[2][r >> 1], T.v[3][r >> 1], r & 1);
+    W.acc[r] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, (uint2){a01, a23}), preg,
+                                                         W.acc[r], 0, 0, 0);
   }
 }
 
@@ -266,11 +265,16 @@ __device__ __forceinline__ void attend_pair(const Dims& D, int pair, int split, 
   const int G = D.G;
   const int wstride = G * ROW + 32;  // floats of LDS per wave
 
-  const int first = split * WAVES + wave, stride = P.nsplit * WAVES;
   n = n < 0 ? 0 : (n > D.k ? D.k : n);
   if (n_slots <= 0) n = 0;
   const int ctx = D.ctx_len[b];
   const float scale2 = D.sm_scale * kLog2e;
+  const int S = D.S, upb = S / kUnitTokens;
+
+  // this wave's contiguous share of the pair's units
+  const int n_units = n * upb, n_waves = P.nsplit * WAVES, v = split * WAVES + wave;
+  const int u0 = (int)((long long)v * n_units / n_waves);
+  const int u1 = (int)((long long)(v + 1) * n_units / n_waves);
 
   WaveState W;
 #pragma unroll
@@ -278,34 +282,24 @@ __device__ __forceinline__ void attend_pair(const Dims& D, int pair, int split, 
   W.m = -INFINITY;
   W.l = 0.0f;
 
-  if constexpr (WAVES <= 8) {
-    // Two tiles are kept in flight per wave (the register file allows it at two waves per SIMD):
-    // the loads of tile t+1 are issued before tile t is consumed, so a wave with two tiles has
-    // everything requested up front.
-    TileRegs A, Bt;
-    Entry ea = read_entry(sel, slot_list, first, n, ctx, n_slots);
-    Entry eb = read_entry(sel, slot_list, first + stride, n, ctx, n_slots);
-    issue_tile(A, k_pool, v_pool, ea, ln, kg);
-    issue_tile(Bt, k_pool, v_pool, eb, ln, kg);
-    for (int i = first; i < n; i += 2 * stride) {
-      const Entry na = read_entry(sel, slot_list, i + 2 * stride, n, ctx, n_slots);
-      const Entry nb = read_entry(sel, slot_list, i + 3 * stride, n, ctx, n_slots);
-      consume_tile(W, A, qreg, ea.valid, scale2, kg);
-      ea = na;
-      issue_tile(A, k_pool, v_pool, ea, ln, kg);
-      consume_tile(W, Bt, qreg, eb.valid, scale2, kg);
-      eb = nb;
-      issue_tile(Bt, k_pool, v_pool, eb, ln, kg);
-    }
-  } else {
-    // Sixteen waves share the register file four to a SIMD: one tile in flight per wave.
-    TileRegs A;
-    Entry ea = read_entry(sel, slot_list, first, n, ctx, n_slots);
-    for (int i = first; i < n; i += stride) {
-      const Entry na = read_entry(sel, slot_list, i + stride, n, ctx, n_slots);
-      issue_tile(A, k_pool, v_pool, ea, ln, kg);
-      consume_tile(W, A, qreg, ea.valid, scale2, kg);
-      ea = na;
+  // DEPTH units are kept in flight per wave: the loads of the next ones are issued before a unit is
+  // consumed, so a wave with up to DEPTH units has everything requested up front.  Eight waves per
+  // workgroup run two to a SIMD and can hold four units (128 registers); sixteen hold two.
+  constexpr int DEPTH = WAVES <= 8 ? 4 : 2;
+  UnitRegs buf[DEPTH];
+  Entry ent[DEPTH];
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d) {
+    ent[d] = read_entry(sel, slot_list, u0 + d, u1, upb, S, ctx, n_slots);
+    issue_unit(buf[d], k_pool, v_pool, ent[d], ln, kg);
+  }
+  for (int u = u0; u < u1; u += DEPTH) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      const Entry nx = read_entry(sel, slot_list, u + d + DEPTH, u1, upb, S, ctx, n_slots);
+      consume_unit(W, buf[d], qreg, ent[d].valid, scale2, kg);
+      ent[d] = nx;
+      issue_unit(buf[d], k_pool, v_pool, nx, ln, kg);
     }
   }
   f32x4(&acc)[8] = W.acc;
@@ -314,6 +308,16 @@ __device__ __forceinline__ void attend_pair(const Dims& D, int pair, int split, 
   // lanes kg = 0..3 of a head saw disjoint tokens under a common maximum
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
+
+  // the host's partial for the outputs this thread will finish: requested now, used after the fold
+  constexpr int kOutPerThread = 16 * kMfmaD / (WAVES * kWave);
+  HostPart hp[kOutPerThread];
+#pragma unroll
+  for (int t = 0; t < kOutPerThread; ++t) {
+    const int idx = threadIdx.x + t * WAVES * kWave;
+    const int hh = idx < G * kMfmaD ? idx / kMfmaD : 0;
+    hp[t] = load_host(D, E, b * D.Hq + g * G + hh, idx % kMfmaD);
+  }
 
   // fold the waves of the workgroup through LDS
   float* wo = smem + (size_t)wave * wstride;
@@ -334,7 +338,10 @@ __device__ __forceinline__ void attend_pair(const Dims& D, int pair, int split, 
   }
   __syncthreads();
   const size_t pbase = (size_t)pair * P.nsplit + split;
-  for (int idx = threadIdx.x; idx < G * kMfmaD; idx += WAVES * kWave) {
+#pragma unroll
+  for (int t = 0; t < kOutPerThread; ++t) {
+    const int idx = threadIdx.x + t * WAVES * kWave;
+    if (idx >= G * kMfmaD) break;
     const int h = idx / kMfmaD, c = idx % kMfmaD;
     float M = -INFINITY;
 #pragma unroll
@@ -354,7 +361,7 @@ __device__ __forceinline__ void attend_pair(const Dims& D, int pair, int split, 
         P.l[pbase * G + h] = l;
       }
     } else {
-      finish(D, E, b * D.Hq + g * G + h, c, o, l, M);
+      finish(D, E, b * D.Hq + g * G + h, c, o, l, M, hp[t]);
     }
   }
 }
@@ -588,7 +595,7 @@ __global__ void combine_kernel(Dims D, Partials P, Epilogue E) {
     acc += f * P.o[((p0 + s) * D.G + h) * D.d + c];
     l += f * P.l[(p0 + s) * D.G + h];
   }
-  finish(D, E, bh, c, acc, l, M);
+  finish(D, E, bh, c, acc, l, M, load_host(D, E, bh, c));
 }
 
 // Stand-alone merge of two partials given in natural-log units (Alg. 1 Merge).
@@ -625,14 +632,14 @@ __global__ void merge_kernel(Dims D, const float* __restrict__ o_a, const float*
 // ------------------------------------------------------------ host launchers
 
 bool mfma_supported(const Dims& D, int dtype) {
-  return dtype == SCOUT_BF16 && D.d == kMfmaD && D.S == kMfmaS && D.G <= 16;
+  return dtype == SCOUT_BF16 && D.d == kMfmaD && D.S % kUnitTokens == 0 && D.G <= 16;
 }
 
 size_t mfma_smem_bytes(const Dims& D, int waves) {
   return (size_t)waves * (D.G * (kMfmaD + 4) + 32) * sizeof(float);
 }
 
-// family 2: MFMA kernel with `waves` waves per workgroup (4, 8 or 16); family 1: vector ALU.
+// family 2: MFMA kernel with `waves` waves per workgroup (8 or 16); family 1: vector ALU.
 // E.mode != 0 requires P.nsplit == 1 and family 2 (the workgroup finishes the pair itself).
 int launch_attn(const Dims& D, int dtype, int family, int waves, const void* q, const void* k_pool,
                 const void* v_pool, long long n_slots, const int32_t* sel_gpu,
@@ -650,9 +657,6 @@ int launch_attn(const Dims& D, int dtype, int family, int waves, const void* q, 
                          slot_gpu, n_gpu, P, E);
     else if (waves == 8)
       hipLaunchKernelGGL((attn_mfma_kernel<8>), grid, block, lds, st, D, q16, k16, v16, n_slots, sel_gpu,
-                         slot_gpu, n_gpu, P, E);
-    else if (waves == 4)
-      hipLaunchKernelGGL((attn_mfma_kernel<4>), grid, block, lds, st, D, q16, k16, v16, n_slots, sel_gpu,
                          slot_gpu, n_gpu, P, E);
     else
       return SCOUT_EINVAL;

@@ -84,7 +84,7 @@ def test_null_misaligned_and_workspace_errors(lib):
     # host partial must be given completely or not at all
     assert L.merge_partials(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, None, None, FAKE, None, None) == lib.EINVAL
     assert L.periodic_recall(ctypes.byref(p), FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == lib.EINVAL
-    assert L.scout_set_attn_mode(4, 0, 0) == lib.EINVAL and L.scout_set_attn_mode(0, 0, 5) == lib.EINVAL and L.scout_set_attn_mode(0, 0, 0) == 0
+    assert L.scout_set_attn_mode(4, 0, 0) == lib.EINVAL and L.scout_set_attn_mode(0, 0, 4) == lib.EINVAL and L.scout_set_attn_mode(0, 0, 0) == 0
     # MFMA family forced on a shape it does not cover
     p32 = _problem(lib, dtype=lib.F32)
     assert L.scout_set_attn_mode(2, 0, 0) == 0

@@ -30,7 +30,8 @@ def small_configs():
     ragged32 = W.shrink(W.tiny(), name="ragged-f32", B=2, Hq=8, Hkv=2, ctx=(517, 2040), k=20, p_host=0.25)
     d64 = W.shrink(W.qwen3_8b(B=2, ctx=2048), name="bf16-d64-s16", d=64, S=16, k=32)
     s64 = W.shrink(W.qwen3_8b(B=1, ctx=8192), name="bf16-s64-g2", S=64, Hq=16, k=16)
-    return [W.tiny(), c2, c3, c4, c5, ragged, ragged32, d64, s64]
+    s16 = W.shrink(W.qwen3_32b(B=2, ctx=0), name="bf16-s16-ragged", S=16, ctx=(4100, 777), k=40, p_host=0.3)
+    return [W.tiny(), c2, c3, c4, c5, ragged, ragged32, d64, s64, s16]
 
 
 _CACHE = {}
@@ -154,7 +155,7 @@ def test_score_then_select_chain(cfg):
 @pytest.mark.parametrize("family", [1, 2])
 def test_sparse_decode_attn(cfg, family):
     wl, res, dev = setup(cfg)
-    if family == 2 and not (cfg.dtype == "bf16" and cfg.d == 128 and cfg.S == 32):
+    if family == 2 and not (cfg.dtype == "bf16" and cfg.d == 128):
         with pytest.raises(B.ScoutError) as ei:
             B.set_attn_mode(2, 0, 0)
             try:
@@ -164,7 +165,7 @@ def test_sparse_decode_attn(cfg, family):
         assert ei.value.code == B.EUNSUPPORTED
         return
     dev.set_selection_from_oracle(res)
-    modes = [(0, 0), (1, 0), (3, 0)] if family == 1 else [(0, 0), (1, 16), (1, 8), (1, 4), (3, 8), (2, 4), (5, 16)]
+    modes = [(0, 0), (1, 0), (3, 0)] if family == 1 else [(0, 0), (1, 16), (1, 8), (2, 8), (3, 8), (7, 8), (5, 16)]
     for nsplit, waves in modes:
         B.set_attn_mode(family, nsplit, waves)
         try:
@@ -221,8 +222,8 @@ def test_layer_step_end_to_end(cfg):
     wl, res, dev = setup(cfg)
     dev.set_digest_from_oracle(res)
     dev.set_host_partials_from_oracle(res)
-    mfma = cfg.dtype == "bf16" and cfg.d == 128 and cfg.S == 32
-    for mode in ([(0, 0, 0), (2, 1, 16), (2, 4, 4), (2, 1, 8), (2, 3, 8), (3, 1, 8), (3, 2, 8), (1, 2, 0)] if mfma else [(0, 0, 0), (1, 2, 0)]):
+    mfma = cfg.dtype == "bf16" and cfg.d == 128
+    for mode in ([(0, 0, 0), (2, 1, 16), (2, 4, 16), (2, 1, 8), (2, 3, 8), (3, 1, 8), (3, 2, 8), (1, 2, 0)] if mfma else [(0, 0, 0), (1, 2, 0)]):
         dev.out.zero_(); dev.lse.fill_(float("nan"))
         for t_ in (dev.sel_all, dev.sel_gpu, dev.slot_gpu, dev.sel_host, dev.n_gpu, dev.n_host):
             t_.fill_(-7)
