@@ -140,6 +140,18 @@ int sparse_decode_attn(const scout_problem* p, const void* q, const void* k_pool
                        float* l, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * First half of sparse_decode_attn on its own: the pass that streams the K/V
+ * rows and leaves one partial per (pair, split) in the workspace; the small
+ * combine pass that folds the splits is left out.  Same arguments; writes
+ * nothing but the workspace.  It exists so that the bandwidth-bound kernel can
+ * be timed alone.
+ */
+int scout_attn_partials(const scout_problem* p, const void* q, const void* k_pool,
+                        const void* v_pool, int64_t n_slots, const int32_t* sel_gpu,
+                        const int32_t* slot_gpu, const int32_t* n_gpu, void* ws, size_t ws_bytes,
+                        void* stream);
+
+/*
  * Merge of two partial results (Alg. 1 Merge; FlashAttention rescaling):
  *   m* = max(m_a, m_b), w_x = l_x exp(m_x - m*), out = (w_a o_a + w_b o_b)/(w_a + w_b),
  *   lse = m* + ln(w_a + w_b).  A side with l = 0 has weight 0.

@@ -21,7 +21,7 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 
 EXPORTS = ["scout_version", "scout_strerror", "scout_workspace_bytes", "build_digests", "score_blocks",
            "select_topk", "sparse_decode_attn", "merge_partials", "periodic_recall",
-           "scout_layer_step", "scout_set_attn_mode", "scout_calib_copy"]
+           "scout_layer_step", "scout_set_attn_mode", "scout_calib_copy", "scout_attn_partials"]
 
 
 class ScoutError(RuntimeError):
@@ -63,6 +63,7 @@ def lib():
         L.merge_partials.argtypes = [pp] + [vp] * 9
         L.periodic_recall.argtypes = [pp] + [vp] * 8 + [sz, vp]
         L.scout_calib_copy.argtypes = [vp, vp, sz, vp]
+        L.scout_attn_partials.argtypes = [pp, vp, vp, vp, i64] + [vp] * 4 + [sz, vp]
         L.scout_layer_step.argtypes = [pp, vp, vp, vp, vp, vp, i64] + [vp] * 13 + [sz, vp]
         for name in EXPORTS:
             if name not in ("scout_strerror",):
@@ -143,6 +144,13 @@ def sparse_decode_attn(p: Problem, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu
            lib().sparse_decode_attn(ctypes.byref(p), _ptr(q), _ptr(k_pool), _ptr(v_pool), int(n_slots),
                                     _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu), _ptr(o), _ptr(m), _ptr(l),
                                     _ptr(ws), ws.numel(), _stream()))
+
+
+def attn_partials(p: Problem, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, ws):
+    _check("scout_attn_partials",
+           lib().scout_attn_partials(ctypes.byref(p), _ptr(q), _ptr(k_pool), _ptr(v_pool), int(n_slots),
+                                     _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu), _ptr(ws), ws.numel(),
+                                     _stream()))
 
 
 def merge_partials(p: Problem, o_a, m_a, l_a, o_b, m_b, l_b, out, lse=None):

@@ -253,6 +253,27 @@ int select_topk(const scout_problem* p, const float* scores, const int32_t* bloc
                      static_cast<hipStream_t>(stream));
 }
 
+int scout_attn_partials(const scout_problem* p, const void* q, const void* k_pool, const void* v_pool,
+                        int64_t n_slots, const int32_t* sel_gpu, const int32_t* slot_gpu,
+                        const int32_t* n_gpu, void* ws, size_t ws_bytes, void* stream) {
+  Dims D;
+  int rc = check_problem(p, &D);
+  if (rc != SCOUT_OK) return rc;
+  if (!q || !sel_gpu || !slot_gpu || !n_gpu || n_slots < 0) return SCOUT_EINVAL;
+  if (n_slots > 0 && (!k_pool || !v_pool)) return SCOUT_EINVAL;
+  if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool)) return SCOUT_EINVAL;
+  WsLayout L;
+  rc = check_ws(D, ws, ws_bytes, &L);
+  if (rc != SCOUT_OK) return rc;
+  AttnPlan A;
+  rc = plan_attn(D, p->dtype, &A);
+  if (rc != SCOUT_OK) return rc;
+  Epilogue part{};
+  part.mode = 0;
+  return launch_attn(D, p->dtype, A.family, A.waves, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu,
+                     carve(ws, L, A.nsplit), part, static_cast<hipStream_t>(stream));
+}
+
 int sparse_decode_attn(const scout_problem* p, const void* q, const void* k_pool, const void* v_pool,
                        int64_t n_slots, const int32_t* sel_gpu, const int32_t* slot_gpu,
                        const int32_t* n_gpu, float* o, float* m, float* l, void* ws, size_t ws_bytes,
