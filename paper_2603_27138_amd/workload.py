@@ -75,7 +75,7 @@ class Config:
     recall_interval: int = 0   # 0: no periodic recall
     steps: int = 1
     layers: int = 1
-    rho: float = 0.98          # step-to-step query correlation for multi-step runs
+    rho: float = 0.90          # step-to-step query correlation: ~12 % of the top-k set changes per step
 
     @property
     def G(self) -> int:
