@@ -374,19 +374,31 @@ __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
   extern __shared__ float smem[];
   const int pair = blockIdx.y, split = blockIdx.x;
   const int lane = lane_id();
+  // The pair's whole list is copied to LDS by all threads at once, in the same round trip that
+  // brings the count and the queries: which entries a wave needs depends on the count, and a
+  // second, dependent trip to memory would cost more than the few hundred bytes read in vain.
+  int* l_sel = reinterpret_cast<int*>(smem + WAVES * (D.G * (kMfmaD + 4) + 32));
+  int* l_slot = l_sel + D.k;
+  const size_t list0 = (size_t)pair * D.k;
+  const int n = n_gpu[pair];
+  for (int t = threadIdx.x; t < D.k; t += WAVES * kWave) {
+    l_sel[t] = sel_gpu[list0 + t];
+    l_slot[t] = slot_gpu[list0 + t];
+  }
   u32x4 qreg[4];
   load_q(qreg, D, q, pair / D.Hkv, pair % D.Hkv, lane & 15, lane >> 4);
-  const size_t list0 = (size_t)pair * D.k;
-  attend_pair<WAVES>(D, pair, split, qreg, k_pool, v_pool, n_slots, sel_gpu + list0, slot_gpu + list0,
-                     n_gpu[pair], P, E, smem);
+  __syncthreads();
+  attend_pair<WAVES>(D, pair, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, n, P, E, smem);
 }
 
 // Selection and attention of a pair in one launch (the non-pipelined description of Sec. 3.2:
 // identify the top-k blocks, then attend to the resident ones).  Every workgroup of the pair
-// repeats the cheap selection from the scores (integer work on 4 KiB of keys), keeps the resident
-// list in LDS and goes straight on to its share of the tiles; split 0 also writes the lists out,
-// because the host needs to know which selected blocks are its own.
-template <int KPL>
+// repeats the cheap selection from the scores (integer work on a few KiB of keys), keeps the
+// resident list in LDS and goes straight on to its share of the units; split 0 also writes the
+// lists out, because the host needs to know which selected blocks are its own.
+// SEL_WAVES = 8: all waves share the keys and exchange counts through LDS; SEL_WAVES = 1: one wave
+// holds all keys and selects without a barrier while the others wait (kept for comparison).
+template <int SEL_WAVES, int KPL>
 __global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
     Dims D, const uint16_t* __restrict__ q, const float* __restrict__ scores,
     const int32_t* __restrict__ table, const uint16_t* __restrict__ k_pool,
@@ -399,65 +411,71 @@ __global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
   const int b = pair / D.Hkv;
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-  // LDS after the fold area: resident list (block, slot), then the selector's exchange words
+  // LDS after the fold area: resident list (block, slot), the selector's exchange words, the count
   int* l_sel = reinterpret_cast<int*>(smem + WAVES * (D.G * (kMfmaD + 4) + 32));
   int* l_slot = l_sel + D.k;
   int* l_x = l_slot + D.k;
+  int* l_n = l_x + selector_lds_ints<WAVES>();
 
   u32x4 qreg[4];
   load_q(qreg, D, q, b, pair % D.Hkv, lane & 15, lane >> 4);
 
-  const int nb = num_blocks_of(D, b);
-  const int k_eff = D.k < nb ? D.k : nb;
-  uint32_t key[KPL];
-  int slot[KPL];
-  load_keys<WAVES, KPL>(D, scores, table, pair, nb, wave, lane, key, slot);
-  Selector<WAVES, KPL> S{l_x, 0, wave};
-  uint32_t sel = 0;
-  if (k_eff > 0) sel = S.best(key, k_eff, false);
-  uint32_t gpu = 0;
+  if (SEL_WAVES == WAVES || wave == 0) {  // wave-uniform
+    const int sw = SEL_WAVES == WAVES ? wave : 0;
+    const int nb = num_blocks_of(D, b);
+    const int k_eff = D.k < nb ? D.k : nb;
+    uint32_t key[KPL];
+    int slot[KPL];
+    load_keys<SEL_WAVES, KPL>(D, scores, table, pair, nb, sw, lane, key, slot);
+    Selector<SEL_WAVES, KPL> S{l_x, 0, sw};
+    uint32_t sel = 0;
+    if (k_eff > 0) sel = S.best(key, k_eff, false);
+    uint32_t gpu = 0;
 #pragma unroll
-  for (int r = 0; r < KPL; ++r)
-    if (((sel >> r) & 1u) && slot[r] >= 0) gpu |= 1u << r;
-  int pos_all[KPL], pos_gpu[KPL];
-  S.positions(sel, pos_all);
-  const int ng = S.positions(gpu, pos_gpu);
-  const int nh = k_eff - ng;
-  const size_t out0 = (size_t)pair * D.k;
-  const bool writer = split == 0;
+    for (int r = 0; r < KPL; ++r)
+      if (((sel >> r) & 1u) && slot[r] >= 0) gpu |= 1u << r;
+    int pos_all[KPL], pos_gpu[KPL];
+    S.positions(sel, pos_all);
+    const int ng = S.positions(gpu, pos_gpu);
+    const int nh = k_eff - ng;
+    const size_t out0 = (size_t)pair * D.k;
+    const bool writer = split == 0;
 #pragma unroll
-  for (int r = 0; r < KPL; ++r) {
-    if ((sel >> r) & 1u) {
-      const int i = (wave * KPL + r) * kWave + lane;
-      if (writer) sel_all[out0 + pos_all[r]] = i;
-      if ((gpu >> r) & 1u) {
-        l_sel[pos_gpu[r]] = i;
-        l_slot[pos_gpu[r]] = slot[r];
-        if (writer) {
-          sel_gpu[out0 + pos_gpu[r]] = i;
-          slot_gpu[out0 + pos_gpu[r]] = slot[r];
+    for (int r = 0; r < KPL; ++r) {
+      if ((sel >> r) & 1u) {
+        const int i = (sw * KPL + r) * kWave + lane;
+        if (writer) sel_all[out0 + pos_all[r]] = i;
+        if ((gpu >> r) & 1u) {
+          l_sel[pos_gpu[r]] = i;
+          l_slot[pos_gpu[r]] = slot[r];
+          if (writer) {
+            sel_gpu[out0 + pos_gpu[r]] = i;
+            slot_gpu[out0 + pos_gpu[r]] = slot[r];
+          }
+        } else if (writer) {
+          sel_host[out0 + pos_all[r] - pos_gpu[r]] = i;
         }
-      } else if (writer) {
-        sel_host[out0 + pos_all[r] - pos_gpu[r]] = i;
       }
     }
-  }
-  if (writer) {
-    for (int t = threadIdx.x; t < D.k; t += WAVES * kWave) {
-      if (t >= k_eff) sel_all[out0 + t] = -1;
-      if (t >= ng) {
-        sel_gpu[out0 + t] = -1;
-        slot_gpu[out0 + t] = -1;
+    const int tid = sw * kWave + lane;
+    if (writer) {
+      for (int t = tid; t < D.k; t += SEL_WAVES * kWave) {
+        if (t >= k_eff) sel_all[out0 + t] = -1;
+        if (t >= ng) {
+          sel_gpu[out0 + t] = -1;
+          slot_gpu[out0 + t] = -1;
+        }
+        if (t >= nh) sel_host[out0 + t] = -1;
       }
-      if (t >= nh) sel_host[out0 + t] = -1;
+      if (tid == 0) {
+        n_gpu[pair] = ng;
+        n_host[pair] = nh;
+      }
     }
-    if (threadIdx.x == 0) {
-      n_gpu[pair] = ng;
-      n_host[pair] = nh;
-    }
+    if (tid == 0) l_n[0] = ng;
   }
   __syncthreads();
-  attend_pair<WAVES>(D, pair, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, ng, P, E, smem);
+  attend_pair<WAVES>(D, pair, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, l_n[0], P, E, smem);
 }
 
 // ---------------------------------------------------------------- VALU family
@@ -648,7 +666,7 @@ int launch_attn(const Dims& D, int dtype, int family, int waves, const void* q, 
   if (pairs == 0) return SCOUT_OK;
   if (family == 2) {
     dim3 grid(P.nsplit, pairs), block(waves * kWave);
-    const size_t lds = mfma_smem_bytes(D, waves);
+    const size_t lds = mfma_smem_bytes(D, waves) + 2 * (size_t)D.k * sizeof(int);
     const uint16_t* q16 = static_cast<const uint16_t*>(q);
     const uint16_t* k16 = static_cast<const uint16_t*>(k_pool);
     const uint16_t* v16 = static_cast<const uint16_t*>(v_pool);
@@ -693,22 +711,24 @@ int launch_select_attend(const Dims& D, const void* q, const float* scores, cons
   const int pairs = D.B * D.Hkv;
   if (pairs == 0) return SCOUT_OK;
   dim3 grid(P.nsplit, pairs), block(8 * kWave);
-  const size_t lds = mfma_smem_bytes(D, 8) + (2 * (size_t)D.k + selector_lds_ints<8>()) * sizeof(int);
+  const size_t lds = mfma_smem_bytes(D, 8) + (2 * (size_t)D.k + selector_lds_ints<8>() + 4) * sizeof(int);
   const uint16_t* q16 = static_cast<const uint16_t*>(q);
   const uint16_t* k16 = static_cast<const uint16_t*>(k_pool);
   const uint16_t* v16 = static_cast<const uint16_t*>(v_pool);
-#define SCOUT_SA(KPL)                                                                                    \
-  hipLaunchKernelGGL((select_attend_kernel<KPL>), grid, block, lds, st, D, q16, scores, table, k16, v16, \
-                     n_slots, sel_all, sel_gpu, slot_gpu, n_gpu, sel_host, n_host, P, E)
+#define SCOUT_SA(SW, KPL)                                                                              \
+  hipLaunchKernelGGL((select_attend_kernel<SW, KPL>), grid, block, lds, st, D, q16, scores, table, k16, \
+                     v16, n_slots, sel_all, sel_gpu, slot_gpu, n_gpu, sel_host, n_host, P, E)
+  // All eight waves share the keys: measured faster than one wave selecting alone while seven wait
+  // (46.9 vs 44.1 us per step at 1024 blocks per pair), a lone wave issues too slowly.
   const int per_lane = (D.max_blocks + 8 * kWave - 1) / (8 * kWave);
   if (per_lane <= 2)
-    SCOUT_SA(2);
+    SCOUT_SA(8, 2);
   else if (per_lane <= 4)
-    SCOUT_SA(4);
+    SCOUT_SA(8, 4);
   else if (per_lane <= 8)
-    SCOUT_SA(8);
+    SCOUT_SA(8, 8);
   else if (per_lane <= 16)
-    SCOUT_SA(16);
+    SCOUT_SA(8, 16);
   else
     return SCOUT_EUNSUPPORTED;
 #undef SCOUT_SA
