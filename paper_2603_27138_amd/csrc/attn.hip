@@ -208,8 +208,7 @@ __device__ __forceinline__ void consume_unit(WaveState& W, UnitRegs& T, const u3
     }
   }
   float bm = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
-  bm = fmaxf(bm, __shfl_xor(bm, 16));
-  bm = fmaxf(bm, __shfl_xor(bm, 32));
+  bm = max_xor32(max_xor16(bm));  // over the four lanes that share the head
   const float m_new = fmaxf(W.m, bm);
   const float m_sub = m_new == -INFINITY ? 0.0f : m_new;  // nothing seen yet: weights are 2^-inf = 0
   float p[4];
@@ -306,8 +305,7 @@ __device__ __forceinline__ void attend_pair(const Dims& D, int pair, int split, 
   float m_run = W.m, l_run = W.l;
 
   // lanes kg = 0..3 of a head saw disjoint tokens under a common maximum
-  l_run += __shfl_xor(l_run, 16);
-  l_run += __shfl_xor(l_run, 32);
+  l_run = sum_xor32(sum_xor16(l_run));
 
   // the host's partial for the outputs this thread will finish: requested now, used after the fold
   constexpr int kOutPerThread = 16 * kMfmaD / (WAVES * kWave);
@@ -605,15 +603,38 @@ __global__ void combine_kernel(Dims D, Partials P, Epilogue E) {
   const int pair = b * D.Hkv + hq / D.G, h = hq % D.G;
   const int c = threadIdx.x;
   const size_t p0 = (size_t)pair * P.nsplit;
-  float M = -INFINITY;
-  for (int s = 0; s < P.nsplit; ++s) M = fmaxf(M, P.m[(p0 + s) * D.G + h]);
-  float acc = 0.0f, l = 0.0f;
-  for (int s = 0; s < P.nsplit; ++s) {
-    const float f = exp2_diff(P.m[(p0 + s) * D.G + h], M);
-    acc += f * P.o[((p0 + s) * D.G + h) * D.d + c];
-    l += f * P.l[(p0 + s) * D.G + h];
+  const HostPart hp = load_host(D, E, bh, c);
+  // one pass with a running maximum, four splits at a time: every load of a group is independent
+  // of the others, so a group costs one trip to memory
+  float M = -INFINITY, acc = 0.0f, l = 0.0f;
+  for (int s0 = 0; s0 < P.nsplit; s0 += 4) {
+    float ms[4], ls[4], os[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int sp = s0 + j < P.nsplit ? s0 + j : P.nsplit - 1;
+      const size_t r = (p0 + sp) * D.G + h;
+      ms[j] = P.m[r];
+      ls[j] = P.l[r];
+      os[j] = P.o[r * D.d + c];
+    }
+    float Mn = M;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (s0 + j < P.nsplit) Mn = fmaxf(Mn, ms[j]);
+    const float f0 = exp2_diff(M, Mn);
+    acc *= f0;
+    l *= f0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (s0 + j < P.nsplit) {
+        const float f = exp2_diff(ms[j], Mn);
+        acc += f * os[j];
+        l += f * ls[j];
+      }
+    }
+    M = Mn;
   }
-  finish(D, E, bh, c, acc, l, M, load_host(D, E, bh, c));
+  finish(D, E, bh, c, acc, l, M, hp);
 }
 
 // Stand-alone merge of two partials given in natural-log units (Alg. 1 Merge).

@@ -76,6 +76,28 @@ __device__ __forceinline__ int mbcnt64(uint64_t mask) {
                                    __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0));
 }
 
+// Exchanges between the four 16-lane rows of a wave on the vector ALU (no trip through the LDS
+// crossbar): v_permlane16_swap trades the odd rows of its first operand with the even rows of its
+// second, v_permlane32_swap the upper half of the first with the lower half of the second.  Fed the
+// same value twice, the two results hold, lane for lane, the value of the lane and of its partner
+// (lane ^ 16, lane ^ 32), in an order that does not matter to a commutative operation.
+__device__ __forceinline__ float max_xor16(float x) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float max_xor32(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_xor16(float x) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float sum_xor32(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 // Load 8 consecutive elements of storage type as binary32.
 template <int DT>
 __device__ __forceinline__ void load8(const void* base, size_t elem_off, float (&x)[8]);
