@@ -410,9 +410,10 @@ __global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   // LDS after the fold area: resident list (block, slot), the selector's exchange words, the count
+  const int kpad = (D.k + 3) & ~3;  // keeps what follows 16-byte aligned
   int* l_sel = reinterpret_cast<int*>(smem + WAVES * (D.G * (kMfmaD + 4) + 32));
-  int* l_slot = l_sel + D.k;
-  int* l_x = l_slot + D.k;
+  int* l_slot = l_sel + kpad;
+  int* l_x = l_slot + kpad;
   int* l_n = l_x + selector_lds_ints<WAVES>();
 
   u32x4 qreg[4];
@@ -732,7 +733,7 @@ int launch_select_attend(const Dims& D, const void* q, const float* scores, cons
   const int pairs = D.B * D.Hkv;
   if (pairs == 0) return SCOUT_OK;
   dim3 grid(P.nsplit, pairs), block(8 * kWave);
-  const size_t lds = mfma_smem_bytes(D, 8) + (2 * (size_t)D.k + selector_lds_ints<8>() + 4) * sizeof(int);
+  const size_t lds = mfma_smem_bytes(D, 8) + (2 * (size_t)((D.k + 3) & ~3) + selector_lds_ints<8>() + 4) * sizeof(int);
   const uint16_t* q16 = static_cast<const uint16_t*>(q);
   const uint16_t* k16 = static_cast<const uint16_t*>(k_pool);
   const uint16_t* v16 = static_cast<const uint16_t*>(v_pool);

@@ -48,6 +48,19 @@ __device__ __forceinline__ void wg_exchange(int v, int* lds, int& phase, int wav
   ++phase;
 }
 
+// Inclusive prefix sum over the 64 lanes on the vector ALU (DPP row shifts, then the two
+// row-to-row broadcasts), no LDS traffic.
+__device__ __forceinline__ int wave_inclusive_scan(int x) {
+  int v = x;
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);  // row_shr:1
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);  // row_shr:2
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);  // row_shr:4
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);  // row_shr:8
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
+  return v;
+}
+
 template <int WAVES, int KPL>
 struct Selector {
   int* lds;
@@ -135,13 +148,69 @@ struct Selector {
     // the largest T with  count(key >= T) >= kk  is the kk-th largest key
     uint32_t T = diff ? (all_and & ~(0xffffffffu >> __builtin_clz(diff))) : all_and;
     int n_ge = -1;
-    for (int bit = diff ? 31 - __builtin_clz(diff) : -1; bit >= 0; --bit) {
-      const uint32_t cand = T | (1u << bit);
-      const int c = count_ge(key, cand);
-      if (c >= kk) T = cand;
-      if (c == kk) {  // {key >= cand} is exactly the answer; lower bits cannot matter
-        n_ge = c;
-        break;
+    if constexpr (WAVES == 1) {
+      for (int bit = diff ? 31 - __builtin_clz(diff) : -1; bit >= 0; --bit) {
+        const uint32_t cand = T | (1u << bit);
+        const int c = count_ge(key, cand);
+        if (c >= kk) T = cand;
+        if (c == kk) {  // {key >= cand} is exactly the answer; lower bits cannot matter
+          n_ge = c;
+          break;
+        }
+      }
+    } else {
+      // Several waves: every exchange through LDS costs a barrier's latency, so the threshold is
+      // settled eight bits per round by a histogram.  Keys that agree with the bits found so far
+      // add one to the bin of their next digit (LDS atomics), one barrier, then every wave reads the
+      // 256 bins (four per lane), forms the suffix sums with a vector-ALU scan and picks the largest
+      // digit whose suffix count, added to the keys already known to be above, still reaches kk.
+      // Three bin arrays rotate: the one for the round after next is cleared while this round's is read.
+      int* hist = lds + 4 * WAVES;
+      const int tid = wave * kWave + lane_id();
+      for (int i = tid; i < 2 * 256; i += WAVES * kWave) hist[i] = 0;
+      __syncthreads();
+      int n_above = 0;  // keys whose settled bits are larger than T's
+      int bit = diff ? 31 - __builtin_clz(diff) : -1;
+      int round = 0;
+      while (bit >= 0) {
+        const int nbits = bit >= 7 ? 8 : bit + 1;
+        const int shift = bit - nbits + 1;
+        int* h = hist + (round % 3) * 256;
+        int* hz = hist + ((round + 2) % 3) * 256;
+        const uint32_t hi_mask = bit == 31 ? 0u : ~((2u << bit) - 1u);  // bits above this round's digit
+#pragma unroll
+        for (int r = 0; r < KPL; ++r) {
+          if (key[r] != 0u && (key[r] & hi_mask) == (T & hi_mask))
+            atomicAdd(&h[(key[r] >> shift) & ((1u << nbits) - 1u)], 1);
+        }
+        __syncthreads();
+        // every wave is past the previous round's reads now: clear the array of the round after next
+        for (int i = tid; i < 256; i += WAVES * kWave) hz[i] = 0;
+        // lane l owns digits 4l .. 4l+3
+        const int4 b4 = *reinterpret_cast<const int4*>(h + 4 * lane_id());
+        const int lane_sum = b4.x + b4.y + b4.z + b4.w;
+        const int incl = wave_inclusive_scan(lane_sum);
+        const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
+        // suffix counts (keys with digit >= d), plus the keys already above
+        const int s3 = n_above + total - incl + b4.w;
+        const int s2 = s3 + b4.z, s1 = s2 + b4.y, s0 = s1 + b4.x;
+        const int n_ok = (s0 >= kk) + (s1 >= kk) + (s2 >= kk) + (s3 >= kk);  // a prefix of the four
+        const uint64_t any = __ballot(n_ok > 0);
+        // some digit qualifies: digit 0 counts every candidate that matches so far
+        const int top_lane = 63 - __builtin_clzll(any);
+        const int top_ok = __builtin_amdgcn_readlane(n_ok, top_lane);
+        const int dstar = 4 * top_lane + top_ok - 1;
+        const int s_at = __builtin_amdgcn_readlane(top_ok == 1 ? s0 : top_ok == 2 ? s1 : top_ok == 3 ? s2 : s3, top_lane);
+        const int h_at = __builtin_amdgcn_readlane(top_ok == 1 ? b4.x : top_ok == 2 ? b4.y : top_ok == 3 ? b4.z : b4.w,
+                                                   top_lane);
+        T |= (uint32_t)dstar << shift;
+        n_above = s_at - h_at;
+        if (s_at == kk) {  // {key >= T} is exactly the answer; lower bits cannot matter
+          n_ge = kk;
+          break;
+        }
+        bit -= nbits;
+        ++round;
       }
     }
     uint32_t ge = 0;
@@ -194,6 +263,6 @@ __device__ __forceinline__ void load_keys(const Dims& D, const float* __restrict
 
 // LDS words a Selector needs for WAVES waves
 template <int WAVES>
-constexpr int selector_lds_ints() { return 4 * WAVES; }
+constexpr int selector_lds_ints() { return 4 * WAVES + 3 * 256; }
 
 }  // namespace scout

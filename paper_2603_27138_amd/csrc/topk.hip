@@ -10,7 +10,7 @@ __global__ __launch_bounds__(WAVES* kWave) void topk_kernel(
     Dims D, const float* __restrict__ scores, const int32_t* __restrict__ table,
     int32_t* __restrict__ sel_all, int32_t* __restrict__ sel_gpu, int32_t* __restrict__ slot_gpu,
     int32_t* __restrict__ n_gpu, int32_t* __restrict__ sel_host, int32_t* __restrict__ n_host) {
-  __shared__ int lds[4 * WAVES];
+  __shared__ __attribute__((aligned(16))) int lds[selector_lds_ints<WAVES>()];
   const int pair = blockIdx.x, b = pair / D.Hkv;
   const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int nb = num_blocks_of(D, b);
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(WAVES* kWave) void recall_kernel(
     Dims D, const float* __restrict__ scores, int32_t* __restrict__ table,
     int32_t* __restrict__ recall_blk, int32_t* __restrict__ recall_slot,
     int32_t* __restrict__ evict_blk, int32_t* __restrict__ n_recall) {
-  __shared__ int lds[4 * WAVES];
+  __shared__ __attribute__((aligned(16))) int lds[selector_lds_ints<WAVES>()];
   __shared__ int freed[kMaxK];  // slots of the evicted blocks, in ascending block order
   const int pair = blockIdx.x, b = pair / D.Hkv;
   const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
