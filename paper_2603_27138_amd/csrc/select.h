@@ -61,6 +61,19 @@ __device__ __forceinline__ int wave_inclusive_scan(int x) {
   return v;
 }
 
+// OR over the 64 lanes, result in every lane: rotations inside the 16-lane rows (DPP), then the
+// row exchanges, all on the vector ALU.
+__device__ __forceinline__ uint32_t wave_or(uint32_t v) {
+  v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x128, 0xf, 0xf, false);  // row_ror:8
+  v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x124, 0xf, 0xf, false);  // row_ror:4
+  v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x122, 0xf, 0xf, false);  // row_ror:2
+  v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x121, 0xf, 0xf, false);  // row_ror:1
+  auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+  v = r[0] | r[1];
+  r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return r[0] | r[1];
+}
+
 template <int WAVES, int KPL>
 struct Selector {
   int* lds;
@@ -105,11 +118,8 @@ struct Selector {
 
   // OR and AND of a per-lane word over the whole workgroup
   __device__ __forceinline__ void or_and(uint32_t vo, uint32_t va, uint32_t& all_or, uint32_t& all_and) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-      vo |= __shfl_xor(vo, off);
-      va &= __shfl_xor(va, off);
-    }
+    vo = wave_or(vo);
+    va = ~wave_or(~va);
     if (WAVES > 1) {
       int* buf = lds + (phase & 1) * WAVES;  // same alternation as wg_exchange
       int* buf2 = lds + 2 * WAVES + (phase & 1) * WAVES;
