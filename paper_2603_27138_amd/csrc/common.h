@@ -98,6 +98,33 @@ __device__ __forceinline__ float sum_xor32(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// The value that the partner lane holds, for the butterfly partner of level LEVEL: lane ^ 32 and
+// lane ^ 16 through the row swaps (own ^ both results leaves the partner's bits), lane ^ 15, ^ 7, ^ 3,
+// ^ 1 through the DPP mirrors inside a 16-lane row.  The XOR masks 32, 16, 15, 7, 3, 1 are
+// independent, so a reduction that walks the levels downwards covers the same lane groups as the
+// usual 32, 16, 8, 4, 2, 1 butterfly, and bit LEVEL of the lane index still tells the two partners
+// apart.  All on the vector ALU: no trip through the LDS crossbar.
+template <int LEVEL>
+__device__ __forceinline__ uint32_t partner_u32(uint32_t x) {
+  if constexpr (LEVEL == 5) {
+    const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    return r[0] ^ r[1] ^ x;
+  } else if constexpr (LEVEL == 4) {
+    const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+    return r[0] ^ r[1] ^ x;
+  } else {
+    constexpr int ctrl = LEVEL == 3 ? 0x140 /* row_mirror */ : LEVEL == 2 ? 0x141 /* row_half_mirror */
+                       : LEVEL == 1 ? 0x1B /* quad_perm 3,2,1,0 */ : 0xB1 /* quad_perm 1,0,3,2 */;
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, ctrl, 0xf, 0xf, false);
+  }
+}
+template <int LEVEL>
+__device__ __forceinline__ double partner_f64(double x) {
+  const uint64_t u = __double_as_longlong(x);
+  const uint32_t lo = partner_u32<LEVEL>((uint32_t)u), hi = partner_u32<LEVEL>((uint32_t)(u >> 32));
+  return __longlong_as_double(((uint64_t)hi << 32) | lo);
+}
+
 // Load 8 consecutive elements of storage type as binary32.
 template <int DT>
 __device__ __forceinline__ void load8(const void* base, size_t elem_off, float (&x)[8]);

@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_kernel(
   constexpr int LPB = 2 * DH / EPL;                // lanes per block
   constexpr int BPW = kWave / LPB;                 // blocks per wave-wide load
   constexpr int BLK_PER_WAVE = BPW * kScoreBatch * kScoreBatches;
-  static_assert(LPB >= 8 && LPB <= kWave, "layout");
+  static_assert(LPB >= 16 && LPB <= kWave, "layout");
 
   const int pair = blockIdx.y;
   const int b = pair / D.Hkv, g = pair % D.Hkv;
@@ -157,7 +157,8 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_kernel(
     }
   }
 
-  const bool hiA = (sub & (LPB / 2)) != 0, hiB = (sub & (LPB / 4)) != 0, hiC = (sub & (LPB / 8)) != 0;
+  constexpr int LV = LPB == 64 ? 5 : LPB == 32 ? 4 : LPB == 16 ? 3 : 2;  // top butterfly level inside an entry
+  const bool hiA = (lane >> LV) & 1, hiB = (lane >> (LV - 1)) & 1, hiC = (lane >> (LV - 2)) & 1;
   const int my_it = (hiA ? 4 : 0) + (hiB ? 2 : 0) + (hiC ? 1 : 0);
   const bool writer = (sub & (LPB / 8 - 1)) == 0;
 
@@ -192,23 +193,25 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_kernel(
         cur[it] = __builtin_bit_cast(
             u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff0 + ((t + 2) * kScoreBatch + it) * LOAD_STRIDE, 0, 0));
     }
-    // exchange-and-halve reduction across the LPB lanes of an entry
+    // exchange-and-halve reduction across the LPB lanes of an entry: at each of the first three
+    // levels a lane keeps half of its sums and hands the other half to its partner
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const double keep = hiA ? a[i + 4] : a[i], send = hiA ? a[i] : a[i + 4];
-      a[i] = keep + __shfl_xor(send, LPB / 2);
+      a[i] = keep + partner_f64<LV>(send);
     }
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const double keep = hiB ? a[i + 2] : a[i], send = hiB ? a[i] : a[i + 2];
-      a[i] = keep + __shfl_xor(send, LPB / 4);
+      a[i] = keep + partner_f64<LV - 1>(send);
     }
     {
       const double keep = hiC ? a[1] : a[0], send = hiC ? a[0] : a[1];
-      a[0] = keep + __shfl_xor(send, LPB / 8);
+      a[0] = keep + partner_f64<LV - 2>(send);
     }
-#pragma unroll
-    for (int off = LPB / 16; off >= 1; off >>= 1) a[0] += __shfl_xor(a[0], off);
+    if constexpr (LV - 3 >= 0) a[0] += partner_f64<(LV - 3 >= 0 ? LV - 3 : 0)>(a[0]);
+    if constexpr (LV - 4 >= 0) a[0] += partner_f64<(LV - 4 >= 0 ? LV - 4 : 0)>(a[0]);
+    if constexpr (LV - 5 >= 0) a[0] += partner_f64<(LV - 5 >= 0 ? LV - 5 : 0)>(a[0]);
     // a[0]: score of the block that load my_it of this batch brought to this lane group
     const int j = j_wave + (t * kScoreBatch + my_it) * BPW + grp;
     if (writer && j < D.max_blocks) scores[(size_t)pair * D.max_blocks + j] = j < nb ? (float)a[0] : -INFINITY;
