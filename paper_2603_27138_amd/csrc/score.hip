@@ -77,26 +77,36 @@ constexpr int kScoreBatches = 4;    // batches per wave
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-// One digest entry (min row + max row = 2*DH elements) is spread over LPB
-// consecutive lanes, 16 bytes per lane, so that each wave-wide load reads one
-// contiguous kilobyte of the digest cache.  A wave walks over kScoreBatches
-// batches of kScoreBatch such loads and keeps two batches in flight.  The loads
-// go through a buffer descriptor that ends at the pair's last valid block:
-// blocks beyond it read as zero without touching memory, so the issue path has
-// no branches.  Per batch every lane ends up with kScoreBatch partial sums (one
-// per load) that still have to be added across the LPB lanes of an entry; the
-// first three reduction steps exchange half of the remaining sums each, so the
-// batch needs 4+2+1 exchanges plus log2(LPB)-3 plain ones instead of
-// kScoreBatch*log2(LPB).
+// The score of a block is sum_c P_c*max_j[c] + N_c*min_j[c], with P_c (N_c) the sum over the group's
+// query heads of the positive (negative) parts of q[c]: the group is folded before the stream.
+//
+// Stream layout: a wave-wide load takes one 128-byte line from each of 8 consecutive digest entries
+// (8 lanes x 16 bytes per entry), and NL such loads cover the entries whole.  A lane therefore adds
+// the products of NL loads into one partial sum, and only the 8 lanes of an entry remain to be added
+// across lanes: three DPP steps.  Where a batch of kScoreBatch loads holds several 8-entry groups,
+// the first steps exchange half of the remaining sums each instead of adding all of them everywhere.
+// A wave walks over kScoreBatches batches and keeps two in flight.  The loads go through a buffer
+// descriptor that ends at the pair's last valid block: blocks beyond it read as zero without touching
+// memory, so the issue path has no branches.
+//
+// The fold of the query group is done once per workgroup (one channel and one sign per thread) and
+// handed to the lanes through LDS, while the first digest loads are in flight.  The pointers are
+// deliberately not marked restrict: loads that the compiler knows to be invariant float freely, and
+// here the order of issue matters (queries first, then batch by batch), because a wait for one load
+// is a wait for every load issued before it.
 template <int DT, int DH>
 __global__ __launch_bounds__(kScoreWaves* kWave) void score_kernel(
-    Dims D, const void* __restrict__ q, const void* __restrict__ digest, float* __restrict__ scores) {
+    Dims D, const void* q, const void* digest, float* scores) {
   constexpr int EPL = (DT == SCOUT_BF16) ? 8 : 4;  // elements per 16-byte load
   constexpr int ESZ = (DT == SCOUT_BF16) ? 2 : 4;
-  constexpr int LPB = 2 * DH / EPL;                // lanes per block
-  constexpr int BPW = kWave / LPB;                 // blocks per wave-wide load
-  constexpr int BLK_PER_WAVE = BPW * kScoreBatch * kScoreBatches;
-  static_assert(LPB >= 16 && LPB <= kWave, "layout");
+  constexpr int EB = 2 * DH * ESZ;                 // bytes per digest entry
+  constexpr int NL = EB / 128;                     // 128-byte lines per entry
+  constexpr int NG = kScoreBatch / NL;             // 8-entry groups per batch
+  constexpr int BLK_PER_WAVE = NG * 8 * kScoreBatches;
+  constexpr int NT = kScoreWaves * kWave;
+  static_assert(NL >= 2 && NL <= kScoreBatch && 2 * DH <= NT, "layout");
+
+  __shared__ __align__(16) double coef_lds[2][DH];  // [0]: N_c (goes with the min row), [1]: P_c
 
   const int pair = blockIdx.y;
   const int b = pair / D.Hkv, g = pair % D.Hkv;
@@ -104,116 +114,113 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int nb = num_blocks_of(D, b);
   const int j_wave = (blockIdx.x * kScoreWaves + wave) * BLK_PER_WAVE;
-  if (j_wave >= D.max_blocks) return;
+  const bool active = j_wave < D.max_blocks;  // a wave past the row still helps with the fold
 
-  const int sub = lane % LPB;  // position inside the digest entry
-  const int grp = lane / LPB;  // which of the BPW blocks of a load
-  const int e0 = sub * EPL;    // first element: [0, DH) min row, [DH, 2DH) max row
-  const bool is_max = e0 >= DH;
-  const int c0 = e0 % DH;
-
-  // the group's queries first, so that they arrive before the digest stream
-  u32x4 qraw[16];
-  const char* qbase = static_cast<const char*>(q) + (((size_t)b * D.Hq + g * D.G) * DH + c0) * ESZ;
+  // the group's queries first: thread t takes channel t % DH, negative (t < DH) or positive parts
+  const int fc = threadIdx.x % DH;
+  const bool fpos = threadIdx.x >= DH;
+  const char* qbase = static_cast<const char*>(q) + (((size_t)b * D.Hq + g * D.G) * DH + fc) * ESZ;
+  float qv[16];
 #pragma unroll
   for (int h = 0; h < 16; ++h) {  // rows beyond the group re-read its last row and are ignored below
     const int hs = h < D.G ? h : D.G - 1;
-    qraw[h] = *reinterpret_cast<const u32x4*>(qbase + (size_t)hs * DH * ESZ);
+    if (DT == SCOUT_BF16)
+      qv[h] = __uint_as_float((uint32_t) * reinterpret_cast<const uint16_t*>(qbase + (size_t)hs * DH * ESZ) << 16);
+    else
+      qv[h] = *reinterpret_cast<const float*>(qbase + (size_t)hs * DH * ESZ);
   }
 
-  const char* dpair = static_cast<const char*>(digest) + (size_t)pair * D.max_blocks * 2 * DH * ESZ;
+  const char* dpair = static_cast<const char*>(digest) + (size_t)pair * D.max_blocks * EB;
   const __amdgpu_buffer_rsrc_t rs =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(dpair), 0, nb * 2 * DH * ESZ, 0x00020000);
-  const int voff0 = ((j_wave + grp) * 2 * DH + e0) * ESZ;
-  constexpr int LOAD_STRIDE = BPW * 2 * DH * ESZ;  // bytes between consecutive loads of a wave (1 KiB)
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(dpair), 0, active ? nb * EB : 0, 0x00020000);
+  const int voff0 = (j_wave + (lane >> 3)) * EB + (lane & 7) * 16;
+  // byte offset of load `it` of batch `t`: group it / NL of the batch, line it % NL of its entries
+  auto load_off = [&](int t, int it) { return voff0 + (t * NG + it / NL) * 8 * EB + (it % NL) * 128; };
 
   u32x4 raw[2][kScoreBatch];
+  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int t = 0; t < 2; ++t)
+  for (int t = 0; t < 2; ++t) {
 #pragma unroll
     for (int it = 0; it < kScoreBatch; ++it)
-      raw[t][it] = __builtin_bit_cast(
-          u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff0 + (t * kScoreBatch + it) * LOAD_STRIDE, 0, 0));
-
-  // fold the query group: P_c = sum of positive parts (pairs with the max row),
-  // N_c = sum of negative parts (pairs with the min row)
-  double coef[EPL];
-#pragma unroll
-  for (int i = 0; i < EPL; ++i) coef[i] = 0.0;
-#pragma unroll
-  for (int h = 0; h < 16; ++h) {
-    float qv[8];
-    if (DT == SCOUT_BF16) {
-      qv[0] = bf16_lo(qraw[h][0]); qv[1] = bf16_hi(qraw[h][0]); qv[2] = bf16_lo(qraw[h][1]); qv[3] = bf16_hi(qraw[h][1]);
-      qv[4] = bf16_lo(qraw[h][2]); qv[5] = bf16_hi(qraw[h][2]); qv[6] = bf16_lo(qraw[h][3]); qv[7] = bf16_hi(qraw[h][3]);
-    } else {
-      qv[0] = __uint_as_float(qraw[h][0]); qv[1] = __uint_as_float(qraw[h][1]);
-      qv[2] = __uint_as_float(qraw[h][2]); qv[3] = __uint_as_float(qraw[h][3]);
-      qv[4] = qv[5] = qv[6] = qv[7] = 0.0f;
-    }
-    if (h < D.G) {
-#pragma unroll
-      for (int i = 0; i < EPL; ++i) coef[i] += (double)(is_max ? fmaxf(qv[i], 0.0f) : fminf(qv[i], 0.0f));
-    }
+      raw[t][it] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, load_off(t, it), 0, 0));
+    __builtin_amdgcn_sched_barrier(0);
   }
 
-  constexpr int LV = LPB == 64 ? 5 : LPB == 32 ? 4 : LPB == 16 ? 3 : 2;  // top butterfly level inside an entry
-  const bool hiA = (lane >> LV) & 1, hiB = (lane >> (LV - 1)) & 1, hiC = (lane >> (LV - 2)) & 1;
-  const int my_it = (hiA ? 4 : 0) + (hiB ? 2 : 0) + (hiC ? 1 : 0);
-  const bool writer = (sub & (LPB / 8 - 1)) == 0;
+  {
+    double f = 0.0;
+#pragma unroll
+    for (int h = 0; h < 16; ++h)
+      if (h < D.G) f += (double)(fpos ? fmaxf(qv[h], 0.0f) : fminf(qv[h], 0.0f));
+    if (threadIdx.x < 2 * DH) coef_lds[fpos ? 1 : 0][fc] = f;
+  }
+  __syncthreads();
+  // line u of an entry: min row for u < NL/2, max row after; channels (u % (NL/2))*128/ESZ + 8 lanes x EPL
+  double coef[NL][EPL];
+#pragma unroll
+  for (int u = 0; u < NL; ++u)
+#pragma unroll
+    for (int i = 0; i < EPL; ++i)
+      coef[u][i] = coef_lds[u >= NL / 2 ? 1 : 0][(u % (NL / 2)) * (128 / ESZ) + (lane & 7) * EPL + i];
+
+  const bool hi2 = (lane >> 2) & 1, hi1 = (lane >> 1) & 1;
+  const int my_g = NG == 4 ? (hi2 ? 2 : 0) + (hi1 ? 1 : 0) : NG == 2 ? (hi2 ? 1 : 0) : 0;
+  const bool writer = NG == 4 ? (lane & 1) == 0 : NG == 2 ? (lane & 3) == 0 : (lane & 7) == 0;
 
 #pragma unroll
   for (int t = 0; t < kScoreBatches; ++t) {
     u32x4(&cur)[kScoreBatch] = raw[t & 1];
-    double a[kScoreBatch];
+    double a[NG];
 #pragma unroll
-    for (int it = 0; it < kScoreBatch; ++it) {
+    for (int gq = 0; gq < NG; ++gq) {
       double acc = 0.0;
-      if (DT == SCOUT_BF16) {
-        acc = fma(coef[0], (double)bf16_lo(cur[it][0]), acc);
-        acc = fma(coef[1], (double)bf16_hi(cur[it][0]), acc);
-        acc = fma(coef[2 % EPL], (double)bf16_lo(cur[it][1]), acc);
-        acc = fma(coef[3 % EPL], (double)bf16_hi(cur[it][1]), acc);
-        acc = fma(coef[4 % EPL], (double)bf16_lo(cur[it][2]), acc);
-        acc = fma(coef[5 % EPL], (double)bf16_hi(cur[it][2]), acc);
-        acc = fma(coef[6 % EPL], (double)bf16_lo(cur[it][3]), acc);
-        acc = fma(coef[7 % EPL], (double)bf16_hi(cur[it][3]), acc);
-      } else {
-        acc = fma(coef[0], (double)__uint_as_float(cur[it][0]), acc);
-        acc = fma(coef[1], (double)__uint_as_float(cur[it][1]), acc);
-        acc = fma(coef[2], (double)__uint_as_float(cur[it][2]), acc);
-        acc = fma(coef[3], (double)__uint_as_float(cur[it][3]), acc);
+#pragma unroll
+      for (int u = 0; u < NL; ++u) {
+        const u32x4 w = cur[gq * NL + u];
+        if (DT == SCOUT_BF16) {
+          acc = fma(coef[u][0], (double)bf16_lo(w[0]), acc);
+          acc = fma(coef[u][1], (double)bf16_hi(w[0]), acc);
+          acc = fma(coef[u][2 % EPL], (double)bf16_lo(w[1]), acc);
+          acc = fma(coef[u][3 % EPL], (double)bf16_hi(w[1]), acc);
+          acc = fma(coef[u][4 % EPL], (double)bf16_lo(w[2]), acc);
+          acc = fma(coef[u][5 % EPL], (double)bf16_hi(w[2]), acc);
+          acc = fma(coef[u][6 % EPL], (double)bf16_lo(w[3]), acc);
+          acc = fma(coef[u][7 % EPL], (double)bf16_hi(w[3]), acc);
+        } else {
+          acc = fma(coef[u][0], (double)__uint_as_float(w[0]), acc);
+          acc = fma(coef[u][1], (double)__uint_as_float(w[1]), acc);
+          acc = fma(coef[u][2], (double)__uint_as_float(w[2]), acc);
+          acc = fma(coef[u][3], (double)__uint_as_float(w[3]), acc);
+        }
       }
-      a[it] = acc;
+      a[gq] = acc;
     }
     // the batch after next takes over this buffer
     if (t + 2 < kScoreBatches) {
 #pragma unroll
       for (int it = 0; it < kScoreBatch; ++it)
-        cur[it] = __builtin_bit_cast(
-            u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff0 + ((t + 2) * kScoreBatch + it) * LOAD_STRIDE, 0, 0));
+        cur[it] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, load_off(t + 2, it), 0, 0));
     }
-    // exchange-and-halve reduction across the LPB lanes of an entry: at each of the first three
-    // levels a lane keeps half of its sums and hands the other half to its partner
+    // add across the 8 lanes of an entry; with several groups the first steps exchange and halve
+    if constexpr (NG == 4) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const double keep = hiA ? a[i + 4] : a[i], send = hiA ? a[i] : a[i + 4];
-      a[i] = keep + partner_f64<LV>(send);
+      for (int i = 0; i < 2; ++i) {
+        const double keep = hi2 ? a[i + 2] : a[i], send = hi2 ? a[i] : a[i + 2];
+        a[i] = keep + partner_f64<2>(send);
+      }
+      const double keep = hi1 ? a[1] : a[0], send = hi1 ? a[0] : a[1];
+      a[0] = keep + partner_f64<1>(send);
+    } else if constexpr (NG == 2) {
+      const double keep = hi2 ? a[1] : a[0], send = hi2 ? a[0] : a[1];
+      a[0] = keep + partner_f64<2>(send);
+      a[0] += partner_f64<1>(a[0]);
+    } else {
+      a[0] += partner_f64<2>(a[0]);
+      a[0] += partner_f64<1>(a[0]);
     }
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const double keep = hiB ? a[i + 2] : a[i], send = hiB ? a[i] : a[i + 2];
-      a[i] = keep + partner_f64<LV - 1>(send);
-    }
-    {
-      const double keep = hiC ? a[1] : a[0], send = hiC ? a[0] : a[1];
-      a[0] = keep + partner_f64<LV - 2>(send);
-    }
-    if constexpr (LV - 3 >= 0) a[0] += partner_f64<(LV - 3 >= 0 ? LV - 3 : 0)>(a[0]);
-    if constexpr (LV - 4 >= 0) a[0] += partner_f64<(LV - 4 >= 0 ? LV - 4 : 0)>(a[0]);
-    if constexpr (LV - 5 >= 0) a[0] += partner_f64<(LV - 5 >= 0 ? LV - 5 : 0)>(a[0]);
-    // a[0]: score of the block that load my_it of this batch brought to this lane group
-    const int j = j_wave + (t * kScoreBatch + my_it) * BPW + grp;
+    a[0] += partner_f64<0>(a[0]);
+    // a[0]: score of entry lane/8 of group my_g of this batch
+    const int j = j_wave + (t * NG + my_g) * 8 + (lane >> 3);
     if (writer && j < D.max_blocks) scores[(size_t)pair * D.max_blocks + j] = j < nb ? (float)a[0] : -INFINITY;
   }
 }
@@ -234,8 +241,8 @@ int launch_digest(const Dims& D, int dtype, const void* k_blocks, void* digest, 
 
 int launch_score(const Dims& D, int dtype, const void* q, const void* digest, float* scores,
                  hipStream_t st) {
-  const int epl = dtype == SCOUT_BF16 ? 8 : 4;
-  const int blocks_per_wg = (kWave / (2 * D.d / epl)) * kScoreBatch * kScoreBatches * kScoreWaves;
+  const int lines = 2 * D.d * (dtype == SCOUT_BF16 ? 2 : 4) / 128;  // 128-byte lines per digest entry
+  const int blocks_per_wg = kScoreBatch / lines * 8 * kScoreBatches * kScoreWaves;
   dim3 grid((D.max_blocks + blocks_per_wg - 1) / blocks_per_wg, D.B * D.Hkv);
   dim3 block(kScoreWaves * kWave);
   if (grid.x == 0 || grid.y == 0) return SCOUT_OK;
