@@ -191,3 +191,20 @@ def recall_plan(s: np.ndarray, k: int, table: np.ndarray):
     eb = np.full(max(k, 1), -1, dtype=np.int32)
     n = _L().orc_recall_plan(_dp(s), len(s), int(k), _ip(table), _ip(rb), _ip(rs), _ip(eb))
     return rb[:k], rs[:k], eb[:k], n
+
+
+def append(dtype: int, S: int, ctx_len: int, k_new: np.ndarray, v_new: np.ndarray, new_slot: int,
+           dig: np.ndarray, table: np.ndarray, k_pool: np.ndarray, v_pool: np.ndarray) -> int:
+    """Decode append for one pair; dig [max_blocks][2][d], table [max_blocks] and the pools
+    [n_slots][S][d] are updated in place.  Returns the new context length."""
+    d = k_new.shape[-1]
+    for a in (k_new, v_new, dig, k_pool, v_pool):
+        assert a.flags["C_CONTIGUOUS"] and a.dtype == (np.float32 if dtype == F32 else np.uint16)
+    assert table.dtype == np.int32 and table.flags["C_CONTIGUOUS"]
+    assert dig.shape == (len(table), 2, d) and k_pool.shape[1:] == (S, d) and v_pool.shape == k_pool.shape
+    L = _L()
+    L.orc_append.restype = ctypes.c_int
+    L.orc_append.argtypes = [ctypes.c_int] * 5 + [ctypes.c_void_p] * 2 + [ctypes.c_int] + [ctypes.c_void_p] * 4 + [ctypes.c_long]
+    return L.orc_append(int(dtype), int(S), int(d), len(table), int(ctx_len), k_new.ctypes.data,
+                        v_new.ctypes.data, int(new_slot), dig.ctypes.data, table.ctypes.data,
+                        k_pool.ctypes.data, v_pool.ctypes.data, len(k_pool))

@@ -22,7 +22,9 @@
  * against a brute-force sort; partial attention against a library dense
  * attention routine when the selection covers everything, against closed
  * forms and against weight normalisation; merge against attention over the
- * union of a split; recall plan against brute-force set arithmetic.
+ * union of a split; recall plan against brute-force set arithmetic; decode
+ * append against the digest and the tiles of the finished sequence built in
+ * one piece.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -256,4 +258,41 @@ int orc_recall_plan(const double* s, int nb, int k, int* table,
   for (int i = n; i < k; ++i) { recall_blk[i] = -1; recall_slot[i] = -1; evict_blk[i] = -1; }
   free(rank);
   return n;
+}
+
+/*
+ * Decode append for one pair (the digest of Sec. 2.2 kept up to date while the
+ * sequence of Sec. 3.2 grows by the token that decode just produced).
+ * The token takes position t = ctx_len, row r = t % S of block j = t / S:
+ *   - r == 0 opens block j: its table entry becomes new_slot (>= 0: a pool
+ *     slot on the GPU, -1: the block lives on the host) and both digest rows
+ *     become the key; otherwise a digest element is replaced only where the
+ *     key is strictly smaller (row 0) or strictly larger (row 1);
+ *   - if the block's table entry is a slot in [0, n_slots), the key and the
+ *     value are written to row r of that slot's K and V tiles.
+ * dig is [max_blocks][2][d], table [max_blocks], the pools [n_slots][S][d].
+ * Returns the new length: ctx_len + 1, or ctx_len unchanged (and nothing
+ * written) when the sequence already fills max_blocks blocks.
+ */
+int orc_append(int dtype, int S, int d, int max_blocks, int ctx_len, const void* k_new,
+               const void* v_new, int new_slot, void* dig, int* table, void* k_pool,
+               void* v_pool, long n_slots) {
+  if (ctx_len >= max_blocks * S) return ctx_len;
+  size_t es = esize(dtype);
+  int j = ctx_len / S, r = ctx_len % S;
+  if (r == 0) table[j] = new_slot;
+  char* dmin = (char*)dig + ((size_t)j * 2 + 0) * d * es;
+  char* dmax = (char*)dig + ((size_t)j * 2 + 1) * d * es;
+  for (int c = 0; c < d; ++c) {
+    const char* kc = (const char*)k_new + (size_t)c * es;
+    if (r == 0 || ld(k_new, dtype, c) < ld(dmin, dtype, c)) memcpy(dmin + (size_t)c * es, kc, es);
+    if (r == 0 || ld(k_new, dtype, c) > ld(dmax, dtype, c)) memcpy(dmax + (size_t)c * es, kc, es);
+  }
+  int slot = table[j];
+  if (slot >= 0 && slot < n_slots) {
+    size_t row = ((size_t)slot * S + r) * d * es;
+    memcpy((char*)k_pool + row, k_new, (size_t)d * es);
+    memcpy((char*)v_pool + row, v_new, (size_t)d * es);
+  }
+  return ctx_len + 1;
 }
