@@ -167,6 +167,31 @@ def select_only(st, i):
                      s.n_host, st.ws)
 
 
+def append_setup(st):
+    """Private cache state for timing the decode append: lengths that leave room for every timed call,
+    a pool with one slot per pair (each block a pair opens during the run reuses it)."""
+    torch, cfg, s0 = st.torch, st.cfg, st.sets[0]
+    a = LayerSet()
+    npairs = cfg.B * cfg.Hkv
+    a.ctx_len = torch.full((cfg.B,), cfg.S * (cfg.max_blocks // 2) + cfg.S // 4, dtype=torch.int32, device="cuda")
+    a.digest, a.block_table = s0.digest.clone(), s0.block_table.clone()
+    a.k_pool = torch.zeros(npairs, cfg.S, cfg.d, dtype=torch.bfloat16, device="cuda")
+    a.v_pool = torch.zeros_like(a.k_pool)
+    a.block_table[:, :, cfg.max_blocks // 2] = torch.arange(npairs, dtype=torch.int32, device="cuda").view(cfg.B, cfg.Hkv)
+    a.new_slot = torch.arange(npairs, dtype=torch.int32, device="cuda").view(cfg.B, cfg.Hkv)
+    a.k_new = torch.randn(cfg.B, cfg.Hkv, cfg.d, device="cuda").to(torch.bfloat16)
+    a.v_new = torch.randn(cfg.B, cfg.Hkv, cfg.d, device="cuda").to(torch.bfloat16)
+    a.n_slots = npairs
+    st.app = a
+    st.app_p = st.B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, st.B.BF16, cfg.max_blocks, cfg.k, a.ctx_len)
+
+
+def append_only(st, i):
+    a = st.app
+    st.B.append_token(st.app_p, a.ctx_len, a.k_new, a.v_new, a.new_slot, a.digest, a.block_table, a.k_pool,
+                      a.v_pool, a.n_slots)
+
+
 def timed(st, fn, n):
     """Microseconds per call: HIP events on the stream the kernels are launched on."""
     torch = st.torch
@@ -215,6 +240,11 @@ def main():
     us_attn = timed(st, attn_only, args.steps)
     us_score = timed(st, score_only, args.steps)
     us_select = timed(st, select_only, args.steps)
+    append_setup(st)
+    assert cfg.S * (cfg.max_blocks // 2) + args.steps + args.warmup < cfg.S * cfg.max_blocks
+    for i in range(args.warmup):
+        append_only(st, i)
+    us_append = timed(st, append_only, args.steps)
 
     tile_bytes = 2 * cfg.S * cfg.d * 2                       # K + V tile of one block, bf16
     n_blocks = int(st.sets[0].n_gpu.sum().item())
@@ -247,7 +277,8 @@ def main():
                    "host_resident": cfg.p_host, "layer_copies": len(st.sets), "gpu_blocks_per_step": n_blocks},
         "kv_gbps": round(attn_gbps, 1),
         "kernels_us": {"score_blocks": round(us_score, 3), "select_topk": round(us_select, 3),
-                       "attn_mfma_kernel": round(us_attn_kernel, 3), "sparse_decode_attn": round(us_attn, 3)},
+                       "attn_mfma_kernel": round(us_attn_kernel, 3), "sparse_decode_attn": round(us_attn, 3),
+                       "append_token": round(us_append, 3)},
         "score_gbps": round(score_gbps, 1),
         "roofline": {"bound": "hbm", "kernel": "attn_mfma_kernel", "achieved": round(attn_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),

@@ -87,6 +87,34 @@ int scout_workspace_bytes(const scout_problem* p, size_t* bytes);
 int build_digests(const scout_problem* p, const void* k_blocks, void* digest, void* stream);
 
 /*
+ * Decode append (the digest of Sec. 2.2 kept current while the cache of
+ * Sec. 3.2 grows): the key and value of the token that decode just produced
+ * join every KV head of every sequence.  With t = ctx_len[b] before the call,
+ * the token takes row r = t % S of block j = t / S:
+ *   - r == 0 opens block j: block_table[b][g][j] = new_slot[b][g] (a pool slot,
+ *     or -1 when the caller keeps the new block on the host) and both digest
+ *     rows become the key; otherwise a digest element changes only where the
+ *     key is strictly smaller (min row) or strictly larger (max row);
+ *   - if the block's table entry is a slot in [0, n_slots), the key and value
+ *     rows are written to row r of that slot's K and V tiles (a host-resident
+ *     tail block is the caller's to extend);
+ *   - ctx_len[b] becomes t + 1.
+ * A sequence that already fills max_blocks blocks is left untouched.
+ *   ctx_len      i32 [B]              in/out; the lengths to advance (normally
+ *                                     the array p->ctx_len points to, which this
+ *                                     call does not read through p)
+ *   k_new, v_new e   [B][Hkv][d]
+ *   new_slot     i32 [B][Hkv]         read only for sequences with r == 0
+ *   digest       e   [B][Hkv][max_blocks][2][d]   in/out
+ *   block_table  i32 [B][Hkv][max_blocks]         in/out
+ *   k_pool, v_pool e [n_slots][S][d]              in/out
+ * Copies and comparisons only; the result is exact.
+ */
+int append_token(const scout_problem* p, int32_t* ctx_len, const void* k_new, const void* v_new,
+                 const int32_t* new_slot, void* digest, int32_t* block_table, void* k_pool,
+                 void* v_pool, int64_t n_slots, void* stream);
+
+/*
  * Block importance (Sec. 2.2, Sec. 3.2, Alg. 1 TopK argument): for each pair
  * and block j, sum over the G query heads of the group and over channels c of
  * max(q[c]*min_j[c], q[c]*max_j[c]).  Unscaled.  Accumulated in binary64 and

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libscout.so")
 F32, BF16 = 0, 1
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 
-EXPORTS = ["scout_version", "scout_strerror", "scout_workspace_bytes", "build_digests", "score_blocks",
+EXPORTS = ["scout_version", "scout_strerror", "scout_workspace_bytes", "build_digests", "append_token", "score_blocks",
            "select_topk", "sparse_decode_attn", "merge_partials", "periodic_recall",
            "scout_layer_step", "scout_set_attn_mode", "scout_calib_copy", "scout_attn_partials"]
 
@@ -57,6 +57,7 @@ def lib():
         L.scout_set_attn_mode.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
         L.scout_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
         L.build_digests.argtypes = [pp, vp, vp, vp]
+        L.append_token.argtypes = [pp] + [vp] * 8 + [i64, vp]
         L.score_blocks.argtypes = [pp, vp, vp, vp, vp, sz, vp]
         L.select_topk.argtypes = [pp] + [vp] * 9 + [sz, vp]
         L.sparse_decode_attn.argtypes = [pp, vp, vp, vp, i64] + [vp] * 7 + [sz, vp]
@@ -126,6 +127,12 @@ def calib_copy(src: torch.Tensor, dst: torch.Tensor):
 
 def build_digests(p: Problem, k_blocks, digest):
     _check("build_digests", lib().build_digests(ctypes.byref(p), _ptr(k_blocks), _ptr(digest), _stream()))
+
+
+def append_token(p: Problem, ctx_len, k_new, v_new, new_slot, digest, block_table, k_pool, v_pool, n_slots):
+    _check("append_token", lib().append_token(ctypes.byref(p), _ptr(ctx_len), _ptr(k_new), _ptr(v_new),
+                                              _ptr(new_slot), _ptr(digest), _ptr(block_table), _ptr(k_pool),
+                                              _ptr(v_pool), int(n_slots), _stream()))
 
 
 def score_blocks(p: Problem, q, digest, scores, ws):

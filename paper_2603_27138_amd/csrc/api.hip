@@ -10,6 +10,8 @@ namespace scout {
 
 int launch_digest(const Dims&, int, const void*, void*, hipStream_t);
 int launch_score(const Dims&, int, const void*, const void*, float*, hipStream_t);
+int launch_append(const Dims&, int, int32_t*, const void*, const void*, const int32_t*, void*, int32_t*, void*, void*,
+                  long long, hipStream_t);
 int launch_topk(const Dims&, const float*, const int32_t*, int32_t*, int32_t*, int32_t*, int32_t*,
                 int32_t*, int32_t*, hipStream_t);
 int launch_recall(const Dims&, const float*, int32_t*, int32_t*, int32_t*, int32_t*, int32_t*,
@@ -225,6 +227,21 @@ int build_digests(const scout_problem* p, const void* k_blocks, void* digest, vo
   if (k_blocks == nullptr || digest == nullptr || !aligned16(k_blocks) || !aligned16(digest))
     return SCOUT_EINVAL;
   return launch_digest(D, p->dtype, k_blocks, digest, static_cast<hipStream_t>(stream));
+}
+
+int append_token(const scout_problem* p, int32_t* ctx_len, const void* k_new, const void* v_new,
+                 const int32_t* new_slot, void* digest, int32_t* block_table, void* k_pool, void* v_pool,
+                 int64_t n_slots, void* stream) {
+  Dims D;
+  int rc = check_problem(p, &D);
+  if (rc != SCOUT_OK) return rc;
+  if (!ctx_len || !k_new || !v_new || !new_slot || !digest || !block_table || !k_pool || !v_pool)
+    return SCOUT_EINVAL;
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(digest) || !aligned16(k_pool) || !aligned16(v_pool))
+    return SCOUT_EINVAL;
+  if (n_slots < 0) return SCOUT_EINVAL;
+  return launch_append(D, p->dtype, ctx_len, k_new, v_new, new_slot, digest, block_table, k_pool, v_pool,
+                       n_slots, static_cast<hipStream_t>(stream));
 }
 
 int score_blocks(const scout_problem* p, const void* q, const void* digest, float* scores, void* ws,
