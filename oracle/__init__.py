@@ -208,3 +208,20 @@ def append(dtype: int, S: int, ctx_len: int, k_new: np.ndarray, v_new: np.ndarra
     return L.orc_append(int(dtype), int(S), int(d), len(table), int(ctx_len), k_new.ctypes.data,
                         v_new.ctypes.data, int(new_slot), dig.ctypes.data, table.ctypes.data,
                         k_pool.ctypes.data, v_pool.ctypes.data, len(k_pool))
+
+
+def recall_fetch(src_k: np.ndarray, src_v: np.ndarray, recall_blk, recall_slot, n: int,
+                 k_pool: np.ndarray, v_pool: np.ndarray) -> int:
+    """Copies the tiles a recall plan names from one pair's blocks [max_blocks][S][d] into the pools
+    [n_slots][S][d] (updated in place).  Returns the number of tiles copied."""
+    for a in (src_k, src_v, k_pool, v_pool):
+        assert a.flags["C_CONTIGUOUS"] and a.dtype == src_k.dtype
+    mb, S, d = src_k.shape
+    assert src_v.shape == src_k.shape and k_pool.shape[1:] == (S, d) and v_pool.shape == k_pool.shape
+    rb = np.ascontiguousarray(recall_blk, dtype=np.int32)
+    rs = np.ascontiguousarray(recall_slot, dtype=np.int32)
+    L = _L()
+    L.orc_recall_fetch.restype = ctypes.c_int
+    L.orc_recall_fetch.argtypes = [ctypes.c_int] * 4 + [ctypes.c_void_p] * 4 + [ctypes.c_int] + [ctypes.c_void_p] * 2 + [ctypes.c_long]
+    return L.orc_recall_fetch(_dtype_code(src_k), S, d, mb, src_k.ctypes.data, src_v.ctypes.data, rb.ctypes.data,
+                              rs.ctypes.data, int(n), k_pool.ctypes.data, v_pool.ctypes.data, len(k_pool))

@@ -24,7 +24,7 @@
  * forms and against weight normalisation; merge against attention over the
  * union of a split; recall plan against brute-force set arithmetic; decode
  * append against the digest and the tiles of the finished sequence built in
- * one piece.
+ * one piece; recall transfer against plain slicing of the source array.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -295,4 +295,28 @@ int orc_append(int dtype, int S, int d, int max_blocks, int ctx_len, const void*
     memcpy((char*)v_pool + row, v_new, (size_t)d * es);
   }
   return ctx_len + 1;
+}
+
+/*
+ * Data movement of a periodic recall for one pair (Sec. 3.4: the blocks the
+ * plan names come back from host memory into the pool slots that the plan
+ * freed).  src_k / src_v hold the pair's blocks by logical index,
+ * [max_blocks][S][d]; entry i < n of the plan copies the K and V tiles of
+ * block recall_blk[i] into slot recall_slot[i] of the pools [n_slots][S][d].
+ * Entries outside [0, max_blocks) x [0, n_slots) are skipped.  Returns the
+ * number of tiles copied (K and V count as one).
+ */
+int orc_recall_fetch(int dtype, int S, int d, int max_blocks, const void* src_k, const void* src_v,
+                     const int* recall_blk, const int* recall_slot, int n, void* k_pool,
+                     void* v_pool, long n_slots) {
+  size_t tile = (size_t)S * d * esize(dtype);
+  int copied = 0;
+  for (int i = 0; i < n; ++i) {
+    int blk = recall_blk[i], slot = recall_slot[i];
+    if (blk < 0 || blk >= max_blocks || slot < 0 || slot >= n_slots) continue;
+    memcpy((char*)k_pool + (size_t)slot * tile, (const char*)src_k + (size_t)blk * tile, tile);
+    memcpy((char*)v_pool + (size_t)slot * tile, (const char*)src_v + (size_t)blk * tile, tile);
+    ++copied;
+  }
+  return copied;
 }

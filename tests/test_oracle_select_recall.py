@@ -9,6 +9,7 @@ import numpy as np
 import pytest
 
 import oracle
+from paper_2603_27138_amd import workload as W
 
 
 def brute_topk(s, k):
@@ -116,3 +117,62 @@ def test_recall_plan_matches_brute_force(seed, nb, k, n_res):
     assert oracle.recall_plan(s, k, t3)[3] == 0 or n_res < min(k, nb)
     if n_res >= min(k, nb):
         assert (t3 == t2).all()
+
+
+# ---------------------------------------------------------------- recall data movement (Sec. 3.4)
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_recall_fetch_is_plain_slicing(dtype):
+    rng = np.random.default_rng(41)
+    mb, S, d, n_slots = 12, 16, 8, 20
+    st = np.float32 if dtype == "f32" else np.uint16
+    def arr(shape):
+        return W.to_storage(rng.standard_normal(shape).astype(np.float32), dtype)
+    src_k, src_v = arr((mb, S, d)), arr((mb, S, d))
+    kp, vp = arr((n_slots, S, d)), arr((n_slots, S, d))
+    kp0, vp0 = kp.copy(), vp.copy()
+    blk = np.array([3, 7, 11, 0, -1, -1], dtype=np.int32)
+    slot = np.array([19, 2, 5, 8, -1, -1], dtype=np.int32)
+    assert oracle.recall_fetch(src_k, src_v, blk, slot, 4, kp, vp) == 4
+    assert kp.dtype == st
+    for b, s in zip(blk[:4], slot[:4]):
+        assert np.array_equal(kp[s], src_k[b]) and np.array_equal(vp[s], src_v[b])
+    rest = [s for s in range(n_slots) if s not in set(slot[:4].tolist())]
+    assert np.array_equal(kp[rest], kp0[rest]) and np.array_equal(vp[rest], vp0[rest])
+    # K goes to the K pool and V to the V pool, not the other way round
+    assert not np.array_equal(kp[19], src_v[3])
+
+
+def test_recall_fetch_skips_what_is_out_of_range_and_respects_n():
+    mb, S, d, n_slots = 4, 2, 2, 3
+    src_k = np.arange(mb * S * d, dtype=np.float32).reshape(mb, S, d)
+    src_v = -src_k
+    kp = np.full((n_slots, S, d), 99.0, dtype=np.float32)
+    vp = kp.copy()
+    blk = np.array([1, 4, -1, 2, 3], dtype=np.int32)     # 4 and -1 are no blocks
+    slot = np.array([0, 1, 1, 3, 2], dtype=np.int32)     # 3 is no slot
+    assert oracle.recall_fetch(src_k, src_v, blk, slot, 4, kp, vp) == 1   # entry 4 is beyond n
+    assert np.array_equal(kp[0], src_k[1]) and np.array_equal(vp[0], src_v[1])
+    assert (kp[1:] == 99.0).all() and (vp[1:] == 99.0).all()
+
+
+def test_recall_plan_then_fetch_makes_every_selected_block_resident_with_its_own_rows():
+    # after plan + transfer, a pool read through the updated table returns the logical block's rows
+    rng = np.random.default_rng(43)
+    mb, S, d, k = 24, 4, 4, 6
+    src_k = rng.standard_normal((mb, S, d)).astype(np.float32)
+    src_v = rng.standard_normal((mb, S, d)).astype(np.float32)
+    resident = rng.permutation(mb)[:10]
+    table = np.full(mb, -1, dtype=np.int32)
+    table[resident] = rng.permutation(10).astype(np.int32)
+    kp = np.zeros((10, S, d), dtype=np.float32)
+    vp = np.zeros((10, S, d), dtype=np.float32)
+    kp[table[resident]], vp[table[resident]] = src_k[resident], src_v[resident]
+    s = rng.standard_normal(mb)
+    rb, rs, eb, n = oracle.recall_plan(s, k, table)
+    assert oracle.recall_fetch(src_k, src_v, rb, rs, n, kp, vp) == n
+    for j in range(mb):
+        if table[j] >= 0:
+            assert np.array_equal(kp[table[j]], src_k[j]) and np.array_equal(vp[table[j]], src_v[j])
+    top = set(np.argsort(-s, kind="stable")[:k].tolist())
+    assert all(table[j] >= 0 for j in top)
