@@ -192,6 +192,43 @@ def append_only(st, i):
                       a.v_pool, a.n_slots)
 
 
+def fetch_setup(st, per_pair=8):
+    """A recall of `per_pair` blocks per pair (12 % of the budget, the turnover the paper reports
+    between recalls) read from a pinned host copy of every block into a private pool."""
+    torch, cfg, wl = st.torch, st.cfg, st.wl
+    f = LayerSet()
+    shape = (cfg.B, cfg.Hkv, cfg.max_blocks, cfg.S, cfg.d)
+    f.k = torch.zeros(shape, dtype=torch.int16).pin_memory()
+    f.v = torch.zeros(shape, dtype=torch.int16).pin_memory()
+    kb, vb = f.k.numpy().view(np.uint16), f.v.numpy().view(np.uint16)
+    for (b, g) in wl.K:
+        kb[b, g] = wl.blocks_padded(b, g, "K")
+        vb[b, g] = wl.blocks_padded(b, g, "V")
+    rng = np.random.default_rng(5)
+    npairs = cfg.B * cfg.Hkv
+    f.plans = []
+    for _ in range(8):   # rotating plans: different host blocks each call, so no call re-reads the last one's
+        blk = np.full((cfg.B, cfg.Hkv, cfg.k), -1, dtype=np.int32)
+        slot = np.full((cfg.B, cfg.Hkv, cfg.k), -1, dtype=np.int32)
+        for pi in range(npairs):
+            b, g = divmod(pi, cfg.Hkv)
+            blk[b, g, :per_pair] = np.sort(rng.permutation(cfg.max_blocks)[:per_pair])
+            slot[b, g, :per_pair] = pi * per_pair + np.arange(per_pair)
+        f.plans.append((torch.from_numpy(blk).cuda(), torch.from_numpy(slot).cuda()))
+    f.n = torch.full((cfg.B, cfg.Hkv), per_pair, dtype=torch.int32, device="cuda")
+    f.n_slots = npairs * per_pair
+    f.k_pool = torch.zeros(f.n_slots, cfg.S, cfg.d, dtype=torch.bfloat16, device="cuda")
+    f.v_pool = torch.zeros_like(f.k_pool)
+    f.bytes = npairs * per_pair * 2 * cfg.S * cfg.d * 2
+    st.fetch = f
+
+
+def fetch_only(st, i):
+    f = st.fetch
+    blk, slot = f.plans[i % len(f.plans)]
+    st.B.recall_fetch(st.probs[0], f.k, f.v, blk, slot, f.n, f.k_pool, f.v_pool, f.n_slots)
+
+
 def timed(st, fn, n):
     """Microseconds per call: HIP events on the stream the kernels are launched on."""
     torch = st.torch
@@ -245,6 +282,10 @@ def main():
     for i in range(args.warmup):
         append_only(st, i)
     us_append = timed(st, append_only, args.steps)
+    fetch_setup(st)
+    for i in range(3):
+        fetch_only(st, i)
+    us_fetch = timed(st, fetch_only, max(8, args.steps // 10))
 
     tile_bytes = 2 * cfg.S * cfg.d * 2                       # K + V tile of one block, bf16
     n_blocks = int(st.sets[0].n_gpu.sum().item())
@@ -278,7 +319,8 @@ def main():
         "kv_gbps": round(attn_gbps, 1),
         "kernels_us": {"score_blocks": round(us_score, 3), "select_topk": round(us_select, 3),
                        "attn_mfma_kernel": round(us_attn_kernel, 3), "sparse_decode_attn": round(us_attn, 3),
-                       "append_token": round(us_append, 3)},
+                       "append_token": round(us_append, 3), "recall_fetch": round(us_fetch, 1)},
+        "recall_h2d_gbps": round(st.fetch.bytes / us_fetch * 1e-3, 1),
         "score_gbps": round(score_gbps, 1),
         "roofline": {"bound": "hbm", "kernel": "attn_mfma_kernel", "achieved": round(attn_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),

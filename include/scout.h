@@ -16,7 +16,7 @@
  *
  * Conventions common to every entry point
  *   - Every pointer except `const scout_problem*` is DEVICE memory owned by
- *     the caller.  The library allocates nothing, frees nothing and keeps no
+ *     the caller (recall_fetch alone also takes pinned host memory).  The library allocates nothing, frees nothing and keeps no
  *     pointer after a call returns.  Scratch comes from the caller's
  *     workspace (`ws`, at least scout_workspace_bytes() bytes, 256-byte
  *     aligned).
@@ -207,6 +207,26 @@ int periodic_recall(const scout_problem* p, const void* q, const void* digest,
                     int32_t* block_table, int32_t* recall_blk, int32_t* recall_slot,
                     int32_t* evict_blk, int32_t* n_recall, void* ws, size_t ws_bytes,
                     void* stream);
+
+/*
+ * Data movement of a periodic recall (Sec. 3.4: the planned blocks return from
+ * host memory after the layer's attention, off the critical path).  For every
+ * pair and every i < n_recall, the K and V tiles of block recall_blk[i] are
+ * copied from the source arrays into pool slot recall_slot[i]; the three plan
+ * arrays are the ones periodic_recall wrote.  Launch it on a stream of its
+ * own to keep it off the compute stream; the recalled blocks are first read by
+ * the next step's attention.
+ *   src_k, src_v  e [B][Hkv][max_blocks][S][d]   every block that may be
+ *                 recalled, by logical index, in memory the GPU can address:
+ *                 PINNED HOST memory (hipHostMalloc; read over the host link
+ *                 by the kernel itself) or device memory
+ *   recall_blk, recall_slot  i32 [B][Hkv][k];  n_recall  i32 [B][Hkv]   DEVICE
+ *   k_pool, v_pool  e [n_slots][S][d]   in/out
+ * Entries outside [0, max_blocks) x [0, n_slots) are skipped.  Pure copies.
+ */
+int recall_fetch(const scout_problem* p, const void* src_k, const void* src_v,
+                 const int32_t* recall_blk, const int32_t* recall_slot, const int32_t* n_recall,
+                 void* k_pool, void* v_pool, int64_t n_slots, void* stream);
 
 /*
  * One whole layer-step (Sec. 3.2, steps 1-4 above) with the fewest launches:

@@ -20,7 +20,7 @@ F32, BF16 = 0, 1
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 
 EXPORTS = ["scout_version", "scout_strerror", "scout_workspace_bytes", "build_digests", "append_token", "score_blocks",
-           "select_topk", "sparse_decode_attn", "merge_partials", "periodic_recall",
+           "select_topk", "sparse_decode_attn", "merge_partials", "periodic_recall", "recall_fetch",
            "scout_layer_step", "scout_set_attn_mode", "scout_calib_copy", "scout_attn_partials"]
 
 
@@ -63,6 +63,7 @@ def lib():
         L.sparse_decode_attn.argtypes = [pp, vp, vp, vp, i64] + [vp] * 7 + [sz, vp]
         L.merge_partials.argtypes = [pp] + [vp] * 9
         L.periodic_recall.argtypes = [pp] + [vp] * 8 + [sz, vp]
+        L.recall_fetch.argtypes = [pp] + [vp] * 7 + [i64, vp]
         L.scout_calib_copy.argtypes = [vp, vp, sz, vp]
         L.scout_attn_partials.argtypes = [pp, vp, vp, vp, i64] + [vp] * 4 + [sz, vp]
         L.scout_layer_step.argtypes = [pp, vp, vp, vp, vp, vp, i64] + [vp] * 13 + [sz, vp]
@@ -82,6 +83,12 @@ def _ptr(t: Optional[torch.Tensor]):
     if t is None:
         return None
     assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous CUDA tensors"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _ptr_addressable(t: torch.Tensor):
+    """Device tensor, or a CPU tensor in pinned memory (which the GPU addresses at the same pointer)."""
+    assert t.is_contiguous() and (t.is_cuda or t.is_pinned()), "need a CUDA tensor or a pinned CPU tensor"
     return ctypes.c_void_p(t.data_ptr())
 
 
@@ -170,6 +177,13 @@ def periodic_recall(p: Problem, q, digest, block_table, recall_blk, recall_slot,
            lib().periodic_recall(ctypes.byref(p), _ptr(q), _ptr(digest), _ptr(block_table), _ptr(recall_blk),
                                  _ptr(recall_slot), _ptr(evict_blk), _ptr(n_recall), _ptr(ws), ws.numel(),
                                  _stream()))
+
+
+def recall_fetch(p: Problem, src_k, src_v, recall_blk, recall_slot, n_recall, k_pool, v_pool, n_slots):
+    """src_k / src_v: tensors in pinned host memory or on the device."""
+    _check("recall_fetch", lib().recall_fetch(ctypes.byref(p), _ptr_addressable(src_k), _ptr_addressable(src_v), _ptr(recall_blk),
+                                              _ptr(recall_slot), _ptr(n_recall), _ptr(k_pool), _ptr(v_pool),
+                                              int(n_slots), _stream()))
 
 
 def layer_step(p: Problem, q, digest, block_table, k_pool, v_pool, n_slots, host_o, host_m, host_l, scores,

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libscout.so")
-SOURCES = ["score.hip", "append.hip", "topk.hip", "attn.hip", "api.hip"]
+SOURCES = ["score.hip", "append.hip", "fetch.hip", "topk.hip", "attn.hip", "api.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

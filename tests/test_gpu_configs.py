@@ -11,6 +11,7 @@ import pytest
 import torch
 
 import oracle
+from paper_2603_27138_amd import binding as B
 from paper_2603_27138_amd import workload as W
 from tests import harness
 from tests.gpu_harness import Dev, to_dev, to_np
@@ -88,23 +89,33 @@ def check_step(cfg, dev, res, tag):
     return worst, excused
 
 
-def apply_recall_on_device(dev, wl, plans):
-    """The caller's part of a recall: copy the recalled blocks' K/V rows into the freed slots."""
-    cfg = wl.cfg
-    slots, kt, vt = [], [], []
+class HostBlocks:
+    """The host's copy of every block, by logical index, in pinned memory (what a recall reads), and a
+    host mirror of the device pools that the oracle's transfer keeps up to date."""
+
+    def __init__(self, wl):
+        cfg = wl.cfg
+        shape = (cfg.B, cfg.Hkv, cfg.max_blocks, cfg.S, cfg.d)
+        self.k = torch.zeros(shape, dtype=torch.int16).pin_memory()
+        self.v = torch.zeros(shape, dtype=torch.int16).pin_memory()
+        self.kb, self.vb = self.k.numpy().view(np.uint16), self.v.numpy().view(np.uint16)
+        for (b, g) in wl.K:
+            self.kb[b, g, :cfg.nb(b)] = wl.blocks_padded(b, g, "K")
+            self.vb[b, g, :cfg.nb(b)] = wl.blocks_padded(b, g, "V")
+        self.k_pool, self.v_pool = wl.k_pool.copy(), wl.v_pool.copy()
+
+
+def fetch_recall_on_device(dev, host, plans):
+    """The transfer of a recall through the library (the kernel reads the pinned host copy), checked
+    bit for bit against the oracle's transfer on the host mirror of the pools."""
+    B.recall_fetch(dev.p, host.k, host.v, dev.recall_blk, dev.recall_slot, dev.n_recall, dev.k_pool, dev.v_pool,
+                   dev.n_slots)
+    moved = 0
     for (b, g), (rb, rs, eb, n) in plans.items():
-        if n == 0:
-            continue
-        kb, vb = wl.blocks_padded(b, g, "K"), wl.blocks_padded(b, g, "V")
-        slots.append(rs[:n].astype(np.int64))
-        kt.append(kb[rb[:n]])
-        vt.append(vb[rb[:n]])
-    if not slots:
-        return 0
-    idx = torch.from_numpy(np.concatenate(slots)).cuda()
-    dev.k_pool.index_copy_(0, idx, to_dev(np.concatenate(kt)))
-    dev.v_pool.index_copy_(0, idx, to_dev(np.concatenate(vt)))
-    return int(idx.numel())
+        moved += oracle.recall_fetch(host.kb[b, g], host.vb[b, g], rb, rs, n, host.k_pool, host.v_pool)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(dev.k_pool), host.k_pool) and np.array_equal(to_np(dev.v_pool), host.v_pool)
+    return moved
 
 
 def run_steps(cfg, layer=0, steps=None, log=None):
@@ -112,6 +123,7 @@ def run_steps(cfg, layer=0, steps=None, log=None):
     wl = W.generate(cfg, layer=layer, workers=16)
     orc = OracleLayer(wl)
     dev = Dev(wl, k_blocks=False)
+    host = HostBlocks(wl) if cfg.recall_interval else None
     dev.set_digest_from_oracle({p: harness.OraclePair(orc.dig[p], None, None, None, None, 0, None, 0) for p in wl.K})
     steps = cfg.steps if steps is None else steps
     R = cfg.recall_interval
@@ -135,7 +147,7 @@ def run_steps(cfg, layer=0, steps=None, log=None):
                 same = (nr[b, g] == n and np.array_equal(rb[b, g], wrb) and np.array_equal(rs[b, g], wrs)
                         and np.array_equal(eb[b, g], web) and np.array_equal(tab[b, g], orc.table[b, g]))
                 assert same, (cfg.name, layer, t, b, g)
-            moved = apply_recall_on_device(dev, wl, plans)
+            moved = fetch_recall_on_device(dev, host, plans)
             moved_total += moved
             line += f"; recall moved {moved} blocks"
         print(line, flush=True)

@@ -288,6 +288,58 @@ def test_periodic_recall_plan_bit_exact(cfg):
     dev.block_table.copy_(torch.from_numpy(table0))
 
 
+def _bits(a):
+    return a.view(np.uint32) if a.dtype == np.float32 else a
+
+
+@pytest.mark.parametrize("source", ["pinned", "device"])
+def test_recall_fetch_bit_exact(cfg, source):
+    """The transfer of a recall: tiles of the planned blocks, read by the kernel from pinned host
+    memory (or device memory), land in the freed slots; everything else in the pools stays."""
+    wl, res, dev = setup(cfg)
+    def by_index(which):   # [B][Hkv][max_blocks][S][d], rows of blocks beyond a context zero
+        out = np.zeros((cfg.B, cfg.Hkv, cfg.max_blocks, cfg.S, cfg.d), dtype=wl.k_pool.dtype)
+        for (b, g) in wl.K:
+            out[b, g, :cfg.nb(b)] = wl.blocks_padded(b, g, which)
+        return out
+    kb, vb = by_index("K"), by_index("V")
+    q1 = W.gen_q(cfg, 0, step=5)
+    rb = np.full((cfg.B, cfg.Hkv, cfg.k), -1, dtype=np.int32)
+    rs = np.full((cfg.B, cfg.Hkv, cfg.k), -1, dtype=np.int32)
+    nr = np.zeros((cfg.B, cfg.Hkv), dtype=np.int32)
+    kp, vp = wl.k_pool.copy(), wl.v_pool.copy()
+    moved = 0
+    for (b, g), op in res.items():
+        s = oracle.decision_scores(oracle.score(q1[b, g * cfg.G:(g + 1) * cfg.G], op.dig))
+        t = wl.block_table[b, g].copy()
+        rb[b, g], rs[b, g], _, nr[b, g] = oracle.recall_plan(s, cfg.k, t[:len(s)])
+        moved += oracle.recall_fetch(kb[b, g], vb[b, g], rb[b, g], rs[b, g], int(nr[b, g]), kp, vp)
+    if source == "pinned":
+        src_k, src_v = (torch.from_numpy(_bits16(x)).pin_memory() for x in (kb, vb))
+    else:
+        src_k, src_v = to_dev(kb), to_dev(vb)
+    k2, v2 = dev.k_pool.clone(), dev.v_pool.clone()
+    B.recall_fetch(dev.p, src_k, src_v, torch.from_numpy(rb).cuda(), torch.from_numpy(rs).cuda(),
+                   torch.from_numpy(nr).cuda(), k2, v2, dev.n_slots)
+    torch.cuda.synchronize()
+    assert np.array_equal(_bits(to_np(k2)), _bits(kp)) and np.array_equal(_bits(to_np(v2)), _bits(vp))
+    assert moved == int(nr.sum()) and (moved > 0 or cfg.p_host == 0)
+    # a plan with entries out of range moves nothing and faults nothing
+    bad_b, bad_s = rb.copy(), rs.copy()
+    bad_b[..., 0], bad_s[..., 0] = cfg.max_blocks, dev.n_slots
+    k3 = dev.k_pool.clone()
+    one = np.ones_like(nr)
+    B.recall_fetch(dev.p, src_k, src_v, torch.from_numpy(bad_b).cuda(), torch.from_numpy(bad_s).cuda(),
+                   torch.from_numpy(one).cuda(), k3, v2, dev.n_slots)
+    torch.cuda.synchronize()
+    assert np.array_equal(_bits(to_np(k3)), _bits(wl.k_pool))
+
+
+def _bits16(a):
+    """numpy storage array as something torch can hold (bf16 bit patterns as int16)."""
+    return a.view(np.int16) if a.dtype == np.uint16 else a
+
+
 def test_recall_then_select_leaves_nothing_on_host():
     cfg = W.shrink(W.qwen3_32b(B=2, ctx=8192))
     wl, res, dev = setup(cfg)
