@@ -1,0 +1,81 @@
+/*
+ * scout_host.h -- C ABI of the HOST side of GPU-CPU collaborative block-wise
+ * sparse decode attention: the attention over the selected blocks that live
+ * in host memory (ScoutAttention, Sec. 3.2; Alg. 1 CPUAttn), computed by a
+ * pool of worker threads next to the data, so that only a partial result of
+ * G*(d+2) floats per (sequence, KV head) pair crosses the host link instead
+ * of the blocks themselves.  The call is asynchronous so that it can run one
+ * layer ahead of the GPU (Sec. 3.3).
+ *
+ * Every pointer here is HOST memory owned by the caller and must stay valid
+ * and unchanged from submit until the matching wait returns.  Symbols as in
+ * scout.h; "e" is the element type selected by `dtype` (SCOUT_F32 = 0,
+ * SCOUT_BF16 = 1).
+ */
+#ifndef SCOUT_HOST_H
+#define SCOUT_HOST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct scout_host_worker scout_host_worker;
+
+typedef struct scout_host_problem {
+  int32_t B, Hq, Hkv; /* Hq % Hkv == 0, G = Hq/Hkv <= 16                       */
+  int32_t d;          /* head dim, a multiple of 8, <= 256                     */
+  int32_t S;          /* tokens per block, <= 64                               */
+  int32_t dtype;      /* element type of q, k_blocks, v_blocks                 */
+  int32_t max_blocks; /* row length of k_blocks / v_blocks                     */
+  int32_t k;          /* row length of sel_host                                */
+  float sm_scale;     /* softmax scale; 0 means 1/sqrt(d)                      */
+} scout_host_problem;
+
+/*
+ * Start a pool of n_threads worker threads (>= 1).  Returns 0 and the handle,
+ * or a negative code (-1 bad argument, -5 out of memory / thread start failed).
+ */
+int scout_host_create(int n_threads, scout_host_worker** out);
+
+/* Stop the threads and free the pool.  Waits for a job in flight. */
+void scout_host_destroy(scout_host_worker* w);
+
+/*
+ * Host-side partial attention (Sec. 3.2; Alg. 1 CPUAttn): for every query head,
+ * softmax(sm_scale * q.K^T) V over all valid tokens of the listed blocks, as a
+ * partial result in the convention of sparse_decode_attn: m = max logit
+ * (natural-log units), l = sum exp(logit - m), o = sum exp(logit - m) v / l;
+ * an empty list gives o = 0, m = -inf, l = 0.
+ *   q         e   [B][Hq][d]      (the predicted query when run a layer ahead)
+ *   k_blocks  e   [B][Hkv][max_blocks][S][d]   the host's copy of the blocks,
+ *   v_blocks  e   same layout                   by logical block index
+ *   sel_host  i32 [B][Hkv][k]     logical indices of the offloaded selected blocks
+ *   n_host    i32 [B][Hkv]        entries used per pair (clamped to k)
+ *   ctx_len   i32 [B]             tokens per sequence (masks a partial last block)
+ *   o f32 [B][Hq][d], m f32 [B][Hq], l f32 [B][Hq]   out
+ * Inputs are read in their stored type; products and sums are binary32.
+ * Returns at once (0), the pairs being dealt to the threads; -1 on a bad
+ * argument, -6 if a job is already in flight.  Indices outside
+ * [0, max_blocks) and blocks beyond the context are skipped.
+ */
+int scout_host_submit(scout_host_worker* w, const scout_host_problem* p, const void* q,
+                      const void* k_blocks, const void* v_blocks, const int32_t* sel_host,
+                      const int32_t* n_host, const int32_t* ctx_len, float* o, float* m, float* l);
+
+/*
+ * Block until the submitted job is done (0), or return 0 at once if none is
+ * in flight.  *seconds, if not NULL, receives the time from submit to the
+ * last pair's completion.
+ */
+int scout_host_wait(scout_host_worker* w, double* seconds);
+
+/* 1 if the job in flight has finished (or none is in flight), else 0.  Never blocks. */
+int scout_host_done(scout_host_worker* w);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCOUT_HOST_H */

@@ -32,5 +32,21 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+HOST_LIB = os.path.join(HERE, "libscout_host.so")
+
+
+def build_host(verbose: bool = False) -> str:
+    """Compile the host-side worker (plain C++17, threads) into libscout_host.so next to this file."""
+    cmd = ["g++", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread", "-Wall", "-Wextra",
+           "-I", os.path.join(ROOT, "include"), os.path.join(CSRC, "host_worker.cpp"), "-o", HOST_LIB]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("g++ failed:\n" + res.stderr)
+    if verbose and res.stderr.strip():
+        print(res.stderr)
+    return HOST_LIB
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
+    print(build_host(verbose=True))

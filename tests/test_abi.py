@@ -38,6 +38,18 @@ def test_every_declared_symbol_is_exported(lib):
     assert L.scout_strerror(-1) == b"invalid argument"
 
 
+def test_host_library_exports_every_declared_symbol():
+    from paper_2603_27138_amd import build, host
+    if not os.path.exists(build.HOST_LIB):
+        build.build_host()
+    text = open(os.path.join(ROOT, "include", "scout_host.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    syms = sorted(set(re.findall(r"\b(?:int|void)\s+(scout_host_\w+)\s*\(", text)))
+    assert len(syms) == 5 and sorted(host.EXPORTS) == syms
+    for s_ in syms:
+        assert hasattr(host.lib(), s_), s_
+
+
 def _problem(lib, **kw):
     base = dict(B=2, Hq=8, Hkv=2, d=128, S=32, dtype=lib.BF16, max_blocks=64, k=8, sm_scale=0.0, ctx_len=0x1000)
     base.update(kw)
