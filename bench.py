@@ -40,6 +40,16 @@ def parse(argv=None):
     ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--pmc-calib", action="store_true",
                     help="also run a plain 256 MiB device copy (a known-size reference for HBM byte counters)")
+    ap.add_argument("--pipeline", action="store_true",
+                    help="instead of the layer-step benchmark, time the layer-ahead GPU+host pipeline "
+                         "(Sec. 3.3) over --pipe-layers layers and print its own JSON line")
+    ap.add_argument("--pipe-layers", type=int, default=4)
+    ap.add_argument("--pipe-host-frac", type=float, default=0.10,
+                    help="share of the blocks that live on the host (the paper reports 8-12 %% of the budget "
+                         "computed on the host between recalls)")
+    ap.add_argument("--pipe-threads", type=int, default=16)
+    ap.add_argument("--pipe-no-filler", action="store_true",
+                    help="leave out the stand-in for the rest of the layer (projections, feed-forward GEMMs)")
     return ap.parse_args(argv)
 
 
@@ -243,8 +253,108 @@ def timed(st, fn, n):
     return e0.elapsed_time(e1) * 1e3 / n
 
 
+def pipeline_main(args):
+    """Layer-ahead pipeline (Sec. 3.3, Algorithm 1) at config 3's shape: per layer the selection with the
+    predicted query, the host worker on the offloaded selected blocks, the GPU's partial and the merge;
+    optionally a stand-in for the rest of the layer (bf16 GEMMs with Qwen3-32B's weight shapes through
+    the BLAS library).  Reports microseconds per layer with and without the host in the loop; their
+    difference is the time the GPU waits for the host."""
+    import dataclasses
+
+    import torch
+
+    from paper_2603_27138_amd import binding as B
+    from paper_2603_27138_amd import pipeline as P
+    from paper_2603_27138_amd import workload as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    B.lib()
+    cfg = dataclasses.replace(W.qwen3_32b(B=args.batch, ctx=args.ctx), p_host=args.pipe_host_frac)
+    n_layers = args.pipe_layers
+
+    def dev(a):
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16) if a.dtype == np.uint16 else torch.from_numpy(a).cuda()
+
+    layers, qs, qps = [], [], []
+    ctx_len = None
+    for i in range(n_layers):
+        wl = W.generate(cfg, layer=i, workers=16)
+        ctx_len = torch.from_numpy(wl.ctx_len).cuda() if ctx_len is None else ctx_len
+        shape = (cfg.B, cfg.Hkv, cfg.max_blocks, cfg.S, cfg.d)
+        kb = torch.zeros(shape, dtype=torch.int16).pin_memory()
+        vb = torch.zeros(shape, dtype=torch.int16).pin_memory()
+        kn, vn = kb.numpy().view(np.uint16), vb.numpy().view(np.uint16)
+        for (b, g) in wl.K:
+            kn[b, g], vn[b, g] = wl.blocks_padded(b, g, "K"), wl.blocks_padded(b, g, "V")
+        digest = torch.zeros(cfg.B, cfg.Hkv, cfg.max_blocks, 2, cfg.d, dtype=torch.bfloat16, device="cuda")
+        p0 = B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, B.BF16, cfg.max_blocks, cfg.k, ctx_len)
+        k_all = kb.cuda().view(torch.bfloat16)
+        B.build_digests(p0, k_all, digest)
+        torch.cuda.synchronize()
+        del k_all
+        layers.append(P.Layer(digest, torch.from_numpy(wl.block_table).cuda(), dev(wl.k_pool), dev(wl.v_pool),
+                              wl.n_slots, kb, vb))
+        qs.append(dev(wl.q))
+        qps.append(dev(W.gen_q_pred(wl.q, 0.94, seed=i)))
+
+    filler = None
+    if not args.pipe_no_filler:
+        hid, qd, kvd, ffn = 5120, 64 * 128, 2 * 8 * 128, 25600     # Qwen3-32B layer shapes
+        bf = dict(dtype=torch.bfloat16, device="cuda")
+        w_qkv, w_o = torch.randn(hid, qd + kvd, **bf) * 0.01, torch.randn(qd, hid, **bf) * 0.01
+        w_gu, w_dn = torch.randn(hid, 2 * ffn, **bf) * 0.01, torch.randn(ffn, hid, **bf) * 0.01
+        x = torch.randn(cfg.B, hid, **bf)
+
+        def filler(i):
+            a = x @ w_qkv
+            h = a[:, :qd] @ w_o
+            gu = h @ w_gu
+            (gu[:, :ffn] * gu[:, ffn:]) @ w_dn
+
+    pipe = P.LayerAheadPipeline(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, B.BF16, cfg.max_blocks, cfg.k, ctx_len, layers,
+                                n_threads=args.pipe_threads, filler=filler)
+    steps = max(4, args.steps // (4 * n_layers))
+
+    def run(host):
+        for _ in range(2):
+            pipe.step(qs, qps, host=host)
+        torch.cuda.synchronize()
+        hs, ws = [], []
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            pipe.step(qs, qps, host=host)
+            hs += pipe.host_seconds
+            ws += pipe.wait_seconds
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e6 / (steps * n_layers), hs, ws
+
+    us_pipe, hs, ws = run(True)
+    us_gpu, _, _ = run(False)
+    n_host_blocks = int(sum(int(b.n_host_h.sum()) for b in pipe.buf)) / n_layers
+    host_bytes = n_host_blocks * 2 * cfg.S * cfg.d * 2
+    host_us = float(np.mean(hs)) * 1e6
+    pipe.close()
+    print(json.dumps({
+        "metric": "layer-ahead pipeline us/layer (select ahead with predicted query, host worker, GPU attention, merge"
+                  + ("" if args.pipe_no_filler else ", stand-in GEMMs for the rest of the layer") + ")",
+        "value": round(us_pipe, 1), "unit": "us/layer", "n_gpus": 1, "steps": steps, "layers": n_layers,
+        "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "C3 shape, pipeline", "batch": cfg.B, "context": args.ctx, "k_blocks": cfg.k,
+                   "host_resident": cfg.p_host, "host_threads": args.pipe_threads, "filler": not args.pipe_no_filler},
+        "gpu_only_us_per_layer": round(us_gpu, 1),
+        "gpu_wait_share": round(max(0.0, 1.0 - us_gpu / us_pipe), 4),
+        "host_blocks_per_layer": round(n_host_blocks, 1),
+        "host_job_us": round(host_us, 1),
+        "host_gbps": round(host_bytes / host_us * 1e-3, 2),
+        "enqueue_thread_wait_us": round(float(np.mean(ws)) * 1e6, 1),
+    }))
+
+
 def main():
     args = parse()
+    if args.pipeline and args.gpus == 1:
+        return pipeline_main(args)
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only; every (sequence, KV head) pair is independent, so "
               "more GPUs would each run this same path on their share. Run with --gpus 1.", file=sys.stderr)

@@ -37,7 +37,7 @@ HOST_LIB = os.path.join(HERE, "libscout_host.so")
 
 def build_host(verbose: bool = False) -> str:
     """Compile the host-side worker (plain C++17, threads) into libscout_host.so next to this file."""
-    cmd = ["g++", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread", "-Wall", "-Wextra",
+    cmd = ["g++", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread", "-Wall", "-Wextra", "-Wno-psabi",
            "-I", os.path.join(ROOT, "include"), os.path.join(CSRC, "host_worker.cpp"), "-o", HOST_LIB]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:

@@ -6,7 +6,8 @@
 // counter, heaviest pairs first would not pay here: pairs are small (a few blocks) and there are many
 // more of them than threads.  A thread keeps one online-softmax stream per query head of the pair and
 // walks the pair's blocks once: a block's K rows are widened to binary32 once and used by all G
-// heads, then its V rows likewise.  Idle threads spin briefly on the job counter before they sleep:
+// heads, then its V rows likewise.  The query heads of the group are the vector lanes of the logits
+// and of the softmax bookkeeping (no sums across lanes), the channels those of the value product.  Idle threads spin briefly on the job counter before they sleep:
 // a layer-step is tens to hundreds of microseconds, a futex wake-up alone is of that order.
 #include <atomic>
 #include <chrono>
@@ -20,8 +21,6 @@
 #include <vector>
 
 #include "scout_host.h"
-
-namespace {
 
 constexpr int kMaxG = 16, kMaxD = 256, kMaxS = 64;
 
@@ -40,116 +39,35 @@ struct Job {
   int pairs = 0;
 };
 
-inline float bf16_to_f32(uint16_t b) {
-  uint32_t u = (uint32_t)b << 16;
-  float f;
-  std::memcpy(&f, &u, sizeof f);
-  return f;
-}
+namespace scout_host_generic {
+using ::Job;
+#include "host_kernels.inc"
+}  // namespace scout_host_generic
 
-// Rows of a tile as binary32.  The loops are written for the auto-vectoriser; the clones let one
-// build serve hosts with and without the wider vector units.
-__attribute__((target_clones("default", "avx2", "avx512f"))) void widen_bf16(const uint16_t* src, float* dst,
-                                                                               int n) {
-  for (int i = 0; i < n; ++i) {
-    uint32_t u = (uint32_t)src[i] << 16;
-    std::memcpy(&dst[i], &u, sizeof(float));
-  }
-}
+#if defined(__x86_64__)
+#pragma GCC push_options
+#pragma GCC target("avx2,fma")
+namespace scout_host_avx2 {
+using ::Job;
+#include "host_kernels.inc"
+}  // namespace scout_host_avx2
+#pragma GCC pop_options
+#endif
 
-__attribute__((target_clones("default", "avx2,fma", "avx512f"))) void logits_of_block(
-    const float* q, const float* kf, int G, int valid, int d, float scale, float* logit /*[G][kMaxS]*/) {
-  for (int h = 0; h < G; ++h) {
-    const float* qh = q + (size_t)h * d;
-    for (int t = 0; t < valid; ++t) {
-      const float* kr = kf + (size_t)t * d;
-      float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-      for (int c = 0; c < d; c += 8)
-        for (int i = 0; i < 8; ++i) acc[i] += qh[c + i] * kr[c + i];
-      logit[h * kMaxS + t] = scale * (((acc[0] + acc[4]) + (acc[2] + acc[6])) + ((acc[1] + acc[5]) + (acc[3] + acc[7])));
-    }
-  }
-}
-
-__attribute__((target_clones("default", "avx2,fma", "avx512f"))) void add_weighted_rows(
-    const float* w /*[valid]*/, const float* vf, int valid, int d, float corr, float* acc /*[d]*/) {
-  for (int c = 0; c < d; ++c) acc[c] *= corr;
-  for (int t = 0; t < valid; ++t) {
-    const float wt = w[t];
-    const float* vr = vf + (size_t)t * d;
-    for (int c = 0; c < d; ++c) acc[c] += wt * vr[c];
-  }
-}
+namespace {
 
 void run_pair(const Job& J, int pair, float* kf, float* vf) {
-  const scout_host_problem& P = J.p;
-  const int G = P.Hq / P.Hkv, d = P.d, S = P.S;
-  const int b = pair / P.Hkv, g = pair % P.Hkv;
-  const size_t esz = P.dtype == 1 ? 2 : 4;
-  float qf[kMaxG * kMaxD];
-  float acc[kMaxG * kMaxD];
-  float mx[kMaxG], sum[kMaxG];
-  float logit[kMaxG * kMaxS];
-  const size_t q_off = ((size_t)b * P.Hq + (size_t)g * G) * d;
-  if (P.dtype == 1)
-    widen_bf16(static_cast<const uint16_t*>(J.q) + q_off, qf, G * d);
-  else
-    std::memcpy(qf, static_cast<const float*>(J.q) + q_off, sizeof(float) * G * d);
-  for (int h = 0; h < G; ++h) {
-    mx[h] = -std::numeric_limits<float>::infinity();
-    sum[h] = 0.0f;
+  const bool wide = J.p.Hq / J.p.Hkv > 8;
+#if defined(__x86_64__)
+  static const bool avx2 = __builtin_cpu_supports("avx2") && __builtin_cpu_supports("fma");
+  if (avx2) {
+    if (wide) scout_host_avx2::run_pair_nv<2>(J, pair, kf, vf);
+    else scout_host_avx2::run_pair_nv<1>(J, pair, kf, vf);
+    return;
   }
-  std::memset(acc, 0, sizeof(float) * G * d);
-
-  int n = J.n[pair];
-  n = n < 0 ? 0 : (n > P.k ? P.k : n);
-  const int ctx = J.ctx[b];
-  const size_t tile = (size_t)S * d;
-  for (int i = 0; i < n; ++i) {
-    const int j = J.sel[(size_t)pair * P.k + i];
-    if (j < 0 || j >= P.max_blocks) continue;
-    int valid = ctx - j * S;
-    valid = valid > S ? S : valid;
-    if (valid <= 0) continue;
-    const size_t off = ((size_t)pair * P.max_blocks + j) * tile;
-    const float *kt, *vt;
-    if (P.dtype == 1) {
-      widen_bf16(static_cast<const uint16_t*>(J.kb) + off, kf, valid * d);
-      widen_bf16(static_cast<const uint16_t*>(J.vb) + off, vf, valid * d);
-      kt = kf;
-      vt = vf;
-    } else {
-      kt = static_cast<const float*>(J.kb) + off;
-      vt = static_cast<const float*>(J.vb) + off;
-    }
-    (void)esz;
-    logits_of_block(qf, kt, G, valid, d, J.scale, logit);
-    for (int h = 0; h < G; ++h) {
-      float* lg = logit + h * kMaxS;
-      float bm = lg[0];
-      for (int t = 1; t < valid; ++t) bm = lg[t] > bm ? lg[t] : bm;
-      const float m_new = bm > mx[h] ? bm : mx[h];
-      // exp(-inf - finite) = 0 covers the first block; a block of -inf logits leaves the stream as it is
-      if (m_new == -std::numeric_limits<float>::infinity()) continue;
-      const float corr = std::exp(mx[h] - m_new);
-      float s = 0.0f;
-      for (int t = 0; t < valid; ++t) {
-        lg[t] = std::exp(lg[t] - m_new);
-        s += lg[t];
-      }
-      sum[h] = sum[h] * corr + s;
-      mx[h] = m_new;
-      add_weighted_rows(lg, vt, valid, d, corr, acc + (size_t)h * d);
-    }
-  }
-  for (int h = 0; h < G; ++h) {
-    const size_t hq = (size_t)b * P.Hq + (size_t)g * G + h;
-    const float inv = sum[h] > 0.0f ? 1.0f / sum[h] : 0.0f;
-    float* oo = J.o + hq * d;
-    for (int c = 0; c < d; ++c) oo[c] = acc[(size_t)h * d + c] * inv;
-    J.m[hq] = mx[h];
-    J.l[hq] = sum[h];
-  }
+#endif
+  if (wide) scout_host_generic::run_pair_nv<2>(J, pair, kf, vf);
+  else scout_host_generic::run_pair_nv<1>(J, pair, kf, vf);
 }
 
 }  // namespace
@@ -168,7 +86,7 @@ struct scout_host_worker {
   std::chrono::steady_clock::time_point t_submit, t_done;
 
   void loop() {
-    std::vector<float> kf((size_t)kMaxS * kMaxD), vf((size_t)kMaxS * kMaxD);
+    std::vector<float> kf((size_t)(kMaxS + 4) * kMaxD), vf((size_t)kMaxS * kMaxD);
     uint64_t seen = 0;
     for (;;) {
       // wait for a new generation: spin for a short while, then sleep

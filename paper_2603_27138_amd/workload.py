@@ -147,6 +147,21 @@ def gen_q(cfg: Config, layer: int = 0, step: int = 0) -> np.ndarray:
     return to_storage(out, cfg.dtype)
 
 
+def gen_q_pred(q: np.ndarray, cos: float, seed: int) -> np.ndarray:
+    """A stand-in for the query predicted one layer ahead (Sec. 3.3): per head, a vector of the same
+    norm as the real query at cosine similarity `cos` to it (the paper's table reports 0.93-0.97).
+    q: [B][Hq][d] storage array; returns the same shape and type."""
+    qf = storage_to_f32(q).astype(np.float64)
+    rng = np.random.default_rng([int(seed), 77])
+    n = rng.standard_normal(qf.shape)
+    qn = np.linalg.norm(qf, axis=-1, keepdims=True)
+    qn = np.where(qn > 0, qn, 1.0)
+    n -= (n * qf).sum(-1, keepdims=True) / (qn * qn) * qf          # the part orthogonal to q
+    n *= qn / np.linalg.norm(n, axis=-1, keepdims=True)            # same norm as q
+    out = cos * qf + np.sqrt(max(0.0, 1.0 - cos * cos)) * n
+    return to_storage(out.astype(np.float32), "bf16" if q.dtype == np.uint16 else "f32")
+
+
 def _n_planted(cfg: Config, nb: int) -> int:
     n = int(cfg.planted) if cfg.planted >= 1 else int(round(cfg.planted * nb))
     return min(n, nb)
