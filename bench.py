@@ -34,6 +34,9 @@ def parse(argv=None):
     ap.add_argument("--layers", type=int, default=8, help="distinct memory copies the steps rotate over")
     ap.add_argument("--batch", type=int, default=16)
     ap.add_argument("--ctx", type=int, default=32768)
+    ap.add_argument("--config", default="C3", choices=["C2", "C3", "C4", "C5"],
+                    help="C3 (default) is the configuration the metric is quoted on; the others are the parity "
+                         "configurations, timed with the same loops for the table in DESIGN.md (C5: one layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-family", type=int, default=0)
     ap.add_argument("--nsplit", type=int, default=0)
@@ -79,7 +82,11 @@ def setup(args) -> State:
 
     st = State()
     st.B, st.torch = B, torch
-    cfg = st.cfg = W.qwen3_32b(B=args.batch, ctx=args.ctx)
+    if args.config == "C3":
+        cfg = W.qwen3_32b(B=args.batch, ctx=args.ctx)
+    else:
+        cfg = {"C2": W.qwen3_8b, "C4": W.long_context, "C5": W.full_step}[args.config]()
+    st.cfg = cfg
     t0 = time.time()
     wl = st.wl = W.generate(cfg, workers=16)
     st.gen_s = time.time() - t0
@@ -103,11 +110,11 @@ def setup(args) -> State:
     st.ws2 = B.alloc_workspace(p0)
 
     # digest cache from the keys of every block (device kernel), then drop the full key tensor
-    kb = np.empty((cfg.B, cfg.Hkv, cfg.max_blocks, cfg.S, cfg.d), dtype=np.uint16)
-    vb = np.empty_like(kb)
+    kb = np.zeros((cfg.B, cfg.Hkv, cfg.max_blocks, cfg.S, cfg.d), dtype=np.uint16)
+    vb = np.zeros_like(kb)
     for (b, g) in wl.K:
-        kb[b, g] = wl.blocks_padded(b, g, "K")
-        vb[b, g] = wl.blocks_padded(b, g, "V")
+        kb[b, g, :cfg.nb(b)] = wl.blocks_padded(b, g, "K")
+        vb[b, g, :cfg.nb(b)] = wl.blocks_padded(b, g, "V")
     k_all, v_all = dev(kb), dev(vb)
     B.build_digests(p0, k_all, L0.digest)
 
@@ -212,8 +219,8 @@ def fetch_setup(st, per_pair=8):
     f.v = torch.zeros(shape, dtype=torch.int16).pin_memory()
     kb, vb = f.k.numpy().view(np.uint16), f.v.numpy().view(np.uint16)
     for (b, g) in wl.K:
-        kb[b, g] = wl.blocks_padded(b, g, "K")
-        vb[b, g] = wl.blocks_padded(b, g, "V")
+        kb[b, g, :cfg.nb(b)] = wl.blocks_padded(b, g, "K")
+        vb[b, g, :cfg.nb(b)] = wl.blocks_padded(b, g, "V")
     rng = np.random.default_rng(5)
     npairs = cfg.B * cfg.Hkv
     f.plans = []
@@ -400,7 +407,7 @@ def main():
     tile_bytes = 2 * cfg.S * cfg.d * 2                       # K + V tile of one block, bf16
     n_blocks = int(st.sets[0].n_gpu.sum().item())
     attn_bytes = n_blocks * tile_bytes                       # algorithmic bytes of one attention launch
-    digest_bytes = cfg.B * cfg.Hkv * cfg.max_blocks * 2 * cfg.d * 2
+    digest_bytes = sum(cfg.nb(b) for b in range(cfg.B)) * cfg.Hkv * 2 * cfg.d * 2   # entries of valid blocks only
     attn_gbps = attn_bytes / us_attn_kernel * 1e-3
     score_gbps = digest_bytes / us_score * 1e-3
 
@@ -413,7 +420,8 @@ def main():
             traffic = None
 
     result = {
-        "metric": "sparse decode attn us/layer-step (score+select+attend+merge), Qwen3-32B shape 32k",
+        "metric": "sparse decode attn us/layer-step (score+select+attend+merge), Qwen3-32B shape 32k" if args.config == "C3"
+                  else f"sparse decode attn us/layer-step (score+select+attend+merge), {cfg.name}",
         "value": round(us_step, 3),
         "unit": "us/layer-step",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -423,8 +431,10 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "C3 qwen3-32b-shaped single layer", "batch": cfg.B, "q_heads": cfg.Hq,
-                   "kv_heads": cfg.Hkv, "head_dim": cfg.d, "context": args.ctx, "block": cfg.S, "k_blocks": cfg.k,
+        "config": {"workload": {"C2": "C2 qwen3-8b-shaped single layer", "C3": "C3 qwen3-32b-shaped single layer",
+                                "C4": "C4 long context single layer", "C5": "C5 ragged batch, one layer"}[args.config],
+                   "batch": cfg.B, "q_heads": cfg.Hq,
+                   "kv_heads": cfg.Hkv, "head_dim": cfg.d, "context": int(max(cfg.ctx)), "block": cfg.S, "k_blocks": cfg.k,
                    "host_resident": cfg.p_host, "layer_copies": len(st.sets), "gpu_blocks_per_step": n_blocks},
         "kv_gbps": round(attn_gbps, 1),
         "kernels_us": {"score_blocks": round(us_score, 3), "select_topk": round(us_select, 3),
