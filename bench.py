@@ -1,6 +1,6 @@
 """Benchmark: one layer-step of the sparse decode-attention hot path on one MI355X.
 
-Workload: benchmark config 3 (Qwen3-32B-shaped single layer: batch 16, 64 q / 8 KV
+Workload: config 3 of the benchmark definition (Qwen3-32B-shaped single layer: batch 16, 64 q / 8 KV
 heads, d 128, bf16, 32768-token contexts in blocks of 32, k = 64, 50 % of blocks
 host-resident), synthetic and seeded.  A step = score_blocks -> select_topk ->
 sparse_decode_attn -> merge with the host partial (scout_layer_step), inputs resident
@@ -36,7 +36,7 @@ def parse(argv=None):
     ap.add_argument("--ctx", type=int, default=32768)
     ap.add_argument("--config", default="C3", choices=["C2", "C3", "C4", "C5"],
                     help="C3 (default) is the configuration the metric is quoted on; the others are the parity "
-                         "configurations, timed with the same loops for the table in DESIGN.md (C5: one layer)")
+                         "configurations, timed with the same loops (C5: one layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-family", type=int, default=0)
     ap.add_argument("--nsplit", type=int, default=0)

@@ -1,4 +1,4 @@
-"""GPU parity at the sizes of the five BASELINE configs (config 5 with fewer layers), including the
+"""GPU parity at the sizes of the five benchmark configurations (config 5 with fewer layers), including the
 multi-step runs with query drift and periodic recall.  Expected values come from the CPU oracle.
 
 Bars as in test_gpu_parity.py: selections, lists and recall plans bit-exact (a mismatch excused only
