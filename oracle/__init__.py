@@ -225,3 +225,13 @@ def recall_fetch(src_k: np.ndarray, src_v: np.ndarray, recall_blk, recall_slot, 
     L.orc_recall_fetch.argtypes = [ctypes.c_int] * 4 + [ctypes.c_void_p] * 4 + [ctypes.c_int] + [ctypes.c_void_p] * 2 + [ctypes.c_long]
     return L.orc_recall_fetch(_dtype_code(src_k), S, d, mb, src_k.ctypes.data, src_v.ctypes.data, rb.ctypes.data,
                               rs.ctypes.data, int(n), k_pool.ctypes.data, v_pool.ctypes.data, len(k_pool))
+
+
+def force_blocks(s: np.ndarray, n_sink: int, n_tail: int) -> np.ndarray:
+    """Scores with the first n_sink and the last n_tail blocks raised to +inf (a copy)."""
+    out = np.ascontiguousarray(s, dtype=np.float64).copy()
+    L = _L()
+    L.orc_force_blocks.restype = None
+    L.orc_force_blocks.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    L.orc_force_blocks(_dp(out), len(out), int(n_sink), int(n_tail))
+    return out

@@ -24,7 +24,8 @@
  * forms and against weight normalisation; merge against attention over the
  * union of a split; recall plan against brute-force set arithmetic; decode
  * append against the digest and the tiles of the finished sequence built in
- * one piece; recall transfer against plain slicing of the source array.
+ * one piece; recall transfer against plain slicing of the source array;
+ * always-kept blocks against a brute-force statement of the same rule.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -319,4 +320,17 @@ int orc_recall_fetch(int dtype, int S, int d, int max_blocks, const void* src_k,
     ++copied;
   }
   return copied;
+}
+
+/*
+ * Always-kept blocks (a variant of the selection rule of Alg. 1's TopK: the
+ * first n_sink blocks of a sequence and the last n_tail blocks that hold
+ * tokens are selected whatever their score).  They are given the score
+ * +infinity, so the ordinary selection keeps them first, lower index first
+ * among them if the budget cannot hold them all; they count against k.
+ * s is [nb], changed in place.
+ */
+void orc_force_blocks(double* s, int nb, int n_sink, int n_tail) {
+  for (int j = 0; j < nb; ++j)
+    if (j < n_sink || j >= nb - n_tail) s[j] = INFINITY;
 }

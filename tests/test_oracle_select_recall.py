@@ -176,3 +176,22 @@ def test_recall_plan_then_fetch_makes_every_selected_block_resident_with_its_own
             assert np.array_equal(kp[table[j]], src_k[j]) and np.array_equal(vp[table[j]], src_v[j])
     top = set(np.argsort(-s, kind="stable")[:k].tolist())
     assert all(table[j] >= 0 for j in top)
+
+
+# ---------------------------------------------------------------- always-kept blocks
+
+@pytest.mark.parametrize("nb,k,n_sink,n_tail", [(40, 8, 1, 2), (40, 8, 0, 0), (40, 8, 3, 0), (10, 4, 2, 3), (5, 8, 1, 1),
+                                                (12, 3, 4, 4), (1, 1, 1, 1), (7, 7, 0, 7)])
+def test_forced_blocks_then_topk_is_the_brute_force_rule(nb, k, n_sink, n_tail):
+    rng = np.random.default_rng(nb * 100 + k)
+    s = rng.standard_normal(nb)
+    sel = oracle.select(oracle.force_blocks(s, n_sink, n_tail), k)
+    got = [int(j) for j in sel if j >= 0]
+    # brute force: forced blocks first in index order, then the others by (score desc, index asc)
+    forced = [j for j in range(nb) if j < n_sink or j >= nb - n_tail]
+    others = sorted((j for j in range(nb) if j not in forced), key=lambda j: (-s[j], j))
+    want = sorted((forced + others)[:min(k, nb)])
+    assert got == want
+    assert np.array_equal(s, s)   # the input is not modified
+    f = oracle.force_blocks(s, n_sink, n_tail)
+    assert all(np.isposinf(f[j]) for j in forced) and all(f[j] == s[j] for j in range(nb) if j not in forced)
