@@ -63,6 +63,8 @@ typedef struct scout_problem {
   int32_t max_blocks; /* row length of scores / block_table / digest, <= 16384      */
   int32_t k;          /* block budget per pair = token budget / S, 1 <= k <= 1024   */
   float sm_scale;     /* softmax scale; 0 means 1/sqrt(d)                           */
+  int32_t n_sink;     /* always-kept blocks: the first n_sink blocks of a sequence  */
+  int32_t n_tail;     /* and its last n_tail blocks that hold tokens (both >= 0)    */
   const int32_t* ctx_len; /* DEVICE int32 [B]: tokens per sequence; blocks beyond
                              max_blocks are ignored                                  */
 } scout_problem;
@@ -118,7 +120,9 @@ int append_token(const scout_problem* p, int32_t* ctx_len, const void* k_new, co
  * Block importance (Sec. 2.2, Sec. 3.2, Alg. 1 TopK argument): for each pair
  * and block j, sum over the G query heads of the group and over channels c of
  * max(q[c]*min_j[c], q[c]*max_j[c]).  Unscaled.  Accumulated in binary64 and
- * rounded once to binary32.
+ * rounded once to binary32.  The always-kept blocks (j < n_sink or
+ * j >= nb_b - n_tail) get +inf instead, so that the selection keeps them first
+ * (lower index first if the budget cannot hold them all); they count against k.
  *   q        e   [B][Hq][d]
  *   digest   e   [B][Hkv][max_blocks][2][d]
  *   scores   f32 [B][Hkv][max_blocks]          out; -inf for j >= nb_b

@@ -34,7 +34,7 @@ class Problem(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
                 ("d", ctypes.c_int32), ("S", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("max_blocks", ctypes.c_int32), ("k", ctypes.c_int32), ("sm_scale", ctypes.c_float),
-                ("ctx_len", ctypes.c_void_p)]
+                ("n_sink", ctypes.c_int32), ("n_tail", ctypes.c_int32), ("ctx_len", ctypes.c_void_p)]
 
 
 _lib = None
@@ -104,9 +104,11 @@ def dtype_code(t: torch.Tensor) -> int:
     raise TypeError(f"unsupported element type {t.dtype}")
 
 
-def make_problem(B, Hq, Hkv, d, S, dtype, max_blocks, k, ctx_len: torch.Tensor, sm_scale: float = 0.0):
+def make_problem(B, Hq, Hkv, d, S, dtype, max_blocks, k, ctx_len: torch.Tensor, sm_scale: float = 0.0,
+                 n_sink: int = 0, n_tail: int = 0):
     assert ctx_len.dtype == torch.int32 and ctx_len.is_cuda
-    return Problem(B, Hq, Hkv, d, S, dtype, max_blocks, k, float(sm_scale), ctx_len.data_ptr())
+    return Problem(B, Hq, Hkv, d, S, dtype, max_blocks, k, float(sm_scale), int(n_sink), int(n_tail),
+                   ctx_len.data_ptr())
 
 
 def version() -> int:

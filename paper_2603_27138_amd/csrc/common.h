@@ -15,6 +15,7 @@ constexpr float kLn2 = 0.6931471805599453f;
 struct Dims {
   int B, Hq, Hkv, G, d, S, max_blocks, k;
   float sm_scale;
+  int n_sink, n_tail;  // always-kept blocks at the start and at the end of a sequence
   const int32_t* ctx_len;
 };
 

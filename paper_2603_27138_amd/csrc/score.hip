@@ -223,7 +223,10 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_kernel(
     a[0] += partner_f64<0>(a[0]);
     // a[0]: score of entry lane/8 of group my_g of this batch
     const int j = j_wave + (t * NG + my_g) * 8 + (lane >> 3);
-    if (writer && j < D.max_blocks) scores[(size_t)pair * D.max_blocks + j] = j < nb ? (float)a[0] : -INFINITY;
+    if (writer && j < D.max_blocks) {
+      const bool kept = j < D.n_sink || j >= nb - D.n_tail;  // always-kept blocks rank above every score
+      scores[(size_t)pair * D.max_blocks + j] = j < nb ? (kept ? INFINITY : (float)a[0]) : -INFINITY;
+    }
   }
 }
 

@@ -297,6 +297,40 @@ def test_periodic_recall_plan_bit_exact(cfg):
     dev.block_table.copy_(torch.from_numpy(table0))
 
 
+@pytest.mark.parametrize("n_sink,n_tail", [(1, 2), (0, 1), (3, 0)])
+def test_always_kept_blocks(cfg, n_sink, n_tail):
+    """Sink and tail blocks get +inf in score_blocks and are therefore selected first; the rest of the
+    budget goes to the best of the others.  Scores and selections against the oracle, alone and
+    through the fused layer-step."""
+    wl, res, dev = setup(cfg)
+    dev.set_digest_from_oracle(res)
+    dev.set_host_partials_from_oracle(res)
+    code = B.F32 if cfg.dtype == "f32" else B.BF16
+    p2 = B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, code, cfg.max_blocks, cfg.k, dev.ctx_len, 0.0,
+                        n_sink=n_sink, n_tail=n_tail)
+    B.score_blocks(p2, dev.q, dev.digest, dev.scores, dev.ws)
+    B.select_topk(p2, dev.scores, dev.block_table, dev.sel_all, dev.sel_gpu, dev.slot_gpu, dev.n_gpu, dev.sel_host,
+                  dev.n_host, dev.ws)
+    got_s, got_sel = dev.scores.cpu().numpy(), dev.sel_all.cpu().numpy()
+    want = {}
+    for (b, g), op in res.items():
+        nb = len(op.s32)
+        f = oracle.force_blocks(op.s32, n_sink, n_tail)
+        want[(b, g)] = oracle.select(f, cfg.k)
+        kept = np.isposinf(f)
+        assert np.array_equal(np.isposinf(got_s[b, g, :nb]), kept), (b, g)
+        assert np.array_equal(got_s[b, g, :nb][~kept].astype(np.float64), op.s32[~kept]) or harness.boundary_gap(op, cfg.k) < 1e-6
+        assert np.array_equal(got_sel[b, g], want[(b, g)]) or harness.boundary_gap(op, cfg.k) < 1e-6, (b, g)
+        for j in [j for j in range(nb) if kept[j]][:cfg.k]:
+            assert j in got_sel[b, g]
+    B.layer_step(p2, dev.q, dev.digest, dev.block_table, dev.k_pool, dev.v_pool, dev.n_slots, dev.host_o, dev.host_m,
+                 dev.host_l, dev.scores, dev.sel_all, dev.sel_gpu, dev.slot_gpu, dev.n_gpu, dev.sel_host, dev.n_host,
+                 dev.out, dev.lse, dev.ws)
+    got_sel = dev.sel_all.cpu().numpy()
+    for (b, g), op in res.items():
+        assert np.array_equal(got_sel[b, g], want[(b, g)]) or harness.boundary_gap(op, cfg.k) < 1e-6, (b, g)
+
+
 def _can_move(cfg):
     """A recall can move something only if blocks live on both sides and some resident block can be unselected."""
     return 0.0 < cfg.p_host < 1.0 and all(cfg.nb(b) > cfg.k for b in range(cfg.B))
