@@ -246,6 +246,18 @@ def fetch_only(st, i):
     st.B.recall_fetch(st.probs[0], f.k, f.v, blk, slot, f.n, f.k_pool, f.v_pool, f.n_slots)
 
 
+def stream_only(st, i):
+    """Read-only stream of exactly the digest cache of the layer copy (what score_blocks reads)."""
+    s = st.sets[i % len(st.sets)]
+    st.B.calib_read(s.digest, s.digest.numel() * s.digest.element_size())
+
+
+def gather_only(st, i):
+    """Bare gather of exactly the tiles sparse_decode_attn reads for this layer copy's lists."""
+    s, p = st.sets[i % len(st.sets)], st.probs[i % len(st.sets)]
+    st.B.calib_gather(p, s.k_pool, s.v_pool, st.wl.n_slots, s.slot_gpu, s.n_gpu)
+
+
 def timed(st, fn, n):
     """Microseconds per call: HIP events on the stream the kernels are launched on."""
     torch = st.torch
@@ -394,6 +406,11 @@ def main():
     us_attn = timed(st, attn_only, args.steps)
     us_score = timed(st, score_only, args.steps)
     us_select = timed(st, select_only, args.steps)
+    for i in range(8):
+        stream_only(st, i)
+        gather_only(st, i)
+    us_stream = timed(st, stream_only, args.steps)
+    us_gather = timed(st, gather_only, args.steps)
     append_setup(st)
     assert cfg.S * (cfg.max_blocks // 2) + args.steps + args.warmup < cfg.S * cfg.max_blocks
     for i in range(args.warmup):
@@ -408,6 +425,7 @@ def main():
     n_blocks = int(st.sets[0].n_gpu.sum().item())
     attn_bytes = n_blocks * tile_bytes                       # algorithmic bytes of one attention launch
     digest_bytes = sum(cfg.nb(b) for b in range(cfg.B)) * cfg.Hkv * 2 * cfg.d * 2   # entries of valid blocks only
+    s0_digest_bytes = st.sets[0].digest.numel() * 2          # the whole digest array (rows of absent blocks too)
     attn_gbps = attn_bytes / us_attn_kernel * 1e-3
     score_gbps = digest_bytes / us_score * 1e-3
 
@@ -442,6 +460,14 @@ def main():
                        "append_token": round(us_append, 3), "recall_fetch": round(us_fetch, 1)},
         "recall_h2d_gbps": round(st.fetch.bytes / us_fetch * 1e-3, 1),
         "score_gbps": round(score_gbps, 1),
+        # what this GPU sustains for the same bytes with nothing computed (same buffers, same rotation):
+        # a read-only stream of the digest cache, and a bare gather of the tiles the attention reads
+        "measured_ceilings": {"stream_read_us": round(us_stream, 3),
+                              "stream_read_gbps": round(s0_digest_bytes / us_stream * 1e-3, 1),
+                              "gather_tiles_us": round(us_gather, 3),
+                              "gather_tiles_gbps": round(attn_bytes / us_gather * 1e-3, 1),
+                              "attn_frac_of_gather": round(us_gather / us_attn_kernel, 4),
+                              "score_frac_of_stream": round(us_stream * digest_bytes / s0_digest_bytes / us_score, 4)},
         "roofline": {"bound": "hbm", "kernel": "attn_mfma_kernel", "achieved": round(attn_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
                      "traffic": traffic, "algorithmic_bytes": attn_bytes},

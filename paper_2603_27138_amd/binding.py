@@ -21,7 +21,8 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 
 EXPORTS = ["scout_version", "scout_strerror", "scout_workspace_bytes", "build_digests", "append_token", "score_blocks",
            "select_topk", "sparse_decode_attn", "merge_partials", "periodic_recall", "recall_fetch",
-           "scout_layer_step", "scout_set_attn_mode", "scout_calib_copy", "scout_attn_partials"]
+           "scout_layer_step", "scout_set_attn_mode", "scout_calib_copy", "scout_attn_partials",
+           "scout_calib_read", "scout_calib_gather"]
 
 
 class ScoutError(RuntimeError):
@@ -65,6 +66,8 @@ def lib():
         L.periodic_recall.argtypes = [pp] + [vp] * 8 + [sz, vp]
         L.recall_fetch.argtypes = [pp] + [vp] * 7 + [i64, vp]
         L.scout_calib_copy.argtypes = [vp, vp, sz, vp]
+        L.scout_calib_read.argtypes = [vp, sz, vp, vp]
+        L.scout_calib_gather.argtypes = [pp, vp, vp, i64, vp, vp, vp, vp]
         L.scout_attn_partials.argtypes = [pp, vp, vp, vp, i64] + [vp] * 4 + [sz, vp]
         L.scout_layer_step.argtypes = [pp, vp, vp, vp, vp, vp, i64] + [vp] * 13 + [sz, vp]
         for name in EXPORTS:
@@ -186,6 +189,15 @@ def recall_fetch(p: Problem, src_k, src_v, recall_blk, recall_slot, n_recall, k_
     _check("recall_fetch", lib().recall_fetch(ctypes.byref(p), _ptr_addressable(src_k), _ptr_addressable(src_v), _ptr(recall_blk),
                                               _ptr(recall_slot), _ptr(n_recall), _ptr(k_pool), _ptr(v_pool),
                                               int(n_slots), _stream()))
+
+
+def calib_read(src, nbytes: int, sink=None):
+    _check("scout_calib_read", lib().scout_calib_read(_ptr(src), int(nbytes), _ptr(sink), _stream()))
+
+
+def calib_gather(p: Problem, k_pool, v_pool, n_slots, slot_gpu, n_gpu, sink=None):
+    _check("scout_calib_gather", lib().scout_calib_gather(ctypes.byref(p), _ptr(k_pool), _ptr(v_pool), int(n_slots),
+                                                          _ptr(slot_gpu), _ptr(n_gpu), _ptr(sink), _stream()))
 
 
 def layer_step(p: Problem, q, digest, block_table, k_pool, v_pool, n_slots, host_o, host_m, host_l, scores,

@@ -171,6 +171,48 @@ __global__ __launch_bounds__(256) void calib_copy_kernel(const uint4* __restrict
     dst[i] = src[i];
 }
 
+// Measured ceilings for the two access patterns of the path, nothing computed: a read-only stream
+// (what the digest pass does) and a gather of whole K and V tiles by slot (what the attention does).
+// Many small waves, everything requested at once: 8 loads of 16 bytes per lane.
+__global__ __launch_bounds__(256) void calib_read_kernel(const uint4* __restrict__ src, size_t n16, uint32_t* sink) {
+  const size_t base = ((size_t)blockIdx.x * 256 * 8) + threadIdx.x;
+  uint4 v[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    const size_t i = base + (size_t)u * 256;
+    v[u] = i < n16 ? src[i] : make_uint4(0, 0, 0, 0);
+  }
+  uint32_t acc = 0;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  if (acc == 0x9e3779b9u && sink != nullptr) sink[0] = acc;  // keeps the loads alive; practically never true
+}
+
+// grid (k, pairs), two waves per workgroup: wave 0 reads the K tile, wave 1 the V tile of entry
+// blockIdx.x of the pair's list, if the list is that long.
+__global__ __launch_bounds__(128) void calib_gather_kernel(const char* __restrict__ k_pool,
+                                                           const char* __restrict__ v_pool, long long n_slots,
+                                                           int tile_bytes, const int32_t* __restrict__ slot_gpu,
+                                                           const int32_t* __restrict__ n_gpu, int k, uint32_t* sink) {
+  const int pair = blockIdx.y, i = blockIdx.x;
+  const long long slot = slot_gpu[(size_t)pair * k + i];  // read with the count, not after it
+  int n = n_gpu[pair];
+  n = n < k ? n : k;
+  if (i >= n || slot < 0 || slot >= n_slots) return;
+  const int lane = threadIdx.x & 63;
+  const char* tile = (threadIdx.x >> 6 ? v_pool : k_pool) + (size_t)slot * tile_bytes;
+  uint32_t acc = 0;
+  for (int off = lane * 16; off < tile_bytes; off += 8 * 1024) {  // 8 KiB per trip: 8 loads in flight
+    uint4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      v[u] = off + u * 1024 < tile_bytes ? *reinterpret_cast<const uint4*>(tile + off + u * 1024) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  }
+  if (acc == 0x9e3779b9u && sink != nullptr) sink[0] = acc;
+}
+
 }  // namespace scout
 
 using namespace scout;
@@ -207,6 +249,32 @@ int scout_calib_copy(const void* src, void* dst, size_t bytes, void* stream) {
   if (bytes == 0) return SCOUT_OK;
   hipLaunchKernelGGL(calib_copy_kernel, dim3(4096), dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<const uint4*>(src), static_cast<uint4*>(dst), bytes / 16);
+  return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
+}
+
+int scout_calib_read(const void* src, size_t bytes, void* sink, void* stream) {
+  if (!src || !aligned16(src) || bytes % 16 != 0) return SCOUT_EINVAL;
+  if (bytes == 0) return SCOUT_OK;
+  const size_t n16 = bytes / 16, per_wg = 256 * 8;
+  hipLaunchKernelGGL(calib_read_kernel, dim3((unsigned)((n16 + per_wg - 1) / per_wg)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const uint4*>(src), n16,
+                     static_cast<uint32_t*>(sink));
+  return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
+}
+
+int scout_calib_gather(const scout_problem* p, const void* k_pool, const void* v_pool, int64_t n_slots,
+                       const int32_t* slot_gpu, const int32_t* n_gpu, void* sink, void* stream) {
+  Dims D;
+  int rc = check_problem(p, &D);
+  if (rc != SCOUT_OK) return rc;
+  if (!k_pool || !v_pool || !slot_gpu || !n_gpu || !aligned16(k_pool) || !aligned16(v_pool) || n_slots < 0)
+    return SCOUT_EINVAL;
+  const int tile_bytes = D.S * D.d * (p->dtype == SCOUT_BF16 ? 2 : 4);
+  dim3 grid(D.k, D.B * D.Hkv);
+  if (grid.y == 0) return SCOUT_OK;
+  hipLaunchKernelGGL(calib_gather_kernel, grid, dim3(128), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const char*>(k_pool), static_cast<const char*>(v_pool), (long long)n_slots,
+                     tile_bytes, slot_gpu, n_gpu, D.k, static_cast<uint32_t*>(sink));
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
 }
 
