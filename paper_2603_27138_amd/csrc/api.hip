@@ -188,19 +188,21 @@ __global__ __launch_bounds__(256) void calib_read_kernel(const uint4* __restrict
   if (acc == 0x9e3779b9u && sink != nullptr) sink[0] = acc;  // keeps the loads alive; practically never true
 }
 
-// grid (k, pairs), two waves per workgroup: wave 0 reads the K tile, wave 1 the V tile of entry
-// blockIdx.x of the pair's list, if the list is that long.
-__global__ __launch_bounds__(128) void calib_gather_kernel(const char* __restrict__ k_pool,
+// grid (ceil(k/2), pairs), four waves per workgroup: waves 0 and 1 read the K and the V tile of entry
+// blockIdx.x of the pair's list, waves 2 and 3 those of entry k-1-blockIdx.x, if the list is that long
+// (a list is rarely full, so folding it keeps most workgroups from being launched for nothing).
+__global__ __launch_bounds__(256) void calib_gather_kernel(const char* __restrict__ k_pool,
                                                            const char* __restrict__ v_pool, long long n_slots,
                                                            int tile_bytes, const int32_t* __restrict__ slot_gpu,
                                                            const int32_t* __restrict__ n_gpu, int k, uint32_t* sink) {
-  const int pair = blockIdx.y, i = blockIdx.x;
+  const int pair = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i = wave < 2 ? (int)blockIdx.x : k - 1 - (int)blockIdx.x;
+  if (wave >= 2 && i <= (int)blockIdx.x) return;  // the middle entry of an odd k belongs to waves 0 and 1
   const long long slot = slot_gpu[(size_t)pair * k + i];  // read with the count, not after it
   int n = n_gpu[pair];
   n = n < k ? n : k;
   if (i >= n || slot < 0 || slot >= n_slots) return;
-  const int lane = threadIdx.x & 63;
-  const char* tile = (threadIdx.x >> 6 ? v_pool : k_pool) + (size_t)slot * tile_bytes;
+  const char* tile = ((wave & 1) ? v_pool : k_pool) + (size_t)slot * tile_bytes;
   uint32_t acc = 0;
   for (int off = lane * 16; off < tile_bytes; off += 8 * 1024) {  // 8 KiB per trip: 8 loads in flight
     uint4 v[8];
@@ -270,9 +272,9 @@ int scout_calib_gather(const scout_problem* p, const void* k_pool, const void* v
   if (!k_pool || !v_pool || !slot_gpu || !n_gpu || !aligned16(k_pool) || !aligned16(v_pool) || n_slots < 0)
     return SCOUT_EINVAL;
   const int tile_bytes = D.S * D.d * (p->dtype == SCOUT_BF16 ? 2 : 4);
-  dim3 grid(D.k, D.B * D.Hkv);
+  dim3 grid((D.k + 1) / 2, D.B * D.Hkv);
   if (grid.y == 0) return SCOUT_OK;
-  hipLaunchKernelGGL(calib_gather_kernel, grid, dim3(128), 0, static_cast<hipStream_t>(stream),
+  hipLaunchKernelGGL(calib_gather_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<const char*>(k_pool), static_cast<const char*>(v_pool), (long long)n_slots,
                      tile_bytes, slot_gpu, n_gpu, D.k, static_cast<uint32_t*>(sink));
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
