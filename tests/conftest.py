@@ -12,6 +12,15 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
+def pytest_sessionstart(session):
+    """The libraries are built beforehand; build here only what is missing (a fresh checkout)."""
+    from paper_2603_27138_amd import build
+    if not os.path.exists(build.LIB):
+        build.build()
+    if not os.path.exists(build.HOST_LIB):
+        build.build_host()
+
+
 @pytest.fixture(scope="session")
 def oracle_lib():
     import oracle
