@@ -235,3 +235,19 @@ def force_blocks(s: np.ndarray, n_sink: int, n_tail: int) -> np.ndarray:
     L.orc_force_blocks.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int, ctypes.c_int, ctypes.c_int]
     L.orc_force_blocks(_dp(out), len(out), int(n_sink), int(n_tail))
     return out
+
+
+def score_max(q: np.ndarray, dig: np.ndarray) -> np.ndarray:
+    """As score(), with the maximum over the group's heads instead of their sum."""
+    q = np.ascontiguousarray(q)
+    dig = np.ascontiguousarray(dig)
+    assert q.dtype == dig.dtype
+    G, d = q.shape
+    nb = dig.shape[0]
+    s = np.zeros(nb, dtype=np.float64)
+    L = _L()
+    L.orc_score_max.restype = None
+    L.orc_score_max.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                ctypes.POINTER(ctypes.c_double)]
+    L.orc_score_max(_dtype_code(q), _vp(q), _vp(dig), nb, G, d, _dp(s))
+    return s

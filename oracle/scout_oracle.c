@@ -25,7 +25,8 @@
  * union of a split; recall plan against brute-force set arithmetic; decode
  * append against the digest and the tiles of the finished sequence built in
  * one piece; recall transfer against plain slicing of the source array;
- * always-kept blocks against a brute-force statement of the same rule.
+ * always-kept blocks against a brute-force statement of the same rule; the
+ * max-over-heads score against an array computation and its G = 1 case.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -333,4 +334,28 @@ int orc_recall_fetch(int dtype, int S, int d, int max_blocks, const void* src_k,
 void orc_force_blocks(double* s, int nb, int n_sink, int n_tail) {
   for (int j = 0; j < nb; ++j)
     if (j < n_sink || j >= nb - n_tail) s[j] = INFINITY;
+}
+
+/*
+ * Block importance with the group's heads combined by their maximum instead
+ * of their sum (a variant of the selection argument of Alg. 1: a block matters
+ * to the KV head if it matters to any of the query heads that share it).  Per
+ * head the estimate is the one of orc_score: sum over channels of the larger
+ * of q*min and q*max.  q is [G][d], dig is [nb][2][d]; s is [nb], unscaled.
+ */
+void orc_score_max(int dtype, const void* q, const void* dig, int nb, int G, int d, double* s) {
+  for (int j = 0; j < nb; ++j) {
+    double best = -INFINITY;
+    for (int h = 0; h < G; ++h) {
+      double sh = 0.0;
+      for (int c = 0; c < d; ++c) {
+        double qc = ld(q, dtype, (size_t)h * d + c);
+        double lo = qc * ld(dig, dtype, ((size_t)j * 2 + 0) * d + c);
+        double hi = qc * ld(dig, dtype, ((size_t)j * 2 + 1) * d + c);
+        sh += lo > hi ? lo : hi;
+      }
+      if (sh > best) best = sh;
+    }
+    s[j] = best;
+  }
 }

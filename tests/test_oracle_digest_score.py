@@ -122,3 +122,26 @@ def test_planted_blocks_rank_high_on_tiny():
     s = oracle.score(wl.q[0], dig)
     top = set(oracle.select(s, 16).tolist())
     assert len(top & set(wl.planted[(0, 0)].tolist())) >= 7
+
+
+# ---------------------------------------------------------------- max over the group's heads
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("G,d,nb,S", [(8, 128, 9, 32), (4, 64, 5, 16), (16, 8, 3, 4)])
+def test_score_max_is_the_maximum_of_the_per_head_estimates(dtype, G, d, nb, S):
+    K = _rand((nb * S, d), 21, dtype)
+    q = _rand((G, d), 22, dtype)
+    dig = oracle.digest(K, nb * S, S)
+    qf = W.storage_to_f32(q).astype(np.float64)
+    df = W.storage_to_f32(dig).astype(np.float64)
+    per_head = np.maximum(qf[None, :, :] * df[:, None, 0, :], qf[None, :, :] * df[:, None, 1, :]).sum(-1)   # [nb][G]
+    got = oracle.score_max(q, dig)
+    assert np.allclose(got, per_head.max(axis=1), rtol=1e-13, atol=0)
+    # the sum over heads is the other aggregation: never below the maximum when every estimate is positive,
+    # and equal to it for a group of one head
+    assert np.allclose(oracle.score(q, dig), per_head.sum(axis=1), rtol=1e-13, atol=0)
+    assert np.array_equal(oracle.score_max(q[:1], dig), oracle.score(q[:1], dig))
+    # each head's estimate bounds its dot products over the block from above, so does the maximum for its own head
+    Kf = W.storage_to_f32(K).astype(np.float64).reshape(nb, S, d)
+    dots = np.einsum("hc,jtc->jht", qf, Kf).max(axis=2)     # [nb][G] largest true logit per head
+    assert (per_head >= dots - 1e-9).all() and (got >= dots.max(axis=1) - 1e-9).all()
