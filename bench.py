@@ -37,6 +37,8 @@ def parse(argv=None):
     ap.add_argument("--config", default="C3", choices=["C2", "C3", "C4", "C5"],
                     help="C3 (default) is the configuration the metric is quoted on; the others are the parity "
                          "configurations, timed with the same loops (C5: one layer)")
+    ap.add_argument("--group-max", action="store_true",
+                    help="time the variant that combines the group's heads by their maximum (not the metric's setting)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-family", type=int, default=0)
     ap.add_argument("--nsplit", type=int, default=0)
@@ -147,7 +149,8 @@ def setup(args) -> State:
     torch.cuda.empty_cache()
 
     st.sets = [L0] + [LayerSet(L0) for _ in range(args.layers - 1)]
-    st.probs = [B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, B.BF16, cfg.max_blocks, cfg.k, s.ctx_len)
+    st.probs = [B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, B.BF16, cfg.max_blocks, cfg.k, s.ctx_len,
+                               group_max=int(args.group_max))
                 for s in st.sets]
     st.part_o = torch.empty(cfg.B, cfg.Hq, cfg.d, **f32)
     st.part_m = torch.empty(cfg.B, cfg.Hq, **f32)

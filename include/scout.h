@@ -65,6 +65,9 @@ typedef struct scout_problem {
   float sm_scale;     /* softmax scale; 0 means 1/sqrt(d)                           */
   int32_t n_sink;     /* always-kept blocks: the first n_sink blocks of a sequence  */
   int32_t n_tail;     /* and its last n_tail blocks that hold tokens (both >= 0)    */
+  int32_t group_max;  /* block importance of a KV head: 0 = sum over its G query
+                         heads (default), 1 = maximum over them                     */
+  int32_t reserved;   /* 0                                                          */
   const int32_t* ctx_len; /* DEVICE int32 [B]: tokens per sequence; blocks beyond
                              max_blocks are ignored                                  */
 } scout_problem;
@@ -119,7 +122,8 @@ int append_token(const scout_problem* p, int32_t* ctx_len, const void* k_new, co
 /*
  * Block importance (Sec. 2.2, Sec. 3.2, Alg. 1 TopK argument): for each pair
  * and block j, sum over the G query heads of the group and over channels c of
- * max(q[c]*min_j[c], q[c]*max_j[c]).  Unscaled.  Accumulated in binary64 and
+ * max(q[c]*min_j[c], q[c]*max_j[c])  (with group_max = 1: the maximum over the
+ * heads of that sum over channels).  Unscaled.  Accumulated in binary64 and
  * rounded once to binary32.  The always-kept blocks (j < n_sink or
  * j >= nb_b - n_tail) get +inf instead, so that the selection keeps them first
  * (lower index first if the budget cannot hold them all); they count against k.

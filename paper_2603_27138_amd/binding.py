@@ -35,7 +35,8 @@ class Problem(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
                 ("d", ctypes.c_int32), ("S", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("max_blocks", ctypes.c_int32), ("k", ctypes.c_int32), ("sm_scale", ctypes.c_float),
-                ("n_sink", ctypes.c_int32), ("n_tail", ctypes.c_int32), ("ctx_len", ctypes.c_void_p)]
+                ("n_sink", ctypes.c_int32), ("n_tail", ctypes.c_int32), ("group_max", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("ctx_len", ctypes.c_void_p)]
 
 
 _lib = None
@@ -108,10 +109,10 @@ def dtype_code(t: torch.Tensor) -> int:
 
 
 def make_problem(B, Hq, Hkv, d, S, dtype, max_blocks, k, ctx_len: torch.Tensor, sm_scale: float = 0.0,
-                 n_sink: int = 0, n_tail: int = 0):
+                 n_sink: int = 0, n_tail: int = 0, group_max: int = 0):
     assert ctx_len.dtype == torch.int32 and ctx_len.is_cuda
     return Problem(B, Hq, Hkv, d, S, dtype, max_blocks, k, float(sm_scale), int(n_sink), int(n_tail),
-                   ctx_len.data_ptr())
+                   int(group_max), 0, ctx_len.data_ptr())
 
 
 def version() -> int:

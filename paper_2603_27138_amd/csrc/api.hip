@@ -46,7 +46,7 @@ static int check_problem(const scout_problem* p, Dims* D) {
   if (p->max_blocks < 1 || p->k < 1) return SCOUT_EINVAL;
   if (p->dtype != SCOUT_F32 && p->dtype != SCOUT_BF16) return SCOUT_EINVAL;
   if (!(p->sm_scale >= 0.0f) || std::isinf(p->sm_scale)) return SCOUT_EINVAL;
-  if (p->n_sink < 0 || p->n_tail < 0) return SCOUT_EINVAL;
+  if (p->n_sink < 0 || p->n_tail < 0 || (p->group_max != 0 && p->group_max != 1)) return SCOUT_EINVAL;
   if (p->ctx_len == nullptr) return SCOUT_EINVAL;
   if (p->d != 64 && p->d != 128) return SCOUT_EUNSUPPORTED;
   if (p->S != 16 && p->S != 32 && p->S != 64) return SCOUT_EUNSUPPORTED;
@@ -64,6 +64,7 @@ static int check_problem(const scout_problem* p, Dims* D) {
   D->sm_scale = p->sm_scale > 0.0f ? p->sm_scale : 1.0f / std::sqrt((float)p->d);
   D->n_sink = p->n_sink;
   D->n_tail = p->n_tail;
+  D->group_max = p->group_max;
   D->ctx_len = p->ctx_len;
   return SCOUT_OK;
 }

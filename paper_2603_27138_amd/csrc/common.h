@@ -16,6 +16,7 @@ struct Dims {
   int B, Hq, Hkv, G, d, S, max_blocks, k;
   float sm_scale;
   int n_sink, n_tail;  // always-kept blocks at the start and at the end of a sequence
+  int group_max;       // block importance: 0 = sum over the group's heads, 1 = their maximum
   const int32_t* ctx_len;
 };
 

@@ -230,6 +230,102 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_kernel(
   }
 }
 
+// The same stream with the group's heads combined by their maximum instead of their sum.  The fold of
+// the group is not possible then: every head keeps its own estimate, sum over channels of the larger
+// of q*min and q*max (= q*max where q >= 0, q*min elsewhere), reduced over the 8 lanes of an entry
+// head by head.  G times the arithmetic of the folded kernel, on the same loads.
+template <int DT, int DH>
+__global__ __launch_bounds__(kScoreWaves* kWave) void score_max_kernel(Dims D, const void* q, const void* digest,
+                                                                      float* scores) {
+  constexpr int EPL = (DT == SCOUT_BF16) ? 8 : 4;
+  constexpr int ESZ = (DT == SCOUT_BF16) ? 2 : 4;
+  constexpr int EB = 2 * DH * ESZ;
+  constexpr int NL = EB / 128;
+  constexpr int NG = kScoreBatch / NL;
+  constexpr int BLK_PER_WAVE = NG * 8;
+  constexpr int NT = kScoreWaves * kWave;
+  static_assert(NL >= 2 && NL <= kScoreBatch, "layout");
+
+  __shared__ __align__(16) float q_lds[16 * DH];  // the group's queries as binary32, [head][channel]
+
+  const int pair = blockIdx.y;
+  const int b = pair / D.Hkv, g = pair % D.Hkv;
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int nb = num_blocks_of(D, b);
+  const int j_wave = (blockIdx.x * kScoreWaves + wave) * BLK_PER_WAVE;
+  const bool active = j_wave < D.max_blocks;
+
+  // queries first (see score_kernel for why the order of issue matters)
+  constexpr int QPT = (16 * DH + NT - 1) / NT;  // elements per thread
+  float qreg[QPT];
+  const int n_q = D.G * DH;
+#pragma unroll
+  for (int i = 0; i < QPT; ++i) {
+    const int e = threadIdx.x + i * NT;
+    qreg[i] = load1<DT>(q, ((size_t)b * D.Hq + g * D.G) * DH + (e < n_q ? e : n_q - 1));
+  }
+  const char* dpair = static_cast<const char*>(digest) + (size_t)pair * D.max_blocks * EB;
+  const __amdgpu_buffer_rsrc_t rs =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(dpair), 0, active ? nb * EB : 0, 0x00020000);
+  const int voff0 = (j_wave + (lane >> 3)) * EB + (lane & 7) * 16;
+  u32x4 raw[kScoreBatch];
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int it = 0; it < kScoreBatch; ++it)
+    raw[it] = __builtin_bit_cast(
+        u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff0 + (it / NL) * 8 * EB + (it % NL) * 128, 0, 0));
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = 0; i < QPT; ++i) {
+    const int e = threadIdx.x + i * NT;
+    if (e < 16 * DH) q_lds[e] = qreg[i];
+  }
+  __syncthreads();
+
+#pragma unroll
+  for (int gq = 0; gq < NG; ++gq) {
+    // the entry's elements this lane holds: channels (u * 128 / ESZ + (lane & 7) * EPL + i), min and max row
+    float mn[NL / 2][EPL], mx[NL / 2][EPL];
+#pragma unroll
+    for (int u = 0; u < NL / 2; ++u) {
+      const u32x4 a = raw[gq * NL + u], c = raw[gq * NL + u + NL / 2];
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) {
+        if (DT == SCOUT_BF16) {
+          mn[u][i] = (i & 1) ? bf16_hi(a[i >> 1]) : bf16_lo(a[i >> 1]);
+          mx[u][i] = (i & 1) ? bf16_hi(c[i >> 1]) : bf16_lo(c[i >> 1]);
+        } else {
+          mn[u][i] = __uint_as_float(a[i]);
+          mx[u][i] = __uint_as_float(c[i]);
+        }
+      }
+    }
+    double best = -INFINITY;
+    for (int h = 0; h < D.G; ++h) {
+      double acc = 0.0;
+#pragma unroll
+      for (int u = 0; u < NL / 2; ++u) {
+        const float* qh = q_lds + h * DH + u * (128 / ESZ) + (lane & 7) * EPL;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) {
+          const float qv = qh[i];
+          acc = fma((double)qv, (double)(qv >= 0.0f ? mx[u][i] : mn[u][i]), acc);
+        }
+      }
+      acc += partner_f64<2>(acc);
+      acc += partner_f64<1>(acc);
+      acc += partner_f64<0>(acc);
+      best = acc > best ? acc : best;
+    }
+    const int j = j_wave + gq * 8 + (lane >> 3);
+    if ((lane & 7) == 0 && j < D.max_blocks) {
+      const bool kept = j < D.n_sink || j >= nb - D.n_tail;
+      scores[(size_t)pair * D.max_blocks + j] = j < nb ? (kept ? INFINITY : (float)best) : -INFINITY;
+    }
+  }
+}
+
 // ------------------------------------------------------------ host launchers
 
 int launch_digest(const Dims& D, int dtype, const void* k_blocks, void* digest, hipStream_t st) {
@@ -244,8 +340,28 @@ int launch_digest(const Dims& D, int dtype, const void* k_blocks, void* digest, 
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
 }
 
+int launch_score_max(const Dims& D, int dtype, const void* q, const void* digest, float* scores, hipStream_t st) {
+  const int lines = 2 * D.d * (dtype == SCOUT_BF16 ? 2 : 4) / 128;
+  const int blocks_per_wg = kScoreBatch / lines * 8 * kScoreWaves;
+  dim3 grid((D.max_blocks + blocks_per_wg - 1) / blocks_per_wg, D.B * D.Hkv);
+  dim3 block(kScoreWaves * kWave);
+  if (grid.x == 0 || grid.y == 0) return SCOUT_OK;
+  if (dtype == SCOUT_BF16 && D.d == 128)
+    hipLaunchKernelGGL((score_max_kernel<SCOUT_BF16, 128>), grid, block, 0, st, D, q, digest, scores);
+  else if (dtype == SCOUT_BF16 && D.d == 64)
+    hipLaunchKernelGGL((score_max_kernel<SCOUT_BF16, 64>), grid, block, 0, st, D, q, digest, scores);
+  else if (dtype == SCOUT_F32 && D.d == 128)
+    hipLaunchKernelGGL((score_max_kernel<SCOUT_F32, 128>), grid, block, 0, st, D, q, digest, scores);
+  else if (dtype == SCOUT_F32 && D.d == 64)
+    hipLaunchKernelGGL((score_max_kernel<SCOUT_F32, 64>), grid, block, 0, st, D, q, digest, scores);
+  else
+    return SCOUT_EUNSUPPORTED;
+  return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
+}
+
 int launch_score(const Dims& D, int dtype, const void* q, const void* digest, float* scores,
                  hipStream_t st) {
+  if (D.group_max) return launch_score_max(D, dtype, q, digest, scores, st);
   const int lines = 2 * D.d * (dtype == SCOUT_BF16 ? 2 : 4) / 128;  // 128-byte lines per digest entry
   const int blocks_per_wg = kScoreBatch / lines * 8 * kScoreBatches * kScoreWaves;
   dim3 grid((D.max_blocks + blocks_per_wg - 1) / blocks_per_wg, D.B * D.Hkv);

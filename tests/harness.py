@@ -30,7 +30,8 @@ class OraclePair:
     out: list = field(default_factory=list)        # per head (out, lse)
 
 
-def run_pair(wl: W.Workload, b: int, g: int, q=None, table=None, attention: bool = True) -> OraclePair:
+def run_pair(wl: W.Workload, b: int, g: int, q=None, table=None, attention: bool = True,
+             agg: str = "sum") -> OraclePair:
     cfg = wl.cfg
     q = wl.q if q is None else q
     table = wl.block_table if table is None else table
@@ -38,7 +39,7 @@ def run_pair(wl: W.Workload, b: int, g: int, q=None, table=None, attention: bool
     ctx = int(cfg.ctx[b])
     dig = oracle.digest(K, ctx, cfg.S)
     qg = q[b, g * cfg.G:(g + 1) * cfg.G]
-    s = oracle.score(qg, dig)
+    s = oracle.score(qg, dig) if agg == "sum" else oracle.score_max(qg, dig)
     s32 = oracle.decision_scores(s)
     sel = oracle.select(s32, cfg.k)
     sg, ng, sh, nh = oracle.split(sel, table[b, g])

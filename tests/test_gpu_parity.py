@@ -331,6 +331,41 @@ def test_always_kept_blocks(cfg, n_sink, n_tail):
         assert np.array_equal(got_sel[b, g], want[(b, g)]) or harness.boundary_gap(op, cfg.k) < 1e-6, (b, g)
 
 
+def test_group_max_aggregation(cfg):
+    """group_max = 1: the maximum over the group's heads instead of their sum, in score_blocks alone and
+    through the fused layer-step (selection, both partials, merged output)."""
+    if cfg.max_blocks > 4096:
+        pytest.skip("the oracle's attention over the longest pair is run once, in the sum variant")
+    wl, _, dev = setup(cfg)
+    res = harness.run_all(wl, agg="max")
+    dev.set_digest_from_oracle(res)
+    dev.set_host_partials_from_oracle(res)
+    code = B.F32 if cfg.dtype == "f32" else B.BF16
+    p2 = B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, code, cfg.max_blocks, cfg.k, dev.ctx_len, 0.0, group_max=1)
+    B.score_blocks(p2, dev.q, dev.digest, dev.scores, dev.ws)
+    got_s = dev.scores.cpu().numpy()
+    for (b, g), op in res.items():
+        nb = len(op.s32)
+        rel = np.abs(got_s[b, g, :nb].astype(np.float64) - op.s32) / np.maximum(np.abs(op.s32), 1e-30)
+        assert rel.max() <= 2e-7 if nb else True, (b, g)      # one binary32 rounding of nearly equal binary64 sums
+        assert np.isneginf(got_s[b, g, nb:]).all()
+    B.layer_step(p2, dev.q, dev.digest, dev.block_table, dev.k_pool, dev.v_pool, dev.n_slots, dev.host_o, dev.host_m,
+                 dev.host_l, dev.scores, dev.sel_all, dev.sel_gpu, dev.slot_gpu, dev.n_gpu, dev.sel_host, dev.n_host,
+                 dev.out, dev.lse, dev.ws)
+    sel = dev.sel_all.cpu().numpy()
+    out = _f64(to_np(dev.out))
+    for (b, g), op in res.items():
+        if not np.array_equal(sel[b, g], op.sel):
+            assert harness.boundary_gap(op, cfg.k) < 1e-6, (b, g)
+            continue
+        for h in range(cfg.G):
+            want, _ = op.out[h]
+            assert np.abs(out[b, g * cfg.G + h] - want).max() <= TOL[cfg.dtype], (b, g, h)
+    # restore what the other tests of this config expect
+    res0 = _CACHE[cfg.name][1]
+    dev.set_host_partials_from_oracle(res0)
+
+
 def _can_move(cfg):
     """A recall can move something only if blocks live on both sides and some resident block can be unselected."""
     return 0.0 < cfg.p_host < 1.0 and all(cfg.nb(b) > cfg.k for b in range(cfg.B))
