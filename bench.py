@@ -158,6 +158,23 @@ def setup(args) -> State:
     return st
 
 
+def prepared(fn):
+    """The timed loops replay calls whose arguments were marshalled once per layer copy, so that the
+    interpreter's share of a call does not limit how fast launches are issued."""
+    def run(st, i, **kw):
+        if kw:
+            return fn(st, i, **kw)
+        j = i % len(st.sets)
+        cache = st.__dict__.setdefault("_prepared", {})
+        key = (fn.__name__, j)
+        if key not in cache:
+            cache[key] = st.B.prepare(fn, st, j)
+        cache[key]()
+    run.__name__ = fn.__name__
+    return run
+
+
+@prepared
 def step(st, i, ws=None):
     s, p = st.sets[i % len(st.sets)], st.probs[i % len(st.sets)]
     st.B.layer_step(p, s.q, s.digest, s.block_table, s.k_pool, s.v_pool, st.wl.n_slots, s.host_o, s.host_m,
@@ -165,22 +182,26 @@ def step(st, i, ws=None):
                     s.out, s.lse, st.ws if ws is None else ws)
 
 
+@prepared
 def attn_only(st, i):
     s, p = st.sets[i % len(st.sets)], st.probs[i % len(st.sets)]
     st.B.sparse_decode_attn(p, s.q, s.k_pool, s.v_pool, st.wl.n_slots, s.sel_gpu, s.slot_gpu, s.n_gpu,
                             st.part_o, st.part_m, st.part_l, st.ws)
 
 
+@prepared
 def attn_split_only(st, i):
     s, p = st.sets[i % len(st.sets)], st.probs[i % len(st.sets)]
     st.B.attn_partials(p, s.q, s.k_pool, s.v_pool, st.wl.n_slots, s.sel_gpu, s.slot_gpu, s.n_gpu, st.ws)
 
 
+@prepared
 def score_only(st, i):
     s, p = st.sets[i % len(st.sets)], st.probs[i % len(st.sets)]
     st.B.score_blocks(p, s.q, s.digest, s.scores, st.ws)
 
 
+@prepared
 def select_only(st, i):
     s, p = st.sets[i % len(st.sets)], st.probs[i % len(st.sets)]
     st.B.select_topk(p, s.scores, s.block_table, s.sel_all, s.sel_gpu, s.slot_gpu, s.n_gpu, s.sel_host,
@@ -206,6 +227,7 @@ def append_setup(st):
     st.app_p = st.B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, st.B.BF16, cfg.max_blocks, cfg.k, a.ctx_len)
 
 
+@prepared
 def append_only(st, i):
     a = st.app
     st.B.append_token(st.app_p, a.ctx_len, a.k_new, a.v_new, a.new_slot, a.digest, a.block_table, a.k_pool,
@@ -243,18 +265,21 @@ def fetch_setup(st, per_pair=8):
     st.fetch = f
 
 
+@prepared
 def fetch_only(st, i):
     f = st.fetch
     blk, slot = f.plans[i % len(f.plans)]
     st.B.recall_fetch(st.probs[0], f.k, f.v, blk, slot, f.n, f.k_pool, f.v_pool, f.n_slots)
 
 
+@prepared
 def stream_only(st, i):
     """Read-only stream of exactly the digest cache of the layer copy (what score_blocks reads)."""
     s = st.sets[i % len(st.sets)]
     st.B.calib_read(s.digest, s.digest.numel() * s.digest.element_size())
 
 
+@prepared
 def gather_only(st, i):
     """Bare gather of exactly the tiles sparse_decode_attn reads for this layer copy's lists."""
     s, p = st.sets[i % len(st.sets)], st.probs[i % len(st.sets)]

@@ -83,6 +83,45 @@ def _check(fn: str, rc: int):
         raise ScoutError(fn, rc, lib().scout_strerror(rc).decode())
 
 
+_recording = None   # a Prepared being filled: calls are recorded instead of made
+
+
+def _call(fn: str, cfunc, *cargs):
+    if _recording is not None:
+        _recording.calls.append((fn, cfunc, cargs))
+        return
+    _check(fn, cfunc(*cargs))
+
+
+class Prepared:
+    """Calls with their arguments already marshalled (pointers, sizes, stream): replaying them costs
+    one foreign call each.  Valid while the tensors it was prepared with are alive and unmoved, on the
+    stream that was current when it was prepared."""
+
+    def __init__(self):
+        self.calls = []
+
+    def __call__(self):
+        for fn, cfunc, cargs in self.calls:
+            rc = cfunc(*cargs)
+            if rc != 0:
+                _check(fn, rc)
+
+
+def prepare(fn, *args, **kw) -> Prepared:
+    """Record the library calls that fn(*args, **kw) would make (fn: a function of this module, or any
+    function built from them) without making them."""
+    global _recording
+    assert _recording is None, "prepare() does not nest"
+    rec = Prepared()
+    _recording = rec
+    try:
+        fn(*args, **kw)
+    finally:
+        _recording = None
+    return rec
+
+
 def _ptr(t: Optional[torch.Tensor]):
     if t is None:
         return None
@@ -135,77 +174,73 @@ def alloc_workspace(p: Problem, device="cuda") -> torch.Tensor:
 
 def calib_copy(src: torch.Tensor, dst: torch.Tensor):
     n = src.numel() * src.element_size()
-    _check("scout_calib_copy", lib().scout_calib_copy(_ptr(src), _ptr(dst), n, _stream()))
+    _call("scout_calib_copy", lib().scout_calib_copy, _ptr(src), _ptr(dst), n, _stream())
 
 
 def build_digests(p: Problem, k_blocks, digest):
-    _check("build_digests", lib().build_digests(ctypes.byref(p), _ptr(k_blocks), _ptr(digest), _stream()))
+    _call("build_digests", lib().build_digests, ctypes.byref(p), _ptr(k_blocks), _ptr(digest), _stream())
 
 
 def append_token(p: Problem, ctx_len, k_new, v_new, new_slot, digest, block_table, k_pool, v_pool, n_slots):
-    _check("append_token", lib().append_token(ctypes.byref(p), _ptr(ctx_len), _ptr(k_new), _ptr(v_new),
-                                              _ptr(new_slot), _ptr(digest), _ptr(block_table), _ptr(k_pool),
-                                              _ptr(v_pool), int(n_slots), _stream()))
+    _call("append_token", lib().append_token, ctypes.byref(p), _ptr(ctx_len), _ptr(k_new), _ptr(v_new),
+          _ptr(new_slot), _ptr(digest), _ptr(block_table), _ptr(k_pool),
+          _ptr(v_pool), int(n_slots), _stream())
 
 
 def score_blocks(p: Problem, q, digest, scores, ws):
-    _check("score_blocks", lib().score_blocks(ctypes.byref(p), _ptr(q), _ptr(digest), _ptr(scores),
-                                              _ptr(ws), ws.numel(), _stream()))
+    _call("score_blocks", lib().score_blocks, ctypes.byref(p), _ptr(q), _ptr(digest), _ptr(scores),
+          _ptr(ws), ws.numel(), _stream())
 
 
 def select_topk(p: Problem, scores, block_table, sel_all, sel_gpu, slot_gpu, n_gpu, sel_host, n_host, ws):
-    _check("select_topk", lib().select_topk(ctypes.byref(p), _ptr(scores), _ptr(block_table), _ptr(sel_all),
-                                            _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu), _ptr(sel_host),
-                                            _ptr(n_host), _ptr(ws), ws.numel(), _stream()))
+    _call("select_topk", lib().select_topk, ctypes.byref(p), _ptr(scores), _ptr(block_table), _ptr(sel_all),
+          _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu), _ptr(sel_host),
+          _ptr(n_host), _ptr(ws), ws.numel(), _stream())
 
 
 def sparse_decode_attn(p: Problem, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, o, m, l, ws):
-    _check("sparse_decode_attn",
-           lib().sparse_decode_attn(ctypes.byref(p), _ptr(q), _ptr(k_pool), _ptr(v_pool), int(n_slots),
-                                    _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu), _ptr(o), _ptr(m), _ptr(l),
-                                    _ptr(ws), ws.numel(), _stream()))
+    _call("sparse_decode_attn", lib().sparse_decode_attn, ctypes.byref(p), _ptr(q), _ptr(k_pool), _ptr(v_pool), int(n_slots),
+          _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu), _ptr(o), _ptr(m), _ptr(l),
+          _ptr(ws), ws.numel(), _stream())
 
 
 def attn_partials(p: Problem, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, ws):
-    _check("scout_attn_partials",
-           lib().scout_attn_partials(ctypes.byref(p), _ptr(q), _ptr(k_pool), _ptr(v_pool), int(n_slots),
-                                     _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu), _ptr(ws), ws.numel(),
-                                     _stream()))
+    _call("scout_attn_partials", lib().scout_attn_partials, ctypes.byref(p), _ptr(q), _ptr(k_pool), _ptr(v_pool), int(n_slots),
+          _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu), _ptr(ws), ws.numel(),
+          _stream())
 
 
 def merge_partials(p: Problem, o_a, m_a, l_a, o_b, m_b, l_b, out, lse=None):
-    _check("merge_partials", lib().merge_partials(ctypes.byref(p), _ptr(o_a), _ptr(m_a), _ptr(l_a), _ptr(o_b),
-                                                  _ptr(m_b), _ptr(l_b), _ptr(out), _ptr(lse), _stream()))
+    _call("merge_partials", lib().merge_partials, ctypes.byref(p), _ptr(o_a), _ptr(m_a), _ptr(l_a), _ptr(o_b),
+          _ptr(m_b), _ptr(l_b), _ptr(out), _ptr(lse), _stream())
 
 
 def periodic_recall(p: Problem, q, digest, block_table, recall_blk, recall_slot, evict_blk, n_recall, ws):
-    _check("periodic_recall",
-           lib().periodic_recall(ctypes.byref(p), _ptr(q), _ptr(digest), _ptr(block_table), _ptr(recall_blk),
-                                 _ptr(recall_slot), _ptr(evict_blk), _ptr(n_recall), _ptr(ws), ws.numel(),
-                                 _stream()))
+    _call("periodic_recall", lib().periodic_recall, ctypes.byref(p), _ptr(q), _ptr(digest), _ptr(block_table), _ptr(recall_blk),
+          _ptr(recall_slot), _ptr(evict_blk), _ptr(n_recall), _ptr(ws), ws.numel(),
+          _stream())
 
 
 def recall_fetch(p: Problem, src_k, src_v, recall_blk, recall_slot, n_recall, k_pool, v_pool, n_slots):
     """src_k / src_v: tensors in pinned host memory or on the device."""
-    _check("recall_fetch", lib().recall_fetch(ctypes.byref(p), _ptr_addressable(src_k), _ptr_addressable(src_v), _ptr(recall_blk),
-                                              _ptr(recall_slot), _ptr(n_recall), _ptr(k_pool), _ptr(v_pool),
-                                              int(n_slots), _stream()))
+    _call("recall_fetch", lib().recall_fetch, ctypes.byref(p), _ptr_addressable(src_k), _ptr_addressable(src_v), _ptr(recall_blk),
+          _ptr(recall_slot), _ptr(n_recall), _ptr(k_pool), _ptr(v_pool),
+          int(n_slots), _stream())
 
 
 def calib_read(src, nbytes: int, sink=None):
-    _check("scout_calib_read", lib().scout_calib_read(_ptr(src), int(nbytes), _ptr(sink), _stream()))
+    _call("scout_calib_read", lib().scout_calib_read, _ptr(src), int(nbytes), _ptr(sink), _stream())
 
 
 def calib_gather(p: Problem, k_pool, v_pool, n_slots, slot_gpu, n_gpu, sink=None):
-    _check("scout_calib_gather", lib().scout_calib_gather(ctypes.byref(p), _ptr(k_pool), _ptr(v_pool), int(n_slots),
-                                                          _ptr(slot_gpu), _ptr(n_gpu), _ptr(sink), _stream()))
+    _call("scout_calib_gather", lib().scout_calib_gather, ctypes.byref(p), _ptr(k_pool), _ptr(v_pool), int(n_slots),
+          _ptr(slot_gpu), _ptr(n_gpu), _ptr(sink), _stream())
 
 
 def layer_step(p: Problem, q, digest, block_table, k_pool, v_pool, n_slots, host_o, host_m, host_l, scores,
                sel_all, sel_gpu, slot_gpu, n_gpu, sel_host, n_host, out, lse, ws):
-    _check("scout_layer_step",
-           lib().scout_layer_step(ctypes.byref(p), _ptr(q), _ptr(digest), _ptr(block_table), _ptr(k_pool),
-                                  _ptr(v_pool), int(n_slots), _ptr(host_o), _ptr(host_m), _ptr(host_l),
-                                  _ptr(scores), _ptr(sel_all), _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu),
-                                  _ptr(sel_host), _ptr(n_host), _ptr(out), _ptr(lse), _ptr(ws), ws.numel(),
-                                  _stream()))
+    _call("scout_layer_step", lib().scout_layer_step, ctypes.byref(p), _ptr(q), _ptr(digest), _ptr(block_table), _ptr(k_pool),
+          _ptr(v_pool), int(n_slots), _ptr(host_o), _ptr(host_m), _ptr(host_l),
+          _ptr(scores), _ptr(sel_all), _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu),
+          _ptr(sel_host), _ptr(n_host), _ptr(out), _ptr(lse), _ptr(ws), ws.numel(),
+          _stream())

@@ -50,3 +50,24 @@ def test_layer_step_replays_from_a_graph(name):
         got = (to_np(dev.out), dev.sel_all.cpu().numpy(), dev.lse.cpu().numpy(), dev.scores.cpu().numpy())
         for a, b in zip(got, want):
             assert np.array_equal(a.view(np.uint8), b.view(np.uint8)), step
+
+
+def test_prepared_calls_replay_the_eager_result():
+    """binding.prepare marshals the arguments once; replaying gives what the direct call gives."""
+    from paper_2603_27138_amd import binding as B
+    cfg = W.shrink(W.qwen3_32b(B=2, ctx=4096), name="prepared-bf16", k=16)
+    wl = W.generate(cfg)
+    res = harness.run_all(wl)
+    dev = Dev(wl, k_blocks=False)
+    dev.set_digest_from_oracle(res)
+    dev.set_host_partials_from_oracle(res)
+    call = B.prepare(dev.layer_step)
+    assert len(call.calls) == 1 and float(dev.lse.isnan().sum()) > 0    # nothing has run yet
+    dev.layer_step()
+    torch.cuda.synchronize()
+    want = (to_np(dev.out).copy(), dev.sel_all.cpu().numpy().copy())
+    dev.out.zero_(); dev.sel_all.fill_(-9)
+    call()
+    call()
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(dev.out), want[0]) and np.array_equal(dev.sel_all.cpu().numpy(), want[1])
