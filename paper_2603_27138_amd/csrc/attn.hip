@@ -336,6 +336,35 @@ __device__ __forceinline__ void attend_pair(const Dims& D, int pair, int split, 
   }
   __syncthreads();
   const size_t pbase = (size_t)pair * P.nsplit + split;
+  if (E.mode == 0) {
+    // partial of this split: four channels per thread, 16-byte LDS reads and one 16-byte store
+    for (int item = threadIdx.x; item < G * (kMfmaD / 4); item += WAVES * kWave) {
+      const int h = item / (kMfmaD / 4), c = (item % (kMfmaD / 4)) * 4;
+      float mw[WAVES];
+      float M = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w) {
+        mw[w] = smem[(size_t)w * wstride + G * ROW + h];
+        M = fmaxf(M, mw[w]);
+      }
+      float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+      float l = 0.0f;
+#pragma unroll
+      for (int w = 0; w < WAVES; ++w) {
+        const float* base = smem + (size_t)w * wstride;
+        const float f = exp2_diff(mw[w], M);
+        const float4 x = *reinterpret_cast<const float4*>(base + h * ROW + c);
+        o.x += f * x.x; o.y += f * x.y; o.z += f * x.z; o.w += f * x.w;
+        l += f * base[G * ROW + 16 + h];
+      }
+      *reinterpret_cast<float4*>(P.o + (pbase * G + h) * kMfmaD + c) = o;
+      if (c == 0) {
+        P.m[pbase * G + h] = M;
+        P.l[pbase * G + h] = l;
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int t = 0; t < kOutPerThread; ++t) {
     const int idx = threadIdx.x + t * WAVES * kWave;
