@@ -463,8 +463,7 @@ __global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
     for (int r = 0; r < KPL; ++r)
       if (((sel >> r) & 1u) && slot[r] >= 0) gpu |= 1u << r;
     int pos_all[KPL], pos_gpu[KPL];
-    S.positions(sel, pos_all);
-    const int ng = S.positions(gpu, pos_gpu);
+    const int ng = S.positions2(sel, pos_all, gpu, pos_gpu);
     const int nh = k_eff - ng;
     const size_t out0 = (size_t)pair * D.k;
     const bool writer = split == 0;

@@ -107,6 +107,30 @@ struct Selector {
     return total;
   }
 
+  // positions() of two masks with one exchange: the two per-wave counts travel in the halves of one
+  // word (a workgroup holds at most 16384 elements, so neither half can carry into the other).
+  // Returns the total of the second mask.
+  __device__ __forceinline__ int positions2(uint32_t bits_a, int (&pos_a)[KPL], uint32_t bits_b, int (&pos_b)[KPL]) {
+    int ca = 0, cb = 0;
+#pragma unroll
+    for (int r = 0; r < KPL; ++r) {
+      ca += __popcll(__ballot((bits_a >> r) & 1u));
+      cb += __popcll(__ballot((bits_b >> r) & 1u));
+    }
+    int total, off;
+    wg_exchange<WAVES>(ca | (cb << 16), lds, phase, wave, total, off);
+    int off_a = off & 0xffff, off_b = off >> 16;
+#pragma unroll
+    for (int r = 0; r < KPL; ++r) {
+      const uint64_t ma = __ballot((bits_a >> r) & 1u), mb = __ballot((bits_b >> r) & 1u);
+      pos_a[r] = off_a + mbcnt64(ma);
+      pos_b[r] = off_b + mbcnt64(mb);
+      off_a += __popcll(ma);
+      off_b += __popcll(mb);
+    }
+    return total >> 16;
+  }
+
   __device__ __forceinline__ int count(uint32_t bits) {
     int c = 0;
 #pragma unroll

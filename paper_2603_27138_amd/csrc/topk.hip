@@ -29,8 +29,7 @@ __global__ __launch_bounds__(WAVES* kWave) void topk_kernel(
   for (int r = 0; r < KPL; ++r)
     if (((sel >> r) & 1u) && slot[r] >= 0) gpu |= 1u << r;
   int pos_all[KPL], pos_gpu[KPL];
-  S.positions(sel, pos_all);
-  const int ng = S.positions(gpu, pos_gpu);
+  const int ng = S.positions2(sel, pos_all, gpu, pos_gpu);
   const int nh = k_eff - ng;
   const size_t out0 = (size_t)pair * D.k;
 #pragma unroll
@@ -108,8 +107,7 @@ __global__ __launch_bounds__(WAVES* kWave) void recall_kernel(
     evi = S.best(kk, n, true);
   }
   int pos_r[KPL], pos_e[KPL];
-  S.positions(rec, pos_r);
-  S.positions(evi, pos_e);
+  S.positions2(rec, pos_r, evi, pos_e);
   const size_t out0 = (size_t)pair * D.k;
 #pragma unroll
   for (int r = 0; r < KPL; ++r) {
