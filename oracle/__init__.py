@@ -194,20 +194,28 @@ def recall_plan(s: np.ndarray, k: int, table: np.ndarray):
 
 
 def append(dtype: int, S: int, ctx_len: int, k_new: np.ndarray, v_new: np.ndarray, new_slot: int,
-           dig: np.ndarray, table: np.ndarray, k_pool: np.ndarray, v_pool: np.ndarray) -> int:
-    """Decode append for one pair; dig [max_blocks][2][d], table [max_blocks] and the pools
-    [n_slots][S][d] are updated in place.  Returns the new context length."""
+           dig: np.ndarray, table: np.ndarray, k_pool: np.ndarray, v_pool: np.ndarray,
+           host_k: np.ndarray = None, host_v: np.ndarray = None) -> int:
+    """Decode append for one pair; dig [max_blocks][2][d], table [max_blocks], the pools
+    [n_slots][S][d] and (if given) the host's copy of every block [max_blocks][S][d] are updated
+    in place.  Returns the new context length."""
     d = k_new.shape[-1]
     for a in (k_new, v_new, dig, k_pool, v_pool):
         assert a.flags["C_CONTIGUOUS"] and a.dtype == (np.float32 if dtype == F32 else np.uint16)
     assert table.dtype == np.int32 and table.flags["C_CONTIGUOUS"]
     assert dig.shape == (len(table), 2, d) and k_pool.shape[1:] == (S, d) and v_pool.shape == k_pool.shape
+    hk = hv = None
+    if host_k is not None:
+        for a in (host_k, host_v):
+            assert a.flags["C_CONTIGUOUS"] and a.dtype == k_new.dtype and a.shape == (len(table), S, d)
+        hk, hv = host_k.ctypes.data, host_v.ctypes.data
     L = _L()
     L.orc_append.restype = ctypes.c_int
-    L.orc_append.argtypes = [ctypes.c_int] * 5 + [ctypes.c_void_p] * 2 + [ctypes.c_int] + [ctypes.c_void_p] * 4 + [ctypes.c_long]
+    L.orc_append.argtypes = ([ctypes.c_int] * 5 + [ctypes.c_void_p] * 2 + [ctypes.c_int] + [ctypes.c_void_p] * 4 +
+                             [ctypes.c_long] + [ctypes.c_void_p] * 2)
     return L.orc_append(int(dtype), int(S), int(d), len(table), int(ctx_len), k_new.ctypes.data,
                         v_new.ctypes.data, int(new_slot), dig.ctypes.data, table.ctypes.data,
-                        k_pool.ctypes.data, v_pool.ctypes.data, len(k_pool))
+                        k_pool.ctypes.data, v_pool.ctypes.data, len(k_pool), hk, hv)
 
 
 def recall_fetch(src_k: np.ndarray, src_v: np.ndarray, recall_blk, recall_slot, n: int,

@@ -271,14 +271,18 @@ int orc_recall_plan(const double* s, int nb, int k, int* table,
  *     become the key; otherwise a digest element is replaced only where the
  *     key is strictly smaller (row 0) or strictly larger (row 1);
  *   - if the block's table entry is a slot in [0, n_slots), the key and the
- *     value are written to row r of that slot's K and V tiles.
+ *     value are written to row r of that slot's K and V tiles;
+ *   - if the host keeps a copy of every block (host_k / host_v not NULL,
+ *     [max_blocks][S][d] by logical index), the rows are written there as well,
+ *     whatever the residency: the copy a later recall reads from and the reason
+ *     an eviction has nothing to move.
  * dig is [max_blocks][2][d], table [max_blocks], the pools [n_slots][S][d].
  * Returns the new length: ctx_len + 1, or ctx_len unchanged (and nothing
  * written) when the sequence already fills max_blocks blocks.
  */
 int orc_append(int dtype, int S, int d, int max_blocks, int ctx_len, const void* k_new,
                const void* v_new, int new_slot, void* dig, int* table, void* k_pool,
-               void* v_pool, long n_slots) {
+               void* v_pool, long n_slots, void* host_k, void* host_v) {
   if (ctx_len >= max_blocks * S) return ctx_len;
   size_t es = esize(dtype);
   int j = ctx_len / S, r = ctx_len % S;
@@ -295,6 +299,11 @@ int orc_append(int dtype, int S, int d, int max_blocks, int ctx_len, const void*
     size_t row = ((size_t)slot * S + r) * d * es;
     memcpy((char*)k_pool + row, k_new, (size_t)d * es);
     memcpy((char*)v_pool + row, v_new, (size_t)d * es);
+  }
+  if (host_k != NULL && host_v != NULL) {   /* the host's copy of every block, [max_blocks][S][d] */
+    size_t row = ((size_t)j * S + r) * d * es;
+    memcpy((char*)host_k + row, k_new, (size_t)d * es);
+    memcpy((char*)host_v + row, v_new, (size_t)d * es);
   }
   return ctx_len + 1;
 }

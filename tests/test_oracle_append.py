@@ -112,3 +112,29 @@ def test_append_a_planted_mistake_would_show():
     assert not np.array_equal(dig[2, 0].astype(np.float64), no_reset_min)
     swapped = Kf[16:20].max(axis=0)
     assert not np.array_equal(dig[2, 0].astype(np.float64), swapped)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_append_keeps_the_host_copy_complete(dtype):
+    # with a host copy, every token lands there whatever the block's residency: afterwards the copy is
+    # the sequence itself, block by block
+    S, d, n, mb = 8, 4, 29, 5
+    code = oracle.F32 if dtype == "f32" else oracle.BF16
+    K, V = _rand((n, d), 31, dtype), _rand((n, d), 32, dtype)
+    dig = np.zeros((mb, 2, d), dtype=K.dtype)
+    table = np.full(mb, -7, dtype=np.int32)
+    kp, vp = np.zeros((mb, S, d), dtype=K.dtype), np.zeros((mb, S, d), dtype=K.dtype)
+    hk, hv = np.zeros((mb, S, d), dtype=K.dtype), np.zeros((mb, S, d), dtype=K.dtype)
+    ctx, free = 0, [4, 2, 0]
+    for t in range(n):
+        slot = (free.pop() if (t // S) % 2 == 0 else -1) if t % S == 0 else -9
+        ctx = oracle.append(code, S, ctx, K[t].copy(), V[t].copy(), slot, dig, table, kp, vp, hk, hv)
+    assert ctx == n
+    flat_k, flat_v = hk.reshape(mb * S, d), hv.reshape(mb * S, d)
+    assert np.array_equal(flat_k[:n], K) and np.array_equal(flat_v[:n], V)
+    assert (flat_k[n:] == 0).all() and (flat_v[n:] == 0).all()
+    # and a resident block's tile holds the same rows as the host copy
+    for j in range((n + S - 1) // S):
+        if table[j] >= 0:
+            rows = min(S, n - j * S)
+            assert np.array_equal(kp[table[j], :rows], hk[j, :rows]) and np.array_equal(vp[table[j], :rows], hv[j, :rows])
