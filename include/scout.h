@@ -16,7 +16,7 @@
  *
  * Conventions common to every entry point
  *   - Every pointer except `const scout_problem*` is DEVICE memory owned by
- *     the caller (recall_fetch alone also takes pinned host memory).  The library allocates nothing, frees nothing and keeps no
+ *     the caller (recall_fetch and append_token also take pinned host memory).  The library allocates nothing, frees nothing and keeps no
  *     pointer after a call returns.  Scratch comes from the caller's
  *     workspace (`ws`, at least scout_workspace_bytes() bytes, 256-byte
  *     aligned).
@@ -103,6 +103,10 @@ int build_digests(const scout_problem* p, const void* k_blocks, void* digest, vo
  *   - if the block's table entry is a slot in [0, n_slots), the key and value
  *     rows are written to row r of that slot's K and V tiles (a host-resident
  *     tail block is the caller's to extend);
+ *   - if host_k / host_v are given, the rows are also written to the host's copy
+ *     of every block, whatever the block's residency: with it the host always
+ *     holds the whole cache, which is what recall_fetch reads from and why an
+ *     eviction moves nothing;
  *   - ctx_len[b] becomes t + 1.
  * A sequence that already fills max_blocks blocks is left untouched.
  *   ctx_len      i32 [B]              in/out; the lengths to advance (normally
@@ -113,11 +117,13 @@ int build_digests(const scout_problem* p, const void* k_blocks, void* digest, vo
  *   digest       e   [B][Hkv][max_blocks][2][d]   in/out
  *   block_table  i32 [B][Hkv][max_blocks]         in/out
  *   k_pool, v_pool e [n_slots][S][d]              in/out
+ *   host_k, host_v e [B][Hkv][max_blocks][S][d]   in/out, both or neither (NULL);
+ *                  PINNED HOST memory that the GPU can address (or device memory)
  * Copies and comparisons only; the result is exact.
  */
 int append_token(const scout_problem* p, int32_t* ctx_len, const void* k_new, const void* v_new,
                  const int32_t* new_slot, void* digest, int32_t* block_table, void* k_pool,
-                 void* v_pool, int64_t n_slots, void* stream);
+                 void* v_pool, int64_t n_slots, void* host_k, void* host_v, void* stream);
 
 /*
  * Block importance (Sec. 2.2, Sec. 3.2, Alg. 1 TopK argument): for each pair

@@ -59,7 +59,7 @@ def lib():
         L.scout_set_attn_mode.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
         L.scout_workspace_bytes.argtypes = [pp, ctypes.POINTER(sz)]
         L.build_digests.argtypes = [pp, vp, vp, vp]
-        L.append_token.argtypes = [pp] + [vp] * 8 + [i64, vp]
+        L.append_token.argtypes = [pp] + [vp] * 8 + [i64, vp, vp, vp]
         L.score_blocks.argtypes = [pp, vp, vp, vp, vp, sz, vp]
         L.select_topk.argtypes = [pp] + [vp] * 9 + [sz, vp]
         L.sparse_decode_attn.argtypes = [pp, vp, vp, vp, i64] + [vp] * 7 + [sz, vp]
@@ -181,10 +181,14 @@ def build_digests(p: Problem, k_blocks, digest):
     _call("build_digests", lib().build_digests, ctypes.byref(p), _ptr(k_blocks), _ptr(digest), _stream())
 
 
-def append_token(p: Problem, ctx_len, k_new, v_new, new_slot, digest, block_table, k_pool, v_pool, n_slots):
+def append_token(p: Problem, ctx_len, k_new, v_new, new_slot, digest, block_table, k_pool, v_pool, n_slots,
+                 host_k=None, host_v=None):
+    """host_k / host_v: the host's copy of every block (pinned CPU tensors, or device tensors), or None."""
+    hk = None if host_k is None else _ptr_addressable(host_k)
+    hv = None if host_v is None else _ptr_addressable(host_v)
     _call("append_token", lib().append_token, ctypes.byref(p), _ptr(ctx_len), _ptr(k_new), _ptr(v_new),
           _ptr(new_slot), _ptr(digest), _ptr(block_table), _ptr(k_pool),
-          _ptr(v_pool), int(n_slots), _stream())
+          _ptr(v_pool), int(n_slots), hk, hv, _stream())
 
 
 def score_blocks(p: Problem, q, digest, scores, ws):

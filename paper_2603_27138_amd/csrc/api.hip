@@ -13,7 +13,7 @@ int launch_score(const Dims&, int, const void*, const void*, float*, hipStream_t
 int launch_recall_fetch(const Dims&, int, const void*, const void*, const int32_t*, const int32_t*, const int32_t*,
                         void*, void*, long long, hipStream_t);
 int launch_append(const Dims&, int, int32_t*, const void*, const void*, const int32_t*, void*, int32_t*, void*, void*,
-                  long long, hipStream_t);
+                  long long, void*, void*, hipStream_t);
 int launch_topk(const Dims&, const float*, const int32_t*, int32_t*, int32_t*, int32_t*, int32_t*,
                 int32_t*, int32_t*, hipStream_t);
 int launch_recall(const Dims&, const float*, int32_t*, int32_t*, int32_t*, int32_t*, int32_t*,
@@ -307,7 +307,7 @@ int build_digests(const scout_problem* p, const void* k_blocks, void* digest, vo
 
 int append_token(const scout_problem* p, int32_t* ctx_len, const void* k_new, const void* v_new,
                  const int32_t* new_slot, void* digest, int32_t* block_table, void* k_pool, void* v_pool,
-                 int64_t n_slots, void* stream) {
+                 int64_t n_slots, void* host_k, void* host_v, void* stream) {
   Dims D;
   int rc = check_problem(p, &D);
   if (rc != SCOUT_OK) return rc;
@@ -316,8 +316,9 @@ int append_token(const scout_problem* p, int32_t* ctx_len, const void* k_new, co
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(digest) || !aligned16(k_pool) || !aligned16(v_pool))
     return SCOUT_EINVAL;
   if (n_slots < 0) return SCOUT_EINVAL;
+  if ((host_k == nullptr) != (host_v == nullptr) || !aligned16(host_k) || !aligned16(host_v)) return SCOUT_EINVAL;
   return launch_append(D, p->dtype, ctx_len, k_new, v_new, new_slot, digest, block_table, k_pool, v_pool,
-                       n_slots, static_cast<hipStream_t>(stream));
+                       n_slots, host_k, host_v, static_cast<hipStream_t>(stream));
 }
 
 int score_blocks(const scout_problem* p, const void* q, const void* digest, float* scores, void* ws,

@@ -17,7 +17,7 @@ __global__ __launch_bounds__(1024) void append_kernel(Dims D, int32_t* ctx_len, 
                                                      const void* __restrict__ v_new,
                                                      const int32_t* __restrict__ new_slot, void* digest,
                                                      int32_t* block_table, void* k_pool, void* v_pool,
-                                                     long long n_slots) {
+                                                     long long n_slots, void* host_k, void* host_v) {
   using E = typename std::conditional<DT == SCOUT_BF16, uint16_t, float>::type;
   const int b = blockIdx.x;
   const int t = ctx_len[b];
@@ -29,6 +29,8 @@ __global__ __launch_bounds__(1024) void append_kernel(Dims D, int32_t* ctx_len, 
     E* dg = static_cast<E*>(digest);
     E* kp = static_cast<E*>(k_pool);
     E* vp = static_cast<E*>(v_pool);
+    E* hk = static_cast<E*>(host_k);  // the host's copy of every block (pinned memory), or null
+    E* hv = static_cast<E*>(host_v);
     for (int e = threadIdx.x; e < D.Hkv * D.d; e += blockDim.x) {
       const int g = e / D.d, c = e % D.d;
       const size_t pair = (size_t)b * D.Hkv + g;
@@ -51,6 +53,12 @@ __global__ __launch_bounds__(1024) void append_kernel(Dims D, int32_t* ctx_len, 
         kp[row] = k;
         vp[row] = v;
       }
+      if (hk != nullptr) {  // whatever the residency: this is what a later recall reads, and why an
+                            // eviction has nothing to move
+        const size_t row = ((pair * D.max_blocks + j) * D.S + r) * D.d + c;
+        hk[row] = k;
+        hv[row] = v;
+      }
       if (r == 0 && c == 0) *entry = slot;  // nobody reads the entry in this call when r == 0
     }
   }
@@ -60,7 +68,7 @@ __global__ __launch_bounds__(1024) void append_kernel(Dims D, int32_t* ctx_len, 
 
 int launch_append(const Dims& D, int dtype, int32_t* ctx_len, const void* k_new, const void* v_new,
                   const int32_t* new_slot, void* digest, int32_t* block_table, void* k_pool, void* v_pool,
-                  long long n_slots, hipStream_t st) {
+                  long long n_slots, void* host_k, void* host_v, hipStream_t st) {
   if (D.B == 0) return SCOUT_OK;
   // one element per thread where the sequence's row fits a workgroup: the call is a chain of
   // dependent round trips (length, table entry, digest), so it should walk that chain once
@@ -68,10 +76,10 @@ int launch_append(const Dims& D, int dtype, int32_t* ctx_len, const void* k_new,
   const dim3 block(elems >= 1024 ? 1024 : (elems + 63) / 64 * 64);
   if (dtype == SCOUT_BF16)
     hipLaunchKernelGGL(append_kernel<SCOUT_BF16>, dim3(D.B), block, 0, st, D, ctx_len, k_new, v_new, new_slot,
-                       digest, block_table, k_pool, v_pool, n_slots);
+                       digest, block_table, k_pool, v_pool, n_slots, host_k, host_v);
   else
     hipLaunchKernelGGL(append_kernel<SCOUT_F32>, dim3(D.B), block, 0, st, D, ctx_len, k_new, v_new, new_slot,
-                       digest, block_table, k_pool, v_pool, n_slots);
+                       digest, block_table, k_pool, v_pool, n_slots, host_k, host_v);
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
 }
 

@@ -35,6 +35,8 @@ class State:
         self.table = np.full((Bn, Hkv, max_blocks), -1, dtype=np.int32)
         self.kp = np.zeros((self.n_slots, S, d), dtype=st)
         self.vp = np.zeros((self.n_slots, S, d), dtype=st)
+        self.hk = np.zeros((Bn, Hkv, max_blocks, S, d), dtype=st)   # the host's copy of every block
+        self.hv = np.zeros((Bn, Hkv, max_blocks, S, d), dtype=st)
         self.free = list(self.rng.permutation(self.n_slots))
         self.K = {(b, g): np.zeros((max_blocks * S, d), dtype=st) for b in range(Bn) for g in range(Hkv)}
         self.V = {(b, g): np.zeros((max_blocks * S, d), dtype=st) for b in range(Bn) for g in range(Hkv)}
@@ -65,7 +67,7 @@ class State:
             new = t
             for g in range(self.Hkv):
                 new = oracle.append(self.code, self.S, t, k[b, g].copy(), v[b, g].copy(), int(ns[b, g]),
-                                    self.dig[b, g], self.table[b, g], self.kp, self.vp)
+                                    self.dig[b, g], self.table[b, g], self.kp, self.vp, self.hk[b, g], self.hv[b, g])
                 if new > t:
                     self.K[(b, g)][t], self.V[(b, g)][t] = k[b, g], v[b, g]
             self.ctx[b] = new
@@ -75,6 +77,8 @@ class State:
         self.d_dig = to_dev(self.dig.copy())
         self.d_table = torch.from_numpy(self.table.copy()).cuda()
         self.d_kp, self.d_vp = to_dev(self.kp.copy()), to_dev(self.vp.copy())
+        as_t = lambda a: torch.from_numpy(a.view(np.int16).copy() if a.dtype == np.uint16 else a.copy())
+        self.p_hk, self.p_hv = as_t(self.hk).pin_memory(), as_t(self.hv).pin_memory()   # read and written by the GPU
 
     def problem(self, Hq, k):
         return B.make_problem(self.Bn, Hq, self.Hkv, self.d, self.S, B.F32 if self.dtype == "f32" else B.BF16,
@@ -82,7 +86,7 @@ class State:
 
     def dev_append(self, p, k, v, ns):
         B.append_token(p, self.d_ctx, to_dev(k), to_dev(v), torch.from_numpy(ns).cuda(), self.d_dig, self.d_table,
-                       self.d_kp, self.d_vp, self.n_slots)
+                       self.d_kp, self.d_vp, self.n_slots, self.p_hk, self.p_hv)
 
     def assert_same(self, tag):
         assert np.array_equal(self.d_ctx.cpu().numpy(), self.ctx), tag
@@ -90,6 +94,9 @@ class State:
         assert np.array_equal(to_np(self.d_dig), self.dig), tag
         assert np.array_equal(to_np(self.d_kp), self.kp), tag
         assert np.array_equal(to_np(self.d_vp), self.vp), tag
+        torch.cuda.synchronize()
+        view = lambda t: t.numpy().view(np.uint16) if self.dtype == "bf16" else t.numpy()
+        assert np.array_equal(view(self.p_hk), self.hk) and np.array_equal(view(self.p_hv), self.hv), tag
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -123,6 +130,8 @@ def test_append_rejects_bad_arguments():
         assert e.value.code == B.EINVAL
     with pytest.raises(B.ScoutError):
         B.append_token(p, *args, -1)
+    with pytest.raises(B.ScoutError):
+        B.append_token(p, *args, st.n_slots, st.p_hk, None)      # the host copy is both arrays or neither
     torch.cuda.synchronize()
     st.assert_same("untouched")
 
