@@ -272,6 +272,28 @@ def fetch_only(st, i):
     st.B.recall_fetch(st.probs[0], f.k, f.v, blk, slot, f.n, f.k_pool, f.v_pool, f.n_slots)
 
 
+def recall_setup(st):
+    """Private copies of the tables (the plan updates them in place) and plan outputs."""
+    torch, cfg = st.torch, st.cfg
+    i32 = dict(dtype=torch.int32, device="cuda")
+    st.rec = []
+    for s in st.sets:
+        r = LayerSet()
+        r.table = s.block_table.clone()
+        r.blk, r.slot, r.evict = (torch.empty(cfg.B, cfg.Hkv, cfg.k, **i32) for _ in range(3))
+        r.n = torch.empty(cfg.B, cfg.Hkv, **i32)
+        st.rec.append(r)
+
+
+@prepared
+def recall_only(st, i):
+    """Rescore + recall plan.  The first call on a copy moves blocks; later ones find nothing to move but
+    do the same scoring and selections."""
+    j = i % len(st.sets)
+    s, p, r = st.sets[j], st.probs[j], st.rec[j]
+    st.B.periodic_recall(p, s.q, s.digest, r.table, r.blk, r.slot, r.evict, r.n, st.ws)
+
+
 @prepared
 def stream_only(st, i):
     """Read-only stream of exactly the digest cache of the layer copy (what score_blocks reads)."""
@@ -439,6 +461,8 @@ def main():
         gather_only(st, i)
     us_stream = timed(st, stream_only, args.steps)
     us_gather = timed(st, gather_only, args.steps)
+    recall_setup(st)
+    us_recall = timed(st, recall_only, args.steps)
     append_setup(st)
     assert cfg.S * (cfg.max_blocks // 2) + args.steps + args.warmup < cfg.S * cfg.max_blocks
     for i in range(args.warmup):
@@ -485,7 +509,8 @@ def main():
         "kv_gbps": round(attn_gbps, 1),
         "kernels_us": {"score_blocks": round(us_score, 3), "select_topk": round(us_select, 3),
                        "attn_mfma_kernel": round(us_attn_kernel, 3), "sparse_decode_attn": round(us_attn, 3),
-                       "append_token": round(us_append, 3), "recall_fetch": round(us_fetch, 1)},
+                       "append_token": round(us_append, 3), "periodic_recall": round(us_recall, 3),
+                       "recall_fetch": round(us_fetch, 1)},
         "recall_h2d_gbps": round(st.fetch.bytes / us_fetch * 1e-3, 1),
         "score_gbps": round(score_gbps, 1),
         # what this GPU sustains for the same bytes with nothing computed (same buffers, same rotation):
