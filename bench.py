@@ -383,26 +383,29 @@ def pipeline_main(args):
 
     pipe = P.LayerAheadPipeline(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, B.BF16, cfg.max_blocks, cfg.k, ctx_len, layers,
                                 n_threads=args.pipe_threads, filler=filler)
-    steps = max(4, args.steps // (4 * n_layers))
+    steps = max(8, args.steps // (2 * n_layers))
 
     def run(host):
-        for _ in range(2):
+        """Median over decode steps of the wall time of a step (all layers, drained at its end, as a
+        step ends with sampling anyway), per layer."""
+        for _ in range(3):
             pipe.step(qs, qps, host=host)
         torch.cuda.synchronize()
-        hs, ws = [], []
-        t0 = time.perf_counter()
+        hs, ws, ts = [], [], []
         for _ in range(steps):
+            t0 = time.perf_counter()
             pipe.step(qs, qps, host=host)
+            torch.cuda.synchronize()
+            ts.append(time.perf_counter() - t0)
             hs += pipe.host_seconds
             ws += pipe.wait_seconds
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) * 1e6 / (steps * n_layers), hs, ws
+        return float(np.median(ts)) * 1e6 / n_layers, hs, ws
 
     us_pipe, hs, ws = run(True)
     us_gpu, _, _ = run(False)
     n_host_blocks = int(sum(int(b.n_host_h.sum()) for b in pipe.buf)) / n_layers
     host_bytes = n_host_blocks * 2 * cfg.S * cfg.d * 2
-    host_us = float(np.mean(hs)) * 1e6
+    host_us = float(np.median(hs)) * 1e6
     pipe.close()
     print(json.dumps({
         "metric": "layer-ahead pipeline us/layer (select ahead with predicted query, host worker, GPU attention, merge"
@@ -416,7 +419,7 @@ def pipeline_main(args):
         "host_blocks_per_layer": round(n_host_blocks, 1),
         "host_job_us": round(host_us, 1),
         "host_gbps": round(host_bytes / host_us * 1e-3, 2),
-        "enqueue_thread_wait_us": round(float(np.mean(ws)) * 1e6, 1),
+        "enqueue_thread_wait_us": round(float(np.median(ws)) * 1e6, 1),
     }))
 
 
