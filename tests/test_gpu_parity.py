@@ -40,7 +40,10 @@ def small_configs():
     kbig = W.shrink(W.qwen3_32b(B=2, ctx=0), name="bf16-k-beyond-nb", ctx=(640, 32), k=64, p_host=0.4)
     onetok = W.shrink(W.qwen3_8b(B=2, ctx=0), name="bf16-one-token", ctx=(1, 33), k=4, p_host=0.5)
     huge = W.shrink(W.long_context(B=1, ctx=262144), name="bf16-8192-blocks", Hq=2, Hkv=1, k=200, p_host=0.9)
-    return [W.tiny(), c2, c3, c4, c5, ragged, ragged32, d64, s64, s16, g16, g1, allhost, allgpu, kbig, onetok, huge]
+    empty = W.shrink(W.qwen3_8b(B=3, ctx=0), name="bf16-empty-sequence", ctx=(0, 64, 1), k=4, p_host=0.5)
+    empty32 = W.shrink(W.tiny(), name="f32-empty-sequence", B=2, Hq=4, Hkv=2, ctx=(0, 40), k=3, p_host=0.5)
+    return [W.tiny(), c2, c3, c4, c5, ragged, ragged32, d64, s64, s16, g16, g1, allhost, allgpu, kbig, onetok, huge,
+            empty, empty32]
 
 
 _CACHE = {}
@@ -263,7 +266,10 @@ def test_layer_step_end_to_end(cfg):
                 err = np.abs(out[b, hq] - want).max()
                 worst = max(worst, err)
                 assert err <= TOL[cfg.dtype], (b, g, h, err, mode)
-                assert abs(lse[b, hq] - wlse) <= LSE_TOL[cfg.dtype] * max(1.0, abs(wlse))
+                if np.isneginf(wlse):      # nothing attended to on either side (an empty sequence)
+                    assert np.isneginf(lse[b, hq]) and (out[b, hq] == 0).all()
+                else:
+                    assert abs(lse[b, hq] - wlse) <= LSE_TOL[cfg.dtype] * max(1.0, abs(wlse))
         print(f"{cfg.name} mode {mode}: layer step max |out - oracle| = {worst:.3e}")
 
 
