@@ -42,8 +42,10 @@ def small_configs():
     huge = W.shrink(W.long_context(B=1, ctx=262144), name="bf16-8192-blocks", Hq=2, Hkv=1, k=200, p_host=0.9)
     empty = W.shrink(W.qwen3_8b(B=3, ctx=0), name="bf16-empty-sequence", ctx=(0, 64, 1), k=4, p_host=0.5)
     empty32 = W.shrink(W.tiny(), name="f32-empty-sequence", B=2, Hq=4, Hkv=2, ctx=(0, 40), k=3, p_host=0.5)
+    # the largest shape the library takes: 16384 blocks per pair (524288 tokens), a budget of 1024 blocks
+    biggest = W.shrink(W.long_context(B=1, ctx=524288), name="bf16-max-sizes", Hq=2, Hkv=1, k=1024, p_host=0.6)
     return [W.tiny(), c2, c3, c4, c5, ragged, ragged32, d64, s64, s16, g16, g1, allhost, allgpu, kbig, onetok, huge,
-            empty, empty32]
+            empty, empty32, biggest]
 
 
 _CACHE = {}
