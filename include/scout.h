@@ -194,6 +194,21 @@ int scout_attn_partials(const scout_problem* p, const void* q, const void* k_poo
                         void* stream);
 
 /*
+ * Second half to scout_attn_partials for a caller that starts the GPU's
+ * attention before the host's partial has arrived (the layer-ahead pipeline of
+ * Sec. 3.3): folds the per-split partials that the preceding
+ * scout_attn_partials call (same problem, same workspace, same stream or
+ * ordered after it) left in the workspace and merges them with the host's
+ * partial (Alg. 1 Merge) in one pass, instead of exporting (o, m, l) and
+ * merging in a further launch.  host_* may be all NULL; lse may be NULL.
+ *   host_o f32 [B][Hq][d], host_m, host_l f32 [B][Hq];  out e [B][Hq][d];  lse f32 [B][Hq]
+ * The attention mode must not be changed between the two calls.
+ */
+int scout_attn_finish(const scout_problem* p, const float* host_o, const float* host_m,
+                      const float* host_l, void* out, float* lse, void* ws, size_t ws_bytes,
+                      void* stream);
+
+/*
  * Merge of two partial results (Alg. 1 Merge; FlashAttention rescaling):
  *   m* = max(m_a, m_b), w_x = l_x exp(m_x - m*), out = (w_a o_a + w_b o_b)/(w_a + w_b),
  *   lse = m* + ln(w_a + w_b).  A side with l = 0 has weight 0.

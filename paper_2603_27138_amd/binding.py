@@ -22,7 +22,7 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 EXPORTS = ["scout_version", "scout_strerror", "scout_workspace_bytes", "build_digests", "append_token", "score_blocks",
            "select_topk", "sparse_decode_attn", "merge_partials", "periodic_recall", "recall_fetch",
            "scout_layer_step", "scout_set_attn_mode", "scout_calib_copy", "scout_attn_partials",
-           "scout_calib_read", "scout_calib_gather"]
+           "scout_calib_read", "scout_calib_gather", "scout_attn_finish"]
 
 
 class ScoutError(RuntimeError):
@@ -70,6 +70,7 @@ def lib():
         L.scout_calib_read.argtypes = [vp, sz, vp, vp]
         L.scout_calib_gather.argtypes = [pp, vp, vp, i64, vp, vp, vp, vp]
         L.scout_attn_partials.argtypes = [pp, vp, vp, vp, i64] + [vp] * 4 + [sz, vp]
+        L.scout_attn_finish.argtypes = [pp] + [vp] * 6 + [sz, vp]
         L.scout_layer_step.argtypes = [pp, vp, vp, vp, vp, vp, i64] + [vp] * 13 + [sz, vp]
         for name in EXPORTS:
             if name not in ("scout_strerror",):
@@ -212,6 +213,11 @@ def attn_partials(p: Problem, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_g
     _call("scout_attn_partials", lib().scout_attn_partials, ctypes.byref(p), _ptr(q), _ptr(k_pool), _ptr(v_pool), int(n_slots),
           _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu), _ptr(ws), ws.numel(),
           _stream())
+
+
+def attn_finish(p: Problem, host_o, host_m, host_l, out, lse, ws):
+    _call("scout_attn_finish", lib().scout_attn_finish, ctypes.byref(p), _ptr(host_o), _ptr(host_m), _ptr(host_l),
+          _ptr(out), _ptr(lse), _ptr(ws), ws.numel(), _stream())
 
 
 def merge_partials(p: Problem, o_a, m_a, l_a, o_b, m_b, l_b, out, lse=None):

@@ -368,6 +368,31 @@ int scout_attn_partials(const scout_problem* p, const void* q, const void* k_poo
                      carve(ws, L, A.nsplit), part, static_cast<hipStream_t>(stream));
 }
 
+int scout_attn_finish(const scout_problem* p, const float* host_o, const float* host_m, const float* host_l,
+                      void* out, float* lse, void* ws, size_t ws_bytes, void* stream) {
+  Dims D;
+  int rc = check_problem(p, &D);
+  if (rc != SCOUT_OK) return rc;
+  if (!out || !aligned16(out)) return SCOUT_EINVAL;
+  const bool any_b = host_o || host_m || host_l, all_b = host_o && host_m && host_l;
+  if (any_b && !all_b) return SCOUT_EINVAL;
+  WsLayout L;
+  rc = check_ws(D, ws, ws_bytes, &L);
+  if (rc != SCOUT_OK) return rc;
+  AttnPlan A;
+  rc = plan_attn(D, p->dtype, &A);  // the same plan scout_attn_partials made: same split count
+  if (rc != SCOUT_OK) return rc;
+  Epilogue E{};
+  E.mode = 2;
+  E.host_o = host_o;
+  E.host_m = host_m;
+  E.host_l = host_l;
+  E.out = out;
+  E.lse = lse;
+  E.dtype_out = p->dtype;
+  return launch_combine(D, carve(ws, L, A.nsplit), E, static_cast<hipStream_t>(stream));
+}
+
 int sparse_decode_attn(const scout_problem* p, const void* q, const void* k_pool, const void* v_pool,
                        int64_t n_slots, const int32_t* sel_gpu, const int32_t* slot_gpu,
                        const int32_t* n_gpu, float* o, float* m, float* l, void* ws, size_t ws_bytes,

@@ -42,7 +42,6 @@ class _LayerBuffers:
         self.scores = torch.empty(*pairs, mb, **f32)
         self.sel_all, self.sel_gpu, self.slot_gpu, self.sel_host = (torch.empty(*pairs, k, **i32) for _ in range(4))
         self.n_gpu, self.n_host = torch.empty(pairs, **i32), torch.empty(pairs, **i32)
-        self.o, self.m, self.l = torch.empty(Bn, Hq, d, **f32), torch.empty(Bn, Hq, **f32), torch.empty(Bn, Hq, **f32)
         self.ho, self.hm, self.hl = torch.empty(Bn, Hq, d, **f32), torch.empty(Bn, Hq, **f32), torch.empty(Bn, Hq, **f32)
         self.out = torch.empty(Bn, Hq, d, dtype=tdt, **dev)
         self.lse = torch.empty(Bn, Hq, **f32)
@@ -99,15 +98,15 @@ class LayerAheadPipeline:
     # -- Algorithm 1, "compute current layer's attention" and "merge"
     def _attend(self, i: int, q: torch.Tensor):
         L, b = self.layers[i], self.buf[i]
-        B.sparse_decode_attn(self.p, q, L.k_pool, L.v_pool, L.n_slots, b.sel_gpu, b.slot_gpu, b.n_gpu, b.o, b.m,
-                             b.l, self.ws)
+        # the per-split partials stay in the workspace until _merge folds them together with the host's
+        B.attn_partials(self.p, q, L.k_pool, L.v_pool, L.n_slots, b.sel_gpu, b.slot_gpu, b.n_gpu, self.ws)
 
     def _merge(self, i: int):
         b = self.buf[i]
         b.ho.copy_(b.ho_h, non_blocking=True)
         b.hm.copy_(b.hm_h, non_blocking=True)
         b.hl.copy_(b.hl_h, non_blocking=True)
-        B.merge_partials(self.p, b.o, b.m, b.l, b.ho, b.hm, b.hl, b.out, b.lse)
+        B.attn_finish(self.p, b.ho, b.hm, b.hl, b.out, b.lse, self.ws)
 
     def step(self, qs: List[torch.Tensor], q_preds: List[torch.Tensor], host: bool = True):
         """One decode step over all layers.  qs[i]: the real query of layer i, q_preds[i]: the one

@@ -374,6 +374,29 @@ def test_group_max_aggregation(cfg):
     dev.set_host_partials_from_oracle(res0)
 
 
+def test_attn_partials_then_finish_equals_attention_then_merge(cfg):
+    """The two-call form the pipeline uses (partials first, fold + merge with the host's partial once it
+    has arrived) gives bit for bit what sparse_decode_attn followed by merge_partials gives."""
+    wl, res, dev = setup(cfg)
+    dev.set_selection_from_oracle(res)
+    dev.set_host_partials_from_oracle(res)
+    dev.attn()
+    dev.merge(host=True)
+    want_out, want_lse = to_np(dev.out).copy(), dev.lse.cpu().numpy().copy()
+    dev.out.zero_()
+    dev.lse.zero_()
+    B.attn_partials(dev.p, dev.q, dev.k_pool, dev.v_pool, dev.n_slots, dev.sel_gpu, dev.slot_gpu, dev.n_gpu, dev.ws)
+    B.attn_finish(dev.p, dev.host_o, dev.host_m, dev.host_l, dev.out, dev.lse, dev.ws)
+    got_out, got_lse = _f64(to_np(dev.out)), dev.lse.cpu().numpy()
+    # same arithmetic up to where the GPU partial is normalised: the one-pass form does not round o to
+    # binary32 between the fold and the merge, so allow the last bits of the storage type
+    tol = 1e-6 if cfg.dtype == "f32" else 8e-3
+    assert np.abs(got_out - _f64(want_out)).max() <= tol
+    both = np.isfinite(want_lse)
+    assert np.array_equal(np.isfinite(got_lse), both) and np.abs(got_lse[both] - want_lse[both]).max() <= 1e-5 * max(
+        1.0, float(np.abs(want_lse[both]).max()) if both.any() else 1.0)
+
+
 def _can_move(cfg):
     """A recall can move something only if blocks live on both sides and some resident block can be unselected."""
     return 0.0 < cfg.p_host < 1.0 and all(cfg.nb(b) > cfg.k for b in range(cfg.B))
