@@ -272,8 +272,10 @@ __device__ __forceinline__ void attend_pair(const Dims& D, int pair, int split, 
 
   // this wave's contiguous share of the pair's units
   const int n_units = n * upb, n_waves = P.nsplit * WAVES, v = split * WAVES + wave;
-  const int u0 = (int)((long long)v * n_units / n_waves);
-  const int u1 = (int)((long long)(v + 1) * n_units / n_waves);
+  // at most 1024 waves share at most 4096 units: the products fit 32 bits (a 64-bit division is a
+  // few hundred instructions here)
+  const int u0 = (int)((uint32_t)(v * n_units) / (uint32_t)n_waves);
+  const int u1 = (int)((uint32_t)((v + 1) * n_units) / (uint32_t)n_waves);
 
   WaveState W;
 #pragma unroll
