@@ -31,7 +31,6 @@ int launch_merge(const Dims&, int, const float*, const float*, const float*, con
 
 constexpr int kMaxSplit = 64;
 constexpr int kValuHeadsPerWave = 4;
-constexpr int kMfmaWavesPerWg = 4;
 
 static int g_family = 0;  // 0 auto, 1 vector ALU, 2 MFMA
 static int g_nsplit = 0;  // 0 auto
@@ -137,19 +136,14 @@ static int plan_attn(const Dims& D, int dtype, AttnPlan* out) {
   return SCOUT_OK;
 }
 
-// Attention over the listed blocks, then what E asks for.  One launch when a single MFMA workgroup
-// covers a pair, otherwise the split pass followed by the combine pass.
-static int run_attn(const Dims& D, int dtype, const AttnPlan& A, const void* q, const void* k_pool,
-                    const void* v_pool, long long n_slots, const int32_t* sel_gpu,
-                    const int32_t* slot_gpu, const int32_t* n_gpu, void* ws, const WsLayout& L,
-                    Epilogue E, hipStream_t st);
-
 static Partials carve(void* ws, const WsLayout& L, int nsplit) {
   char* base = static_cast<char*>(ws);
   return Partials{reinterpret_cast<float*>(base + L.part_o), reinterpret_cast<float*>(base + L.part_m),
                   reinterpret_cast<float*>(base + L.part_l), nsplit};
 }
 
+// Attention over the listed blocks, then what E asks for.  One launch when a single MFMA workgroup
+// covers a pair, otherwise the split pass followed by the combine pass.
 static int run_attn(const Dims& D, int dtype, const AttnPlan& A, const void* q, const void* k_pool,
                     const void* v_pool, long long n_slots, const int32_t* sel_gpu,
                     const int32_t* slot_gpu, const int32_t* n_gpu, void* ws, const WsLayout& L,
