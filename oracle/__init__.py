@@ -235,6 +235,47 @@ def recall_fetch(src_k: np.ndarray, src_v: np.ndarray, recall_blk, recall_slot, 
                               rs.ctypes.data, int(n), k_pool.ctypes.data, v_pool.ctypes.data, len(k_pool))
 
 
+def recall_stage(src_k: np.ndarray, src_v: np.ndarray, recall_blk: np.ndarray, n_recall: np.ndarray):
+    """Packs the tiles that the plans of all pairs name.  src_k / src_v are [pairs][max_blocks][S][d],
+    recall_blk is [pairs][k], n_recall is [pairs].  Returns (staged [tiles][2][S][d], tile_off [pairs])."""
+    pairs, mb, S, d = src_k.shape
+    assert src_v.shape == src_k.shape and src_k.flags["C_CONTIGUOUS"] and src_v.flags["C_CONTIGUOUS"]
+    rb = np.ascontiguousarray(recall_blk, dtype=np.int32)
+    nr = np.ascontiguousarray(n_recall, dtype=np.int32)
+    k = rb.shape[1]
+    assert rb.shape == (pairs, k) and nr.shape == (pairs,)
+    total = int(np.clip(nr, 0, k).sum())
+    staged = np.zeros((total, 2, S, d), dtype=src_k.dtype)
+    off = np.zeros(pairs, dtype=np.int32)
+    L = _L()
+    L.orc_recall_stage.restype = ctypes.c_long
+    L.orc_recall_stage.argtypes = [ctypes.c_int] * 6 + [ctypes.c_void_p] * 6
+    got = L.orc_recall_stage(_dtype_code(src_k), S, d, mb, k, pairs, src_k.ctypes.data, src_v.ctypes.data,
+                             rb.ctypes.data, nr.ctypes.data, staged.ctypes.data, off.ctypes.data)
+    assert got == total
+    return staged, off
+
+
+def recall_scatter(staged: np.ndarray, tile_off: np.ndarray, recall_blk: np.ndarray, recall_slot: np.ndarray,
+                   n_recall: np.ndarray, max_blocks: int, k_pool: np.ndarray, v_pool: np.ndarray) -> int:
+    """Puts staged tiles into the pools [n_slots][S][d] (updated in place).  Returns the number placed."""
+    rb = np.ascontiguousarray(recall_blk, dtype=np.int32)
+    rs = np.ascontiguousarray(recall_slot, dtype=np.int32)
+    nr = np.ascontiguousarray(n_recall, dtype=np.int32)
+    off = np.ascontiguousarray(tile_off, dtype=np.int32)
+    pairs, k = rb.shape
+    n_slots, S, d = k_pool.shape
+    for a in (staged, k_pool, v_pool):
+        assert a.flags["C_CONTIGUOUS"] and a.dtype == k_pool.dtype
+    assert staged.shape[1:] == (2, S, d) and v_pool.shape == k_pool.shape and rs.shape == rb.shape
+    L = _L()
+    L.orc_recall_scatter.restype = ctypes.c_long
+    L.orc_recall_scatter.argtypes = [ctypes.c_int] * 6 + [ctypes.c_void_p] * 7 + [ctypes.c_long]
+    return L.orc_recall_scatter(_dtype_code(k_pool), S, d, int(max_blocks), k, pairs, staged.ctypes.data,
+                                off.ctypes.data, rb.ctypes.data, rs.ctypes.data, nr.ctypes.data,
+                                k_pool.ctypes.data, v_pool.ctypes.data, n_slots)
+
+
 def force_blocks(s: np.ndarray, n_sink: int, n_tail: int) -> np.ndarray:
     """Scores with the first n_sink and the last n_tail blocks raised to +inf (a copy)."""
     out = np.ascontiguousarray(s, dtype=np.float64).copy()

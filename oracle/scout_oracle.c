@@ -333,6 +333,67 @@ int orc_recall_fetch(int dtype, int S, int d, int max_blocks, const void* src_k,
 }
 
 /*
+ * The same recall through a staging buffer (Sec. 3.4, asynchronous transfer:
+ * the host packs the planned tiles so that they cross the host link as one
+ * contiguous copy, the device then puts them into their slots).
+ *
+ * Stage (host side): over all pairs, the tiles named by the first
+ * min(n_recall[pair], k) plan entries of each pair are packed in pair order,
+ * entry order: tile t = tile_off[pair] + i holds K at byte t*2*tile and V at
+ * t*2*tile + tile.  An entry whose block index is outside [0, max_blocks)
+ * keeps its place but nothing is written there.  src_k / src_v are
+ * [pairs][max_blocks][S][d], recall_blk is [pairs][k], tile_off is [pairs]
+ * (out).  Returns the total number of tiles.
+ */
+long orc_recall_stage(int dtype, int S, int d, int max_blocks, int k, int pairs, const void* src_k,
+                      const void* src_v, const int* recall_blk, const int* n_recall, void* staged,
+                      int* tile_off) {
+  size_t tile = (size_t)S * d * esize(dtype);
+  long t = 0;
+  for (int p = 0; p < pairs; ++p) {
+    int n = n_recall[p];
+    if (n < 0) n = 0;
+    if (n > k) n = k;
+    tile_off[p] = (int)t;
+    for (int i = 0; i < n; ++i, ++t) {
+      int blk = recall_blk[(size_t)p * k + i];
+      if (blk < 0 || blk >= max_blocks) continue;
+      size_t from = ((size_t)p * max_blocks + blk) * tile;
+      memcpy((char*)staged + (size_t)t * 2 * tile, (const char*)src_k + from, tile);
+      memcpy((char*)staged + (size_t)t * 2 * tile + tile, (const char*)src_v + from, tile);
+    }
+  }
+  return t;
+}
+
+/*
+ * Scatter (device side): entry i of a pair takes staged tile tile_off[pair] + i
+ * to pool slot recall_slot[pair][i]; entries with a block index outside
+ * [0, max_blocks) or a slot outside [0, n_slots) are skipped, as in
+ * orc_recall_fetch.  Returns the number of tiles placed.
+ */
+long orc_recall_scatter(int dtype, int S, int d, int max_blocks, int k, int pairs, const void* staged,
+                        const int* tile_off, const int* recall_blk, const int* recall_slot,
+                        const int* n_recall, void* k_pool, void* v_pool, long n_slots) {
+  size_t tile = (size_t)S * d * esize(dtype);
+  long placed = 0;
+  for (int p = 0; p < pairs; ++p) {
+    int n = n_recall[p];
+    if (n < 0) n = 0;
+    if (n > k) n = k;
+    for (int i = 0; i < n; ++i) {
+      int blk = recall_blk[(size_t)p * k + i], slot = recall_slot[(size_t)p * k + i];
+      if (blk < 0 || blk >= max_blocks || slot < 0 || slot >= n_slots) continue;
+      size_t t = (size_t)tile_off[p] + i;
+      memcpy((char*)k_pool + (size_t)slot * tile, (const char*)staged + t * 2 * tile, tile);
+      memcpy((char*)v_pool + (size_t)slot * tile, (const char*)staged + t * 2 * tile + tile, tile);
+      ++placed;
+    }
+  }
+  return placed;
+}
+
+/*
  * Always-kept blocks (a variant of the selection rule of Alg. 1's TopK: the
  * first n_sink blocks of a sequence and the last n_tail blocks that hold
  * tokens are selected whatever their score).  They are given the score

@@ -178,6 +178,72 @@ def test_recall_plan_then_fetch_makes_every_selected_block_resident_with_its_own
     assert all(table[j] >= 0 for j in top)
 
 
+# ---------------------------------------------------------------- recall through a staging buffer
+
+def _staged_case(seed, dtype="f32"):
+    rng = np.random.default_rng(seed)
+    pairs, mb, S, d, k, n_slots = 5, 9, 4, 8, 6, 14
+    def arr(shape):
+        return W.to_storage(rng.standard_normal(shape).astype(np.float32), dtype)
+    src_k, src_v = arr((pairs, mb, S, d)), arr((pairs, mb, S, d))
+    n = np.array([3, 0, 6, 1, 9], dtype=np.int32)          # 9 is clamped to k
+    blk = np.full((pairs, k), -1, dtype=np.int32)
+    slot = np.full((pairs, k), -1, dtype=np.int32)
+    free = rng.permutation(n_slots)
+    at = 0
+    for p in range(pairs):
+        m = min(int(n[p]), k)
+        blk[p, :m] = rng.permutation(mb)[:m]
+        take = min(m, n_slots - at)
+        slot[p, :take] = free[at:at + take]
+        at += take
+    return src_k, src_v, blk, slot, n, arr((n_slots, S, d)), arr((n_slots, S, d)), mb
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_recall_stage_packs_tiles_in_pair_then_entry_order(dtype):
+    src_k, src_v, blk, slot, n, kp, vp, mb = _staged_case(51, dtype)
+    staged, off = oracle.recall_stage(src_k, src_v, blk, n)
+    counts = np.minimum(n, blk.shape[1])
+    assert off.tolist() == [0] + np.cumsum(counts)[:-1].tolist()
+    assert len(staged) == counts.sum()
+    for p in range(len(n)):
+        for i in range(counts[p]):
+            assert np.array_equal(staged[off[p] + i, 0], src_k[p, blk[p, i]])
+            assert np.array_equal(staged[off[p] + i, 1], src_v[p, blk[p, i]])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_recall_stage_then_scatter_is_recall_fetch(dtype):
+    src_k, src_v, blk, slot, n, kp, vp, mb = _staged_case(52, dtype)
+    # two entries that must be skipped on either route: no such block, no such slot
+    blk[2, 1], slot[2, 4] = mb, len(kp)
+    kp2, vp2 = kp.copy(), vp.copy()
+    moved = sum(oracle.recall_fetch(src_k[p], src_v[p], blk[p], slot[p], min(int(n[p]), blk.shape[1]), kp, vp)
+                for p in range(len(n)))
+    staged, off = oracle.recall_stage(src_k, src_v, blk, n)
+    assert oracle.recall_scatter(staged, off, blk, slot, n, mb, kp2, vp2) == moved
+    assert np.array_equal(kp, kp2) and np.array_equal(vp, vp2)
+    assert moved == 3 + 0 + 4 + 1 + (slot[4] >= 0).sum()
+
+
+def test_recall_scatter_reads_the_tile_the_offsets_name():
+    # hand-made staging: tile t holds the constant t (K) and -t (V)
+    S, d, k, mb = 2, 2, 3, 7
+    staged = np.zeros((5, 2, S, d), dtype=np.float32)
+    for t in range(5):
+        staged[t, 0], staged[t, 1] = t, -t
+    off = np.array([0, 2], dtype=np.int32)
+    blk = np.array([[4, 6, -1], [0, 1, 2]], dtype=np.int32)
+    slot = np.array([[3, 0, -1], [1, 5, 2]], dtype=np.int32)   # 5 is no slot
+    n = np.array([2, 3], dtype=np.int32)
+    kp = np.full((4, S, d), 99.0, dtype=np.float32)
+    vp = kp.copy()
+    assert oracle.recall_scatter(staged, off, blk, slot, n, mb, kp, vp) == 4
+    assert [kp[s, 0, 0] for s in range(4)] == [1.0, 2.0, 4.0, 0.0]
+    assert [vp[s, 0, 0] for s in range(4)] == [-1.0, -2.0, -4.0, -0.0]
+
+
 # ---------------------------------------------------------------- always-kept blocks
 
 @pytest.mark.parametrize("nb,k,n_sink,n_tail", [(40, 8, 1, 2), (40, 8, 0, 0), (40, 8, 3, 0), (10, 4, 2, 3), (5, 8, 1, 1),
