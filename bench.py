@@ -322,6 +322,69 @@ def timed(st, fn, n):
     return e0.elapsed_time(e1) * 1e3 / n
 
 
+def staged_setup(st, threads=16):
+    """The staged route of the same recall plans: host copies of the plans, the host worker that packs
+    the tiles, a pinned and a device staging buffer."""
+    from paper_2603_27138_amd import host as H
+    torch, cfg, f = st.torch, st.cfg, st.fetch
+    g = LayerSet()
+    g.H = H
+    g.hp = H.HostProblem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, H.BF16, cfg.max_blocks, cfg.k, 0.0)
+    g.worker = H.HostWorker(threads)
+    g.plans_host = [(blk.cpu().numpy(), f.n.cpu().numpy()) for blk, _ in f.plans]
+    tiles = int(f.n.sum().item())
+    g.staged = torch.zeros(tiles, 2, cfg.S, cfg.d, dtype=torch.int16).pin_memory()
+    g.d_staged = torch.zeros(tiles, 2, cfg.S, cfg.d, dtype=torch.int16, device="cuda")
+    g.off = torch.zeros(cfg.B * cfg.Hkv, dtype=torch.int32).pin_memory()
+    g.d_off = torch.zeros(cfg.B * cfg.Hkv, dtype=torch.int32, device="cuda")
+    st.staged = g
+
+
+def staged_recall(st, i):
+    """One recall by the staged route on the current stream: pack on the host (waited for), one copy of
+    the packed buffer by the copy engine, the scatter kernel.  Returns the host's packing time (s)."""
+    f, g = st.fetch, st.staged
+    blk_h, n_h = g.plans_host[i % len(g.plans_host)]
+    g.worker.stage_recall(g.hp, f.k, f.v, blk_h, n_h, g.staged, g.off)
+    sec = g.worker.wait()
+    g.d_staged.copy_(g.staged, non_blocking=True)
+    g.d_off.copy_(g.off, non_blocking=True)
+    blk, slot = f.plans[i % len(f.plans)]
+    st.B.recall_scatter(st.probs[0], g.d_staged, g.d_off, blk, slot, f.n, f.k_pool, f.v_pool, f.n_slots)
+    return sec
+
+
+def recall_overlap(st, n, us_recall, us_step, route):
+    """Sec. 3.4: recalled blocks arrive while the GPU goes on computing.  Layer steps on the compute
+    stream while recalls run back to back on a second stream (default priority), by the direct route
+    (recall_fetch reading pinned memory) or the staged one: returns (us per step with transfers in
+    flight, us per transfer with steps in flight)."""
+    torch = st.torch
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    f = st.fetch
+    n_rec = int(n * us_step / us_recall) + 2          # enough transfers to span all the timed steps
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(side):
+        if route == "direct":
+            calls = [st.B.prepare(st.B.recall_fetch, st.probs[0], f.k, f.v, *f.plans[i % len(f.plans)], f.n,
+                                  f.k_pool, f.v_pool, f.n_slots) for i in range(len(f.plans))]
+        torch.cuda.synchronize()
+        f0.record(side)
+        for i in range(n_rec):
+            if route == "direct":
+                calls[i % len(calls)]()
+            else:
+                staged_recall(st, i)
+        f1.record(side)
+    e0.record(main)
+    for i in range(n):
+        step(st, i)
+    e1.record(main)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / n, f0.elapsed_time(f1) * 1e3 / n_rec
+
+
 def pipeline_main(args):
     """Layer-ahead pipeline (Sec. 3.3, Algorithm 1) at config 3's shape: per layer the selection with the
     predicted query, the host worker on the offloaded selected blocks, the GPU's partial and the merge;
@@ -475,6 +538,21 @@ def main():
     for i in range(3):
         fetch_only(st, i)
     us_fetch = timed(st, fetch_only, max(8, args.steps // 10))
+    staged_setup(st)
+    pack_s = []
+    for i in range(3):
+        staged_recall(st, i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(8):
+        pack_s.append(staged_recall(st, i))
+    e1.record()
+    torch.cuda.synchronize()
+    us_staged = e0.elapsed_time(e1) * 1e3 / 8        # includes the host's packing, which each call waits for
+    us_step_ov, us_fetch_ov = recall_overlap(st, args.steps, us_fetch, us_step, "direct")
+    us_step_ovs, us_staged_ov = recall_overlap(st, args.steps, us_staged, us_step, "staged")
+    st.staged.worker.close()
 
     tile_bytes = 2 * cfg.S * cfg.d * 2                       # K + V tile of one block, bf16
     n_blocks = int(st.sets[0].n_gpu.sum().item())
@@ -515,6 +593,14 @@ def main():
                        "append_token": round(us_append, 3), "periodic_recall": round(us_recall, 3),
                        "recall_fetch": round(us_fetch, 1)},
         "recall_h2d_gbps": round(st.fetch.bytes / us_fetch * 1e-3, 1),
+        # the same recall by the staged route (host packs, copy engine moves, recall_scatter places)
+        "recall_staged": {"us": round(us_staged, 1), "host_pack_us": round(1e6 * sorted(pack_s)[len(pack_s) // 2], 1),
+                          "h2d_gbps": round(st.fetch.bytes / us_staged * 1e-3, 1)},
+        # layer steps on the compute stream with recalls running back to back on a second stream
+        "recall_overlap": {"direct": {"step_us": round(us_step_ov, 3), "step_slowdown": round(us_step_ov / us_step, 4),
+                                      "recall_us": round(us_fetch_ov, 1)},
+                           "staged": {"step_us": round(us_step_ovs, 3), "step_slowdown": round(us_step_ovs / us_step, 4),
+                                      "recall_us": round(us_staged_ov, 1)}},
         "score_gbps": round(score_gbps, 1),
         # what this GPU sustains for the same bytes with nothing computed (same buffers, same rotation):
         # a read-only stream of the digest cache, and a bare gather of the tiles the attention reads

@@ -252,10 +252,35 @@ int periodic_recall(const scout_problem* p, const void* q, const void* digest,
  *   recall_blk, recall_slot  i32 [B][Hkv][k];  n_recall  i32 [B][Hkv]   DEVICE
  *   k_pool, v_pool  e [n_slots][S][d]   in/out
  * Entries outside [0, max_blocks) x [0, n_slots) are skipped.  Pure copies.
+ * Wave loads over the host link slow every kernel that runs at the same time
+ * (measured: by 1.7 to 1.9 times); a transfer that is to overlap with compute
+ * goes through recall_scatter below instead.
  */
 int recall_fetch(const scout_problem* p, const void* src_k, const void* src_v,
                  const int32_t* recall_blk, const int32_t* recall_slot, const int32_t* n_recall,
                  void* k_pool, void* v_pool, int64_t n_slots, void* stream);
+
+/*
+ * The same recall (Sec. 3.4) for tiles that were brought over by a copy
+ * engine: the host packs the planned tiles in plan order
+ * (scout_host_stage_recall in scout_host.h), one contiguous asynchronous copy
+ * moves the packed buffer into device memory, and this call puts the tiles into
+ * their slots, device to device.  For every pair and every
+ * i < min(n_recall, k), tile t = tile_off[pair] + i of the buffer (K rows at
+ * byte t * 2 * tile, V rows at t * 2 * tile + tile, tile = S * d * sizeof(e))
+ * goes to pool slot recall_slot[i]; entries whose recall_blk is outside
+ * [0, max_blocks) or whose slot is outside [0, n_slots) are skipped, so the
+ * result equals recall_fetch's.
+ *   staged    e   [tiles][2][S][d]   DEVICE, 16-byte aligned
+ *   tile_off  i32 [B][Hkv]           DEVICE: first tile of each pair (the
+ *                                    exclusive prefix sum of min(n_recall, k))
+ *   the other arguments as for recall_fetch
+ * The caller guarantees that the buffer holds tile_off[pair] + min(n_recall, k)
+ * tiles for every pair.
+ */
+int recall_scatter(const scout_problem* p, const void* staged, const int32_t* tile_off,
+                   const int32_t* recall_blk, const int32_t* recall_slot, const int32_t* n_recall,
+                   void* k_pool, void* v_pool, int64_t n_slots, void* stream);
 
 /*
  * One whole layer-step (Sec. 3.2, steps 1-4 above) with the fewest launches:

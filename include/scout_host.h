@@ -66,6 +66,30 @@ int scout_host_submit(scout_host_worker* w, const scout_host_problem* p, const v
                       const int32_t* n_host, const int32_t* ctx_len, float* o, float* m, float* l);
 
 /*
+ * Pack the tiles of a recall plan for one contiguous transfer (Sec. 3.4: the
+ * planned blocks return to the GPU asynchronously).  Over all pairs in order,
+ * the tiles of the first min(n_recall[pair], k) plan entries are copied, by the
+ * pool's threads, into `staged`: tile t = tile_off[pair] + i holds the K rows of
+ * block recall_blk[pair][i] at byte t * 2 * tile and its V rows at
+ * t * 2 * tile + tile (tile = S * d * sizeof(e)).  An entry outside
+ * [0, max_blocks) keeps its place; nothing is written there.
+ *   k_blocks, v_blocks  e [B][Hkv][max_blocks][S][d]   the host's copy of the blocks
+ *   recall_blk  i32 [B][Hkv][k], n_recall i32 [B][Hkv]   the plan, copied to HOST memory
+ *   staged      bytes, staged_bytes long: out (pinned memory if a copy engine is
+ *               to read it); may be NULL if the plan is empty
+ *   tile_off    i32 [B][Hkv]   out: first tile of each pair, written before the
+ *               call returns
+ *   total_tiles out: tiles in the packed buffer, written before the call returns
+ * Only p's B, Hkv, d, S, dtype, max_blocks and k are read.  Asynchronous like
+ * scout_host_submit and sharing its single job slot: 0 once the work is dealt
+ * (wait with scout_host_wait), -1 on a bad argument or a buffer too small, -6
+ * if a job is already in flight.
+ */
+int scout_host_stage_recall(scout_host_worker* w, const scout_host_problem* p, const void* k_blocks,
+                            const void* v_blocks, const int32_t* recall_blk, const int32_t* n_recall,
+                            void* staged, size_t staged_bytes, int32_t* tile_off, int64_t* total_tiles);
+
+/*
  * Block until the submitted job is done (0), or return 0 at once if none is
  * in flight.  *seconds, if not NULL, receives the time from submit to the
  * last pair's completion.

@@ -20,7 +20,7 @@ F32, BF16 = 0, 1
 OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
 
 EXPORTS = ["scout_version", "scout_strerror", "scout_workspace_bytes", "build_digests", "append_token", "score_blocks",
-           "select_topk", "sparse_decode_attn", "merge_partials", "periodic_recall", "recall_fetch",
+           "select_topk", "sparse_decode_attn", "merge_partials", "periodic_recall", "recall_fetch", "recall_scatter",
            "scout_layer_step", "scout_set_attn_mode", "scout_calib_copy", "scout_attn_partials",
            "scout_calib_read", "scout_calib_gather", "scout_attn_finish"]
 
@@ -66,6 +66,7 @@ def lib():
         L.merge_partials.argtypes = [pp] + [vp] * 9
         L.periodic_recall.argtypes = [pp] + [vp] * 8 + [sz, vp]
         L.recall_fetch.argtypes = [pp] + [vp] * 7 + [i64, vp]
+        L.recall_scatter.argtypes = [pp] + [vp] * 7 + [i64, vp]
         L.scout_calib_copy.argtypes = [vp, vp, sz, vp]
         L.scout_calib_read.argtypes = [vp, sz, vp, vp]
         L.scout_calib_gather.argtypes = [pp, vp, vp, i64, vp, vp, vp, vp]
@@ -236,6 +237,12 @@ def recall_fetch(p: Problem, src_k, src_v, recall_blk, recall_slot, n_recall, k_
     _call("recall_fetch", lib().recall_fetch, ctypes.byref(p), _ptr_addressable(src_k), _ptr_addressable(src_v), _ptr(recall_blk),
           _ptr(recall_slot), _ptr(n_recall), _ptr(k_pool), _ptr(v_pool),
           int(n_slots), _stream())
+
+
+def recall_scatter(p: Problem, staged, tile_off, recall_blk, recall_slot, n_recall, k_pool, v_pool, n_slots):
+    """staged: device buffer of packed tiles [tiles][2][S][d]; tile_off: first tile of each pair."""
+    _call("recall_scatter", lib().recall_scatter, ctypes.byref(p), _ptr(staged), _ptr(tile_off), _ptr(recall_blk),
+          _ptr(recall_slot), _ptr(n_recall), _ptr(k_pool), _ptr(v_pool), int(n_slots), _stream())
 
 
 def calib_read(src, nbytes: int, sink=None):

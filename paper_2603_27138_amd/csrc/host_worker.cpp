@@ -37,6 +37,11 @@ struct Job {
   float* l = nullptr;
   float scale = 0.0f;
   int pairs = 0;
+  // kind 1 (packing the tiles of a recall plan): kb / vb are the block store, sel the planned block
+  // indices, n their counts
+  int kind = 0;
+  char* staged = nullptr;
+  const int32_t* tile_off = nullptr;
 };
 
 namespace scout_host_generic {
@@ -56,7 +61,24 @@ using ::Job;
 
 namespace {
 
+// Recall staging (Sec. 3.4): the pair's planned tiles go to their places in the packed buffer.
+void stage_pair(const Job& J, int pair) {
+  const size_t tile = (size_t)J.p.S * J.p.d * (J.p.dtype == 1 ? 2 : 4);
+  int n = J.n[pair];
+  n = n < 0 ? 0 : (n > J.p.k ? J.p.k : n);
+  const char* kb = static_cast<const char*>(J.kb) + (size_t)pair * J.p.max_blocks * tile;
+  const char* vb = static_cast<const char*>(J.vb) + (size_t)pair * J.p.max_blocks * tile;
+  char* out = J.staged + (size_t)J.tile_off[pair] * 2 * tile;
+  for (int i = 0; i < n; ++i, out += 2 * tile) {
+    const int blk = J.sel[(size_t)pair * J.p.k + i];
+    if (blk < 0 || blk >= J.p.max_blocks) continue;
+    std::memcpy(out, kb + (size_t)blk * tile, tile);
+    std::memcpy(out + tile, vb + (size_t)blk * tile, tile);
+  }
+}
+
 void run_pair(const Job& J, int pair, float* kf, float* vf) {
+  if (J.kind == 1) return stage_pair(J, pair);
   const bool wide = J.p.Hq / J.p.Hkv > 8;
 #if defined(__x86_64__)
   static const bool avx2 = __builtin_cpu_supports("avx2") && __builtin_cpu_supports("fma");
@@ -126,6 +148,21 @@ struct scout_host_worker {
   }
 };
 
+// Hand a job to the threads (the caller has checked that none is in flight).
+static void publish(scout_host_worker* w, const Job& J) {
+  {
+    std::lock_guard<std::mutex> lk(w->mu);
+    w->job = J;
+    w->pairs_left.store(J.pairs, std::memory_order_relaxed);
+    w->in_flight.store(true, std::memory_order_release);
+    w->t_submit = std::chrono::steady_clock::now();
+    const uint64_t gen = w->generation.load(std::memory_order_relaxed) + 1;
+    w->ticket.store((gen & 0xffffffffu) << 32, std::memory_order_release);
+    w->generation.store(gen, std::memory_order_release);
+  }
+  w->cv_job.notify_all();
+}
+
 extern "C" {
 
 int scout_host_create(int n_threads, scout_host_worker** out) {
@@ -170,17 +207,38 @@ int scout_host_submit(scout_host_worker* w, const scout_host_problem* p, const v
   J.scale = p->sm_scale != 0.0f ? p->sm_scale : 1.0f / std::sqrt((float)p->d);
   J.pairs = p->B * p->Hkv;
   if (J.pairs == 0) return 0;
-  {
-    std::lock_guard<std::mutex> lk(w->mu);
-    w->job = J;
-    w->pairs_left.store(J.pairs, std::memory_order_relaxed);
-    w->in_flight.store(true, std::memory_order_release);
-    w->t_submit = std::chrono::steady_clock::now();
-    const uint64_t gen = w->generation.load(std::memory_order_relaxed) + 1;
-    w->ticket.store((gen & 0xffffffffu) << 32, std::memory_order_release);
-    w->generation.store(gen, std::memory_order_release);
+  publish(w, J);
+  return 0;
+}
+
+int scout_host_stage_recall(scout_host_worker* w, const scout_host_problem* p, const void* k_blocks,
+                            const void* v_blocks, const int32_t* recall_blk, const int32_t* n_recall,
+                            void* staged, size_t staged_bytes, int32_t* tile_off, int64_t* total_tiles) {
+  if (!w || !p || !k_blocks || !v_blocks || !recall_blk || !n_recall || !tile_off || !total_tiles) return -1;
+  if (p->B < 0 || p->Hkv < 1 || p->d < 1 || p->S < 1 || (p->dtype != 0 && p->dtype != 1) || p->max_blocks < 0 ||
+      p->k < 0)
+    return -1;
+  if (w->in_flight.load(std::memory_order_acquire)) return -6;
+  const int pairs = p->B * p->Hkv;
+  const size_t tile = (size_t)p->S * p->d * (p->dtype == 1 ? 2 : 4);
+  int64_t total = 0;
+  for (int pair = 0; pair < pairs; ++pair) {
+    const int n = n_recall[pair];
+    if (total > std::numeric_limits<int32_t>::max()) return -1;
+    tile_off[pair] = (int32_t)total;
+    total += n < 0 ? 0 : (n > p->k ? p->k : n);
   }
-  w->cv_job.notify_all();
+  *total_tiles = total;
+  if (total == 0) return 0;
+  if (staged == nullptr || (size_t)total * 2 * tile > staged_bytes) return -1;
+  Job J;
+  J.p = *p;
+  J.kind = 1;
+  J.kb = k_blocks; J.vb = v_blocks; J.sel = recall_blk; J.n = n_recall;
+  J.staged = static_cast<char*>(staged);
+  J.tile_off = tile_off;
+  J.pairs = pairs;
+  publish(w, J);
   return 0;
 }
 

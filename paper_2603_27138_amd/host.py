@@ -12,7 +12,8 @@ import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libscout_host.so")
-EXPORTS = ["scout_host_create", "scout_host_destroy", "scout_host_submit", "scout_host_wait", "scout_host_done"]
+EXPORTS = ["scout_host_create", "scout_host_destroy", "scout_host_submit", "scout_host_stage_recall", "scout_host_wait",
+           "scout_host_done"]
 F32, BF16 = 0, 1
 
 
@@ -36,6 +37,8 @@ def lib():
         L.scout_host_destroy.argtypes = [vp]
         L.scout_host_destroy.restype = None
         L.scout_host_submit.argtypes = [vp, ctypes.POINTER(HostProblem)] + [vp] * 9
+        L.scout_host_stage_recall.argtypes = [vp, ctypes.POINTER(HostProblem)] + [vp] * 5 + [ctypes.c_size_t, vp,
+                                                                                       ctypes.POINTER(ctypes.c_int64)]
         L.scout_host_wait.argtypes = [vp, ctypes.POINTER(ctypes.c_double)]
         L.scout_host_done.argtypes = [vp]
         _lib = L
@@ -66,6 +69,19 @@ class HostWorker:
         if rc != 0:
             raise RuntimeError(f"scout_host_submit failed ({rc})")
         self._keep = (p,) + args
+
+    def stage_recall(self, p: HostProblem, k_blocks, v_blocks, recall_blk, n_recall, staged, tile_off) -> int:
+        """Starts packing the tiles a recall plan names into `staged` (Sec. 3.4); tile_off is filled before
+        this returns.  Returns the number of tiles; wait() as after submit."""
+        total = ctypes.c_int64(0)
+        nbytes = staged.nbytes if isinstance(staged, np.ndarray) else staged.numel() * staged.element_size()
+        rc = lib().scout_host_stage_recall(self._h, ctypes.byref(p), _addr(k_blocks), _addr(v_blocks),
+                                           _addr(recall_blk), _addr(n_recall), _addr(staged), nbytes,
+                                           _addr(tile_off), ctypes.byref(total))
+        if rc != 0:
+            raise RuntimeError(f"scout_host_stage_recall failed ({rc})")
+        self._keep = (p, k_blocks, v_blocks, recall_blk, n_recall, staged, tile_off)
+        return total.value
 
     def wait(self) -> float:
         """Blocks until the job is done; returns seconds from submit to completion."""

@@ -45,7 +45,7 @@ def test_host_library_exports_every_declared_symbol():
     text = open(os.path.join(ROOT, "include", "scout_host.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     syms = sorted(set(re.findall(r"\b(?:int|void)\s+(scout_host_\w+)\s*\(", text)))
-    assert len(syms) == 5 and sorted(host.EXPORTS) == syms
+    assert len(syms) == 6 and sorted(host.EXPORTS) == syms
     for s_ in syms:
         assert hasattr(host.lib(), s_), s_
 
@@ -96,6 +96,10 @@ def test_null_misaligned_and_workspace_errors(lib):
     # host partial must be given completely or not at all
     assert L.merge_partials(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, None, None, FAKE, None, None) == lib.EINVAL
     assert L.periodic_recall(ctypes.byref(p), FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == lib.EINVAL
+    assert L.recall_scatter(ctypes.byref(p), None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 4, None) == lib.EINVAL
+    assert L.recall_scatter(ctypes.byref(p), odd, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 4, None) == lib.EINVAL
+    assert L.recall_scatter(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, -1, None) == lib.EINVAL
+    assert L.recall_fetch(ctypes.byref(p), FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, 4, None) == lib.EINVAL
     assert L.scout_set_attn_mode(4, 0, 0) == lib.EINVAL and L.scout_set_attn_mode(0, 0, 4) == lib.EINVAL and L.scout_set_attn_mode(0, 0, 0) == 0
     # MFMA family forced on a shape it does not cover
     p32 = _problem(lib, dtype=lib.F32)

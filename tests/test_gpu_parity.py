@@ -454,6 +454,59 @@ def _bits16(a):
     return a.view(np.int16) if a.dtype == np.uint16 else a
 
 
+def test_recall_staged_route_bit_exact(cfg):
+    """The recall as it runs beside compute: the host worker packs the planned tiles into pinned memory,
+    one copy brings the packed buffer over, recall_scatter puts the tiles into the freed slots.  The
+    packed buffer equals the oracle's, the pools equal the oracle's (and thereby the direct route's)."""
+    from paper_2603_27138_amd import host as H
+    wl, res, dev = setup(cfg)
+    pairs = cfg.B * cfg.Hkv
+    kb = np.zeros((cfg.B, cfg.Hkv, cfg.max_blocks, cfg.S, cfg.d), dtype=wl.k_pool.dtype)
+    vb = np.zeros_like(kb)
+    for (b, g) in wl.K:
+        kb[b, g, :cfg.nb(b)] = wl.blocks_padded(b, g, "K")
+        vb[b, g, :cfg.nb(b)] = wl.blocks_padded(b, g, "V")
+    q1 = W.gen_q(cfg, 0, step=5)
+    rb = np.full((cfg.B, cfg.Hkv, cfg.k), -1, dtype=np.int32)
+    rs = np.full((cfg.B, cfg.Hkv, cfg.k), -1, dtype=np.int32)
+    nr = np.zeros((cfg.B, cfg.Hkv), dtype=np.int32)
+    for (b, g), op in res.items():
+        s = oracle.decision_scores(oracle.score(q1[b, g * cfg.G:(g + 1) * cfg.G], op.dig))
+        rb[b, g], rs[b, g], _, nr[b, g] = oracle.recall_plan(s, cfg.k, wl.block_table[b, g][:len(s)].copy())
+    if pairs:
+        rb[0, 0, 0] = cfg.max_blocks          # a plan entry that names no block: skipped on both sides
+        nr[0, 0] = max(nr[0, 0], 1)
+    flat = lambda a: a.reshape((pairs,) + a.shape[2:])
+    want_staged, want_off = oracle.recall_stage(flat(kb), flat(vb), flat(rb), nr.reshape(pairs))
+    kp, vp = wl.k_pool.copy(), wl.v_pool.copy()
+    placed = oracle.recall_scatter(want_staged, want_off, flat(rb), flat(rs), nr.reshape(pairs), cfg.max_blocks, kp, vp)
+
+    hp = H.HostProblem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, H.F32 if cfg.dtype == "f32" else H.BF16, cfg.max_blocks,
+                       cfg.k, 0.0)
+    staged = torch.zeros(max(1, want_staged.size), dtype=torch.from_numpy(_bits16(want_staged)).dtype).pin_memory()
+    off = torch.zeros(max(1, pairs), dtype=torch.int32).pin_memory()
+    worker = H.HostWorker(4)
+    try:
+        total = worker.stage_recall(hp, kb, vb, rb, nr, staged, off)
+        worker.wait()
+    finally:
+        worker.close()
+    assert total == len(want_staged)
+    assert np.array_equal(off.numpy()[:pairs], want_off)
+    assert np.array_equal(staged.numpy()[:want_staged.size], _bits16(want_staged).reshape(-1))
+    side = torch.cuda.Stream()
+    k2, v2 = dev.k_pool.clone(), dev.v_pool.clone()
+    d_rb, d_rs, d_nr = (torch.from_numpy(a).cuda() for a in (rb, rs, nr))
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        d_staged = staged.to("cuda", non_blocking=True)
+        d_off = off.to("cuda", non_blocking=True)
+        B.recall_scatter(dev.p, d_staged, d_off, d_rb, d_rs, d_nr, k2, v2, dev.n_slots)
+    torch.cuda.synchronize()
+    assert np.array_equal(_bits(to_np(k2)), _bits(kp)) and np.array_equal(_bits(to_np(v2)), _bits(vp))
+    assert placed > 0 or not _can_move(cfg)
+
+
 def test_recall_then_select_leaves_nothing_on_host():
     cfg = W.shrink(W.qwen3_32b(B=2, ctx=8192))
     wl, res, dev = setup(cfg)

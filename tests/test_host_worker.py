@@ -126,3 +126,59 @@ def test_host_worker_rejects_bad_arguments():
         w.close()
     with pytest.raises(RuntimeError):
         H.HostWorker(0)
+
+
+# ---------------------------------------------------------------- recall staging (Sec. 3.4)
+
+def _plan(rng, pairs, mb, k, counts):
+    blk = np.full((pairs, k), -1, dtype=np.int32)
+    n = np.asarray(counts, dtype=np.int32)
+    for p in range(pairs):
+        m = max(0, min(int(n[p]), k))
+        blk[p, :m] = rng.permutation(mb)[:m]
+    return blk, n
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("threads", [1, 5])
+def test_stage_recall_equals_the_oracle_packing(dtype, threads):
+    rng = np.random.default_rng(61)
+    B, Hkv, mb, S, d, k = 3, 2, 11, 16, 64, 7
+    st = lambda x: W.to_storage(x.astype(np.float32), dtype)
+    kb, vb = st(rng.standard_normal((B, Hkv, mb, S, d))), st(rng.standard_normal((B, Hkv, mb, S, d)))
+    blk, n = _plan(rng, B * Hkv, mb, k, [3, 0, 7, 1, 12, -2])      # 12 is clamped to k, -2 to 0
+    blk[2, 4] = mb                                                   # no such block: its tile stays as it was
+    want, want_off = oracle.recall_stage(kb.reshape(B * Hkv, mb, S, d), vb.reshape(B * Hkv, mb, S, d), blk, n)
+    p = H.HostProblem(B, 4, Hkv, d, S, H.F32 if dtype == "f32" else H.BF16, mb, k, 0.0)
+    staged = np.zeros_like(want)
+    off = np.full(B * Hkv, -7, dtype=np.int32)
+    w = H.HostWorker(threads)
+    try:
+        total = w.stage_recall(p, kb, vb, blk.reshape(B, Hkv, k), n.reshape(B, Hkv), staged, off)
+        w.wait()
+    finally:
+        w.close()
+    assert total == len(want) == 3 + 0 + 7 + 1 + 7 + 0
+    assert np.array_equal(off, want_off) and np.array_equal(staged, want)
+
+
+def test_stage_recall_rejects_a_short_buffer_and_takes_an_empty_plan():
+    B, Hkv, mb, S, d, k = 1, 2, 4, 2, 8, 3
+    kb = np.zeros((B, Hkv, mb, S, d), dtype=np.float32)
+    blk = np.zeros((B, Hkv, k), dtype=np.int32)
+    p = H.HostProblem(B, 2, Hkv, d, S, H.F32, mb, k, 0.0)
+    off = np.zeros(B * Hkv, dtype=np.int32)
+    w = H.HostWorker(2)
+    try:
+        short = np.zeros((2, 2, S, d), dtype=np.float32)             # room for 2 tiles, the plan has 3
+        with pytest.raises(RuntimeError):
+            w.stage_recall(p, kb, kb, blk, np.array([[2, 1]], dtype=np.int32), short, off)
+        assert w.done()
+        assert w.stage_recall(p, kb, kb, blk, np.zeros((B, Hkv), dtype=np.int32), short, off) == 0
+        assert w.done() and off.tolist() == [0, 0]
+        # the pool still takes an attention job afterwards
+        assert w.stage_recall(p, kb, kb, blk, np.array([[1, 1]], dtype=np.int32), short, off) == 2
+        w.wait()
+        assert off.tolist() == [0, 1]
+    finally:
+        w.close()
