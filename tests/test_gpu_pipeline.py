@@ -102,3 +102,58 @@ def test_pipeline_matches_algorithm_1(dtype, tol):
             assert drift > worst      # the predicted query does change the result; that is the method
     finally:
         pipe.close()
+
+
+def test_pipeline_with_periodic_recall():
+    """Algorithm 1 with the recall of Sec. 3.4 every second step: after those steps each layer's plan is
+    made with the real query, the tiles travel by the staged route beside the next layers' work, and the
+    following steps select and attend on the new residency.  The oracle mirrors it by updating its copy of
+    the table with its own plan; tables, pool contents, selections and outputs must agree."""
+    cfg = W.shrink(W.qwen3_32b(B=2, ctx=4096), k=16, p_host=0.5, name="pipe-recall")
+    n_layers, R = 3, 2
+    wls = [W.generate(cfg, layer=i) for i in range(n_layers)]
+    built = [_layer(wl) for wl in wls]
+    layers = [x[0] for x in built]
+    ctx = torch.from_numpy(wls[0].ctx_len).cuda()
+    pipe = P.LayerAheadPipeline(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, B.BF16, cfg.max_blocks, cfg.k, ctx, layers,
+                                n_threads=4, recall_every=R)
+    moved_total = 0
+    try:
+        for step in range(4):
+            qs = [W.gen_q(cfg, layer=i, step=step) for i in range(n_layers)]
+            qps = [W.gen_q_pred(q, 0.94, seed=10 * step + i) for i, q in enumerate(qs)]
+            print(f"[pipeline+recall] step {step}", flush=True)
+            outs = pipe.step([to_dev(q) for q in qs], [to_dev(q) for q in qps])
+            torch.cuda.synchronize()
+            worst = 0.0
+            for i in range(n_layers):
+                wl, digs = wls[i], built[i][1]
+                want = _oracle_alg1(wl, digs, qs[i], qps[i], qps[i])     # on the residency before this step's recall
+                got = W.storage_to_f32(to_np(outs[i])).astype(np.float64)
+                sel = pipe.buf[i].sel_all.cpu().numpy()
+                for (b, g), (wsel, wouts, s32) in want.items():
+                    assert np.array_equal(sel[b, g], wsel), (step, i, b, g)
+                    for h in range(cfg.G):
+                        worst = max(worst, float(np.abs(got[b, g * cfg.G + h] - wouts[h]).max()))
+                if step % R == R - 1:                                    # the oracle's recall, real query
+                    planned = 0
+                    for (b, g) in wl.K:
+                        s = oracle.decision_scores(oracle.score(qs[i][b, g * cfg.G:(g + 1) * cfg.G], digs[(b, g)]))
+                        planned += oracle.recall_plan(s, cfg.k, wl.block_table[b, g][:len(s)])[3]
+                    moved_total += planned
+                    assert np.array_equal(layers[i].block_table.cpu().numpy(), wl.block_table), (step, i)
+                    assert int(pipe.buf[i].n_recall.sum().item()) == planned
+                    # every resident block's slot holds that block's rows
+                    kp, vp = to_np(layers[i].k_pool), to_np(layers[i].v_pool)
+                    for (b, g) in wl.K:
+                        kb, vb = wl.blocks_padded(b, g, "K"), wl.blocks_padded(b, g, "V")
+                        for j in range(cfg.nb(b)):
+                            slot = wl.block_table[b, g, j]
+                            if slot >= 0:
+                                assert np.array_equal(kp[slot], kb[j]) and np.array_equal(vp[slot], vb[j]), (step, i, b, g, j)
+            assert worst <= 2e-2, (step, worst)
+            if step % R == R - 1:
+                assert pipe.recalled_tiles > 0
+        assert moved_total > 0
+    finally:
+        pipe.close()
