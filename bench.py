@@ -40,6 +40,9 @@ def parse(argv=None):
     ap.add_argument("--group-max", action="store_true",
                     help="time the variant that combines the group's heads by their maximum (not the metric's setting)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-recall-overlap", action="store_true",
+                    help="skip the layer steps timed beside running recalls (keeps a kernel trace free of the "
+                         "launches that are slowed on purpose)")
     ap.add_argument("--attn-family", type=int, default=0)
     ap.add_argument("--nsplit", type=int, default=0)
     ap.add_argument("--waves", type=int, default=0)
@@ -550,8 +553,11 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     us_staged = e0.elapsed_time(e1) * 1e3 / 8        # includes the host's packing, which each call waits for
-    us_step_ov, us_fetch_ov = recall_overlap(st, args.steps, us_fetch, us_step, "direct")
-    us_step_ovs, us_staged_ov = recall_overlap(st, args.steps, us_staged, us_step, "staged")
+    if args.no_recall_overlap:
+        us_step_ov = us_fetch_ov = us_step_ovs = us_staged_ov = None
+    else:
+        us_step_ov, us_fetch_ov = recall_overlap(st, args.steps, us_fetch, us_step, "direct")
+        us_step_ovs, us_staged_ov = recall_overlap(st, args.steps, us_staged, us_step, "staged")
     st.staged.worker.close()
 
     tile_bytes = 2 * cfg.S * cfg.d * 2                       # K + V tile of one block, bf16
@@ -597,10 +603,11 @@ def main():
         "recall_staged": {"us": round(us_staged, 1), "host_pack_us": round(1e6 * sorted(pack_s)[len(pack_s) // 2], 1),
                           "h2d_gbps": round(st.fetch.bytes / us_staged * 1e-3, 1)},
         # layer steps on the compute stream with recalls running back to back on a second stream
-        "recall_overlap": {"direct": {"step_us": round(us_step_ov, 3), "step_slowdown": round(us_step_ov / us_step, 4),
-                                      "recall_us": round(us_fetch_ov, 1)},
-                           "staged": {"step_us": round(us_step_ovs, 3), "step_slowdown": round(us_step_ovs / us_step, 4),
-                                      "recall_us": round(us_staged_ov, 1)}},
+        "recall_overlap": None if us_step_ov is None else {
+            "direct": {"step_us": round(us_step_ov, 3), "step_slowdown": round(us_step_ov / us_step, 4),
+                       "recall_us": round(us_fetch_ov, 1)},
+            "staged": {"step_us": round(us_step_ovs, 3), "step_slowdown": round(us_step_ovs / us_step, 4),
+                       "recall_us": round(us_staged_ov, 1)}},
         "score_gbps": round(score_gbps, 1),
         # what this GPU sustains for the same bytes with nothing computed (same buffers, same rotation):
         # a read-only stream of the digest cache, and a bare gather of the tiles the attention reads
