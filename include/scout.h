@@ -56,7 +56,8 @@ enum {
 enum { SCOUT_F32 = 0, SCOUT_BF16 = 1 };
 
 typedef struct scout_problem {
-  int32_t B, Hq, Hkv; /* Hq % Hkv == 0, G = Hq/Hkv <= 16                            */
+  int32_t B, Hq, Hkv; /* Hq % Hkv == 0, G = Hq/Hkv <= 16; B * Hkv <= 65535
+                         (B * Hq with per_head)                                    */
   int32_t d;          /* head dim: 64 or 128                                        */
   int32_t S;          /* tokens per block: 16, 32 or 64                             */
   int32_t dtype;      /* element type of q, k_pool, v_pool, digest, out             */
@@ -67,7 +68,12 @@ typedef struct scout_problem {
   int32_t n_tail;     /* and its last n_tail blocks that hold tokens (both >= 0)    */
   int32_t group_max;  /* block importance of a KV head: 0 = sum over its G query
                          heads (default), 1 = maximum over them                     */
-  int32_t reserved;   /* 0                                                          */
+  int32_t per_head;   /* 0 = one selection per KV head, shared by its G query heads
+                         (default); 1 = every query head selects its own blocks:
+                         scores, the sel_* / slot_gpu lists and the n_* counts
+                         then have Hq where the layouts below say Hkv, while
+                         digest, block_table, the pools and everything about
+                         building, appending and recalling keep Hkv             */
   const int32_t* ctx_len; /* DEVICE int32 [B]: tokens per sequence; blocks beyond
                              max_blocks are ignored                                  */
 } scout_problem;

@@ -48,6 +48,7 @@ static int check_problem(const scout_problem* p, Dims* D) {
   if (p->dtype != SCOUT_F32 && p->dtype != SCOUT_BF16) return SCOUT_EINVAL;
   if (!(p->sm_scale >= 0.0f) || std::isinf(p->sm_scale)) return SCOUT_EINVAL;
   if (p->n_sink < 0 || p->n_tail < 0 || (p->group_max != 0 && p->group_max != 1)) return SCOUT_EINVAL;
+  if (p->per_head != 0 && p->per_head != 1) return SCOUT_EINVAL;
   if (p->ctx_len == nullptr) return SCOUT_EINVAL;
   if (p->d != 64 && p->d != 128) return SCOUT_EUNSUPPORTED;
   if (p->S != 16 && p->S != 32 && p->S != 64) return SCOUT_EUNSUPPORTED;
@@ -66,8 +67,24 @@ static int check_problem(const scout_problem* p, Dims* D) {
   D->n_sink = p->n_sink;
   D->n_tail = p->n_tail;
   D->group_max = p->group_max;
+  D->share = 1;
+  if (p->per_head) {  // every query head is a pair of its own that reads its KV head's digest and table rows
+    D->share = D->G;
+    D->Hkv = D->Hq;
+    D->G = 1;
+  }
   D->ctx_len = p->ctx_len;
+  if ((long long)D->B * D->Hkv > 65535) return SCOUT_EUNSUPPORTED;  // pairs are the second grid dimension
   return SCOUT_OK;
+}
+
+// For the entry points that work on the cache itself (one row per KV head whatever the selection mode).
+static int check_problem_kv(const scout_problem* p, Dims* D) {
+  if (p == nullptr) return SCOUT_EINVAL;
+  scout_problem kv = *p;
+  if (kv.per_head != 0 && kv.per_head != 1) return SCOUT_EINVAL;
+  kv.per_head = 0;
+  return check_problem(&kv, D);
 }
 
 static size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -294,7 +311,7 @@ int scout_workspace_bytes(const scout_problem* p, size_t* bytes) {
 
 int build_digests(const scout_problem* p, const void* k_blocks, void* digest, void* stream) {
   Dims D;
-  int rc = check_problem(p, &D);
+  int rc = check_problem_kv(p, &D);
   if (rc != SCOUT_OK) return rc;
   if (k_blocks == nullptr || digest == nullptr || !aligned16(k_blocks) || !aligned16(digest))
     return SCOUT_EINVAL;
@@ -305,7 +322,7 @@ int append_token(const scout_problem* p, int32_t* ctx_len, const void* k_new, co
                  const int32_t* new_slot, void* digest, int32_t* block_table, void* k_pool, void* v_pool,
                  int64_t n_slots, void* host_k, void* host_v, void* stream) {
   Dims D;
-  int rc = check_problem(p, &D);
+  int rc = check_problem_kv(p, &D);
   if (rc != SCOUT_OK) return rc;
   if (!ctx_len || !k_new || !v_new || !new_slot || !digest || !block_table || !k_pool || !v_pool)
     return SCOUT_EINVAL;
@@ -433,6 +450,7 @@ int periodic_recall(const scout_problem* p, const void* q, const void* digest, i
   Dims D;
   int rc = check_problem(p, &D);
   if (rc != SCOUT_OK) return rc;
+  if (p->per_head) return SCOUT_EUNSUPPORTED;  // a recall plans for the KV head; which heads' choices count is not defined
   if (!q || !digest || !block_table || !recall_blk || !recall_slot || !evict_blk || !n_recall)
     return SCOUT_EINVAL;
   if (!aligned16(q) || !aligned16(digest)) return SCOUT_EINVAL;
@@ -450,7 +468,7 @@ int recall_fetch(const scout_problem* p, const void* src_k, const void* src_v, c
                  const int32_t* recall_slot, const int32_t* n_recall, void* k_pool, void* v_pool,
                  int64_t n_slots, void* stream) {
   Dims D;
-  int rc = check_problem(p, &D);
+  int rc = check_problem_kv(p, &D);
   if (rc != SCOUT_OK) return rc;
   if (!src_k || !src_v || !recall_blk || !recall_slot || !n_recall || !k_pool || !v_pool) return SCOUT_EINVAL;
   if (!aligned16(src_k) || !aligned16(src_v) || !aligned16(k_pool) || !aligned16(v_pool)) return SCOUT_EINVAL;
@@ -463,7 +481,7 @@ int recall_scatter(const scout_problem* p, const void* staged, const int32_t* ti
                    const int32_t* recall_blk, const int32_t* recall_slot, const int32_t* n_recall, void* k_pool,
                    void* v_pool, int64_t n_slots, void* stream) {
   Dims D;
-  int rc = check_problem(p, &D);
+  int rc = check_problem_kv(p, &D);
   if (rc != SCOUT_OK) return rc;
   if (!staged || !tile_off || !recall_blk || !recall_slot || !n_recall || !k_pool || !v_pool) return SCOUT_EINVAL;
   if (!aligned16(staged) || !aligned16(k_pool) || !aligned16(v_pool) || n_slots < 0) return SCOUT_EINVAL;

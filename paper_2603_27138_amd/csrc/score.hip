@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_kernel(
       qv[h] = *reinterpret_cast<const float*>(qbase + (size_t)hs * DH * ESZ);
   }
 
-  const char* dpair = static_cast<const char*>(digest) + (size_t)pair * D.max_blocks * EB;
+  const char* dpair = static_cast<const char*>(digest) + (size_t)(pair / D.share) * D.max_blocks * EB;
   const __amdgpu_buffer_rsrc_t rs =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(dpair), 0, active ? nb * EB : 0, 0x00020000);
   const int voff0 = (j_wave + (lane >> 3)) * EB + (lane & 7) * 16;
@@ -265,7 +265,7 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_max_kernel(Dims D, c
     const int e = threadIdx.x + i * NT;
     qreg[i] = load1<DT>(q, ((size_t)b * D.Hq + g * D.G) * DH + (e < n_q ? e : n_q - 1));
   }
-  const char* dpair = static_cast<const char*>(digest) + (size_t)pair * D.max_blocks * EB;
+  const char* dpair = static_cast<const char*>(digest) + (size_t)(pair / D.share) * D.max_blocks * EB;
   const __amdgpu_buffer_rsrc_t rs =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(dpair), 0, active ? nb * EB : 0, 0x00020000);
   const int voff0 = (j_wave + (lane >> 3)) * EB + (lane & 7) * 16;

@@ -56,6 +56,30 @@ def run_pair(wl: W.Workload, b: int, g: int, q=None, table=None, attention: bool
     return res
 
 
+def run_head(wl: W.Workload, b: int, hq: int, q=None, table=None) -> OraclePair:
+    """Selection per query head (a variant of Alg. 1's TopK argument: the block importance of one
+    head alone decides that head's blocks): the head is a group of one on its KV head's cache."""
+    cfg = wl.cfg
+    q = wl.q if q is None else q
+    table = wl.block_table if table is None else table
+    g = hq // cfg.G
+    K, V = wl.K[(b, g)], wl.V[(b, g)]
+    ctx = int(cfg.ctx[b])
+    dig = oracle.digest(K, ctx, cfg.S)
+    s = oracle.score(q[b, hq:hq + 1], dig)
+    s32 = oracle.decision_scores(s)
+    sel = oracle.select(s32, cfg.k)
+    sg, ng, sh, nh = oracle.split(sel, table[b, g])
+    res = OraclePair(dig, s, s32, sel, sg, ng, sh, nh)
+    pg = oracle.partial_attn(q[b, hq], K, V, sg, ctx, cfg.S, cfg.sm_scale)
+    ph = oracle.partial_attn(q[b, hq], K, V, sh, ctx, cfg.S, cfg.sm_scale)
+    ph32 = (ph[0].astype(np.float32).astype(np.float64), float(np.float32(ph[1])), float(np.float32(ph[2])))
+    res.gpu_part.append(pg)
+    res.host_part.append(ph32)
+    res.out.append(oracle.merge(pg[0], pg[1], pg[2], ph32[0], ph32[1], ph32[2]))
+    return res
+
+
 def run_all(wl: W.Workload, **kw) -> Dict[Tuple[int, int], OraclePair]:
     return {p: run_pair(wl, p[0], p[1], **kw) for p in wl.K}
 

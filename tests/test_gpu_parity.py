@@ -374,6 +374,65 @@ def test_group_max_aggregation(cfg):
     dev.set_host_partials_from_oracle(res0)
 
 
+def test_per_head_selection(cfg):
+    """per_head = 1: every query head scores, selects and attends on its own (lists per query head, the
+    KV head's digest, table and pools shared), step by step and through the fused layer-step."""
+    if cfg.max_blocks > 1024 or cfg.B * cfg.Hq > 200:
+        pytest.skip("the oracle runs every head's attention; the larger shapes add nothing for this variant")
+    wl, res0, dev = setup(cfg)
+    dev.set_digest_from_oracle(res0)
+    heads = {(b, hq): harness.run_head(wl, b, hq) for b in range(cfg.B) for hq in range(cfg.Hq)}
+    code = B.F32 if cfg.dtype == "f32" else B.BF16
+    p2 = B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, code, cfg.max_blocks, cfg.k, dev.ctx_len, 0.0, per_head=1)
+    ws = B.alloc_workspace(p2)
+    ph = (cfg.B, cfg.Hq)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    scores = torch.full((*ph, cfg.max_blocks), float("nan"), dtype=torch.float32, device="cuda")
+    sel_all, sel_gpu, slot_gpu, sel_host = (torch.full((*ph, cfg.k), -7, **i32) for _ in range(4))
+    n_gpu, n_host = torch.full(ph, -7, **i32), torch.full(ph, -7, **i32)
+    ho = np.zeros((cfg.B, cfg.Hq, cfg.d), dtype=np.float32)
+    hm = np.full((cfg.B, cfg.Hq), -np.inf, dtype=np.float32)
+    hl = np.zeros((cfg.B, cfg.Hq), dtype=np.float32)
+    for (b, hq), op in heads.items():
+        ho[b, hq], hm[b, hq], hl[b, hq] = op.host_part[0]
+    host = [torch.from_numpy(a).cuda() for a in (ho, hm, hl)]
+
+    def check(tag):
+        got_s, sel = scores.cpu().numpy(), sel_all.cpu().numpy()
+        sg, ng, sh, nh = sel_gpu.cpu().numpy(), n_gpu.cpu().numpy(), sel_host.cpu().numpy(), n_host.cpu().numpy()
+        out = _f64(to_np(dev.out))
+        for (b, hq), op in heads.items():
+            nb = len(op.s32)
+            if nb:
+                rel = np.abs(got_s[b, hq, :nb].astype(np.float64) - op.s32) / np.maximum(np.abs(op.s32), 1e-30)
+                assert rel.max() <= 2e-7, (tag, b, hq)
+            if not np.array_equal(sel[b, hq], op.sel):
+                assert harness.boundary_gap(op, cfg.k) < 1e-6, (tag, b, hq)
+                continue
+            assert ng[b, hq] == op.n_gpu and nh[b, hq] == op.n_host, (tag, b, hq)
+            assert np.array_equal(sg[b, hq], op.sel_gpu) and np.array_equal(sh[b, hq], op.sel_host), (tag, b, hq)
+            assert np.abs(out[b, hq] - op.out[0][0]).max() <= TOL[cfg.dtype], (tag, b, hq)
+
+    B.score_blocks(p2, dev.q, dev.digest, scores, ws)
+    B.select_topk(p2, scores, dev.block_table, sel_all, sel_gpu, slot_gpu, n_gpu, sel_host, n_host, ws)
+    B.sparse_decode_attn(p2, dev.q, dev.k_pool, dev.v_pool, dev.n_slots, sel_gpu, slot_gpu, n_gpu, dev.o, dev.m, dev.l, ws)
+    B.merge_partials(p2, dev.o, dev.m, dev.l, *host, dev.out, dev.lse)
+    torch.cuda.synchronize()
+    check("separate calls")
+    for t in (scores, dev.out):
+        t.zero_()
+    for t in (sel_all, sel_gpu, slot_gpu, sel_host, n_gpu, n_host):
+        t.fill_(-7)
+    B.layer_step(p2, dev.q, dev.digest, dev.block_table, dev.k_pool, dev.v_pool, dev.n_slots, *host, scores, sel_all,
+                 sel_gpu, slot_gpu, n_gpu, sel_host, n_host, dev.out, dev.lse, ws)
+    torch.cuda.synchronize()
+    check("layer step")
+    # a recall plans for the KV head: not defined with a selection per query head
+    with pytest.raises(B.ScoutError):
+        B.periodic_recall(p2, dev.q, dev.digest, dev.block_table, dev.recall_blk, dev.recall_slot, dev.evict_blk,
+                          dev.n_recall, ws)
+
+
 def test_attn_partials_then_finish_equals_attention_then_merge(cfg):
     """The two-call form the pipeline uses (partials first, fold + merge with the host's partial once it
     has arrived) gives bit for bit what sparse_decode_attn followed by merge_partials gives."""

@@ -193,3 +193,29 @@ def test_pipeline_merge_equals_union_on_split_residency():
     for h in range(cfg.G):
         pu = oracle.partial_attn(qg[h], wl.K[(0, 0)], wl.V[(0, 0)], op.sel, 2048, cfg.S, cfg.sm_scale)
         np.testing.assert_allclose(op.out[h][0], pu[0], rtol=0, atol=1e-6)   # host partial went through binary32
+
+
+def test_per_head_selection_is_the_brute_force_rule_per_head():
+    """Selection per query head: every head keeps the k blocks with the largest value of ITS OWN
+    estimate sum_c max(q_c*min_c, q_c*max_c) (ties to the lower index), attends to exactly those, and
+    heads of one KV head may differ in what they keep."""
+    cfg = W.shrink(W.qwen3_8b(B=1, ctx=2048), p_host=0.5, k=8)
+    wl = W.generate(cfg)
+    differ = False
+    for hq in range(cfg.Hq):
+        op = harness.run_head(wl, 0, hq)
+        g = hq // cfg.G
+        q = _f64(wl.q[0, hq])
+        dig = _f64(op.dig)
+        est = np.maximum(q * dig[:, 0], q * dig[:, 1]).sum(axis=1)
+        est32 = est.astype(np.float32).astype(np.float64)
+        want = sorted(sorted(range(len(est)), key=lambda j: (-est32[j], j))[:cfg.k])
+        assert [int(j) for j in op.sel if j >= 0] == want, hq
+        # the two sides split that list by the KV head's residency and their merge is the attention over it
+        assert sorted(op.sel_gpu[:op.n_gpu].tolist() + op.sel_host[:op.n_host].tolist()) == want
+        assert all(wl.block_table[0, g, j] >= 0 for j in op.sel_gpu[:op.n_gpu])
+        pu = oracle.partial_attn(wl.q[0, hq], wl.K[(0, g)], wl.V[(0, g)], op.sel, int(cfg.ctx[0]), cfg.S, cfg.sm_scale)
+        np.testing.assert_allclose(op.out[0][0], pu[0], rtol=0, atol=1e-6)
+        shared = harness.run_pair(wl, 0, g, attention=False)
+        differ |= not np.array_equal(shared.sel, op.sel)
+    assert differ   # otherwise this workload could not tell the variant from the shared selection
