@@ -40,6 +40,8 @@ def parse(argv=None):
     ap.add_argument("--group-max", action="store_true",
                     help="time the variant that combines the group's heads by their maximum (not the metric's setting)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pipe-recall", type=int, default=0,
+                    help="with --pipeline: every layer recalls after each R-th step (staged route)")
     ap.add_argument("--no-recall-overlap", action="store_true",
                     help="skip the layer steps timed beside running recalls (keeps a kernel trace free of the "
                          "launches that are slowed on purpose)")
@@ -430,8 +432,15 @@ def pipeline_main(args):
         del k_all
         layers.append(P.Layer(digest, torch.from_numpy(wl.block_table).cuda(), dev(wl.k_pool), dev(wl.v_pool),
                               wl.n_slots, kb, vb))
-        qs.append(dev(wl.q))
-        qps.append(dev(W.gen_q_pred(wl.q, 0.94, seed=i)))
+        # with recalls in the loop the query drifts from step to step (cosine 0.98 between consecutive
+        # steps, 13 sets in rotation), so that every recall finds part of its selection changed; without,
+        # one set
+        n_sets = 13 if args.pipe_recall > 0 else 1
+        q_np = [wl.q]
+        for j in range(1, n_sets):
+            q_np.append(W.gen_q_pred(q_np[-1], 0.98, seed=1000 + 17 * i + j))
+        qs.append([dev(q) for q in q_np])
+        qps.append([dev(W.gen_q_pred(q, 0.94, seed=10 * j + i)) for j, q in enumerate(q_np)])
 
     filler = None
     if not args.pipe_no_filler:
@@ -448,21 +457,35 @@ def pipeline_main(args):
             (gu[:, :ffn] * gu[:, ffn:]) @ w_dn
 
     pipe = P.LayerAheadPipeline(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, B.BF16, cfg.max_blocks, cfg.k, ctx_len, layers,
-                                n_threads=args.pipe_threads, filler=filler)
+                                n_threads=args.pipe_threads, filler=filler, recall_every=args.pipe_recall,
+                                n_stage_threads=4)
     steps = max(8, args.steps // (2 * n_layers))
+    if args.pipe_recall > 0:
+        steps = max(steps, 6 * args.pipe_recall)
+    n_sets = len(qs[0])
+    recall_us, recall_tiles = [], []
 
     def run(host):
         """Median over decode steps of the wall time of a step (all layers, drained at its end, as a
         step ends with sampling anyway), per layer."""
+        def one():
+            j = pipe.step_no % n_sets
+            due = pipe.recall_every > 0 and pipe.step_no % pipe.recall_every == pipe.recall_every - 1
+            t0 = time.perf_counter()
+            pipe.step([q[j] for q in qs], [q[j] for q in qps], host=host)
+            torch.cuda.synchronize()
+            return time.perf_counter() - t0, due
         for _ in range(3):
-            pipe.step(qs, qps, host=host)
-        torch.cuda.synchronize()
+            one()
         hs, ws, ts = [], [], []
         for _ in range(steps):
-            t0 = time.perf_counter()
-            pipe.step(qs, qps, host=host)
-            torch.cuda.synchronize()
-            ts.append(time.perf_counter() - t0)
+            t, due = one()
+            if due:                                   # steps that also plan and move a recall, kept apart
+                if host:
+                    recall_us.append(t * 1e6 / n_layers)
+                    recall_tiles.append(pipe.recalled_tiles / n_layers)
+                continue
+            ts.append(t)
             hs += pipe.host_seconds
             ws += pipe.wait_seconds
         return float(np.median(ts)) * 1e6 / n_layers, hs, ws
@@ -486,6 +509,11 @@ def pipeline_main(args):
         "host_job_us": round(host_us, 1),
         "host_gbps": round(host_bytes / host_us * 1e-3, 2),
         "enqueue_thread_wait_us": round(float(np.median(ws)) * 1e6, 1),
+        # steps on which every layer also recalls (plan, host packing, copy, scatter beside the next layer)
+        "recall": None if not recall_us else {
+            "every": args.pipe_recall, "us_per_layer_on_recall_steps": round(float(np.median(recall_us)), 1),
+            "tiles_per_layer": round(float(np.median(recall_tiles)), 1),
+            "mib_per_layer": round(float(np.median(recall_tiles)) * 2 * cfg.S * cfg.d * 2 / 2**20, 2)},
     }))
 
 
