@@ -114,6 +114,44 @@ def score(q: np.ndarray, dig: np.ndarray) -> np.ndarray:
     return s
 
 
+def digest_sum(K: np.ndarray, ctx_len: int, S: int) -> np.ndarray:
+    """Mean-pooled digest stored as binary32 sums of the valid keys of each block: float32 [nb][d]."""
+    K = np.ascontiguousarray(K)
+    d = K.shape[1]
+    nb = (int(ctx_len) + S - 1) // S
+    out = np.zeros((nb, d), dtype=np.float32)
+    L = _L()
+    L.orc_digest_sum.restype = None
+    L.orc_digest_sum.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    L.orc_digest_sum(_dtype_code(K), K.ctypes.data, int(ctx_len), int(S), d, out.ctypes.data)
+    return out
+
+
+def append_sum(S: int, ctx_len: int, k_new: np.ndarray, sums: np.ndarray) -> None:
+    """The token at position ctx_len joins the sums [max_blocks][d] (float32, updated in place)."""
+    k_new = np.ascontiguousarray(k_new)
+    assert sums.dtype == np.float32 and sums.flags["C_CONTIGUOUS"] and sums.shape[1] == k_new.shape[-1]
+    L = _L()
+    L.orc_append_sum.restype = None
+    L.orc_append_sum.argtypes = [ctypes.c_int] * 5 + [ctypes.c_void_p] * 2
+    L.orc_append_sum(_dtype_code(k_new), int(S), sums.shape[1], sums.shape[0], int(ctx_len), k_new.ctypes.data,
+                     sums.ctypes.data)
+
+
+def score_mean(q: np.ndarray, sums: np.ndarray, ctx_len: int, S: int) -> np.ndarray:
+    """q: [G][d] storage, sums: float32 [nb][d].  Returns float64 [nb]: sum over heads of q . mean."""
+    q = np.ascontiguousarray(q)
+    sums = np.ascontiguousarray(sums, dtype=np.float32)
+    G, d = q.shape
+    nb = sums.shape[0]
+    s = np.zeros(nb, dtype=np.float64)
+    L = _L()
+    L.orc_score_mean.restype = None
+    L.orc_score_mean.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int] * 5 + [ctypes.c_void_p]
+    L.orc_score_mean(_dtype_code(q), q.ctypes.data, sums.ctypes.data, nb, G, d, int(ctx_len), int(S), s.ctypes.data)
+    return s
+
+
 def decision_scores(s: np.ndarray) -> np.ndarray:
     """Scores as the selection sees them: rounded once to binary32.
 

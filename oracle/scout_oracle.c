@@ -333,6 +333,60 @@ int orc_recall_fetch(int dtype, int S, int d, int max_blocks, const void* src_k,
 }
 
 /*
+ * Mean-pooled block digest (Sec. 2.2 names mean pooling over a block's keys as
+ * the other common digest; a variant of the min/max digest the method uses).
+ * It is stored as the SUM of the block's valid keys in binary32, added in token
+ * order, so that an append extends it by one addition and a digest built at once
+ * equals one grown token by token; the mean is sum / count where it is used.
+ * K is [ctx_len][d]; out is f32 [ceil(ctx_len/S)][d].
+ */
+void orc_digest_sum(int dtype, const void* K, int ctx_len, int S, int d, float* out) {
+  int nb = (ctx_len + S - 1) / S;
+  for (int j = 0; j < nb; ++j) {
+    int t0 = j * S, t1 = t0 + S < ctx_len ? t0 + S : ctx_len;
+    for (int c = 0; c < d; ++c) {
+      float sum = (float)ld(K, dtype, (size_t)t0 * d + c);
+      for (int t = t0 + 1; t < t1; ++t) {
+        volatile float next = sum + (float)ld(K, dtype, (size_t)t * d + c); /* one binary32 rounding per token */
+        sum = next;
+      }
+      out[(size_t)j * d + c] = sum;
+    }
+  }
+}
+
+/* The append of one key to that digest: the token at position ctx_len opens block ctx_len / S with
+ * its key, or is added to the block's sum (binary32).  sums is f32 [max_blocks][d].  Nothing happens
+ * when the sequence already fills max_blocks blocks. */
+void orc_append_sum(int dtype, int S, int d, int max_blocks, int ctx_len, const void* k_new, float* sums) {
+  if (ctx_len >= max_blocks * S) return;
+  int j = ctx_len / S, r = ctx_len % S;
+  for (int c = 0; c < d; ++c) {
+    float k = (float)ld(k_new, dtype, c);
+    volatile float next = sums[(size_t)j * d + c] + k;
+    sums[(size_t)j * d + c] = r == 0 ? k : next;
+  }
+}
+
+/*
+ * Block importance with the mean-pooled digest: the query against the block's
+ * mean key, summed over the G query heads of the KV head,
+ *   s_j = sum_h sum_c q[h][c] * sums[j][c] / count_j,
+ * count_j the number of valid tokens of block j.  q is [G][d], sums f32 [nb][d].
+ */
+void orc_score_mean(int dtype, const void* q, const float* sums, int nb, int G, int d, int ctx_len, int S,
+                    double* s) {
+  for (int j = 0; j < nb; ++j) {
+    int count = ctx_len - j * S;
+    if (count > S) count = S;
+    double acc = 0.0;
+    for (int h = 0; h < G; ++h)
+      for (int c = 0; c < d; ++c) acc += ld(q, dtype, (size_t)h * d + c) * (double)sums[(size_t)j * d + c];
+    s[j] = acc / (double)count;
+  }
+}
+
+/*
  * The same recall through a staging buffer (Sec. 3.4, asynchronous transfer:
  * the host packs the planned tiles so that they cross the host link as one
  * contiguous copy, the device then puts them into their slots).

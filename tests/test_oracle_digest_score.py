@@ -145,3 +145,56 @@ def test_score_max_is_the_maximum_of_the_per_head_estimates(dtype, G, d, nb, S):
     Kf = W.storage_to_f32(K).astype(np.float64).reshape(nb, S, d)
     dots = np.einsum("hc,jtc->jht", qf, Kf).max(axis=2)     # [nb][G] largest true logit per head
     assert (per_head >= dots - 1e-9).all() and (got >= dots.max(axis=1) - 1e-9).all()
+
+
+# ---------------------------------------------------------------- mean-pooled digest (stored as sums)
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("ctx,S", [(96, 32), (70, 16), (5, 64), (64, 64)])
+def test_digest_sum_is_the_sequential_binary32_sum(dtype, ctx, S):
+    rng = np.random.default_rng(ctx * 7 + S)
+    K = W.to_storage(rng.standard_normal((ctx, 24)).astype(np.float32) * 3, dtype)
+    got = oracle.digest_sum(K, ctx, S)
+    Kf = W.storage_to_f32(K)
+    nb = (ctx + S - 1) // S
+    assert got.shape == (nb, 24) and got.dtype == np.float32
+    for j in range(nb):
+        blk = Kf[j * S:min(ctx, (j + 1) * S)]
+        assert np.array_equal(got[j], np.cumsum(blk, axis=0, dtype=np.float32)[-1])      # sequential, one rounding per token
+        exact = blk.astype(np.float64).sum(axis=0)
+        assert np.abs(got[j] - exact).max() <= 1e-6 * np.abs(blk).astype(np.float64).sum(axis=0).max()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_append_sum_grows_the_digest_built_at_once(dtype):
+    rng = np.random.default_rng(77)
+    S, d, mb = 8, 16, 5
+    K = W.to_storage(rng.standard_normal((mb * S, d)).astype(np.float32), dtype)
+    sums = np.full((mb, d), 123.0, dtype=np.float32)       # stale contents must not leak into a new block
+    for t in range(mb * S - 3):
+        oracle.append_sum(S, t, K[t], sums)
+        nb = t // S + 1
+        assert np.array_equal(sums[:nb], oracle.digest_sum(K[:t + 1], t + 1, S)), t
+    before = sums.copy()
+    oracle.append_sum(S, mb * S, K[0], sums)                # a full sequence is left as it is
+    assert np.array_equal(sums, before)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_score_mean_is_the_query_group_against_the_block_means(dtype):
+    rng = np.random.default_rng(91)
+    ctx, S, d, G = 150, 32, 64, 4
+    K = W.to_storage(rng.standard_normal((ctx, d)).astype(np.float32), dtype)
+    q = W.to_storage(rng.standard_normal((G, d)).astype(np.float32), dtype)
+    sums = oracle.digest_sum(K, ctx, S)
+    got = oracle.score_mean(q, sums, ctx, S)
+    Kf, qf = W.storage_to_f32(K).astype(np.float64), W.storage_to_f32(q).astype(np.float64)
+    for j in range(len(sums)):
+        blk = Kf[j * S:min(ctx, (j + 1) * S)]
+        want = float((qf @ blk.mean(axis=0)).sum())         # sum over heads of q_h . mean_j, exact means
+        assert abs(got[j] - want) <= 1e-5 * max(1.0, abs(want)), j
+        # and exactly the definition on the stored sums
+        want2 = float((qf @ sums[j].astype(np.float64)).sum()) / len(blk)
+        assert abs(got[j] - want2) <= 1e-12 * max(1.0, abs(want2))
+    # a transposed operand or a forgotten division by the count of the partly filled last block would show
+    assert ctx % S != 0
