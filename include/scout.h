@@ -74,6 +74,12 @@ typedef struct scout_problem {
                          then have Hq where the layouts below say Hkv, while
                          digest, block_table, the pools and everything about
                          building, appending and recalling keep Hkv             */
+  int32_t digest_kind; /* 0 = channel-wise min and max of a block's keys (default; the
+                         digest layouts below), 1 = mean pooling: `digest` is then
+                         f32 [B][Hkv][max_blocks][d], the SUM of the block's valid
+                         keys in binary32 added in token order (an append is one
+                         addition and equals a rebuild bit for bit), and a block's
+                         importance is sum_h q_h . sum / count; not with group_max */
   const int32_t* ctx_len; /* DEVICE int32 [B]: tokens per sequence; blocks beyond
                              max_blocks are ignored                                  */
 } scout_problem;

@@ -49,6 +49,8 @@ static int check_problem(const scout_problem* p, Dims* D) {
   if (!(p->sm_scale >= 0.0f) || std::isinf(p->sm_scale)) return SCOUT_EINVAL;
   if (p->n_sink < 0 || p->n_tail < 0 || (p->group_max != 0 && p->group_max != 1)) return SCOUT_EINVAL;
   if (p->per_head != 0 && p->per_head != 1) return SCOUT_EINVAL;
+  if (p->digest_kind != 0 && p->digest_kind != 1) return SCOUT_EINVAL;
+  if (p->digest_kind == 1 && p->group_max) return SCOUT_EUNSUPPORTED;
   if (p->ctx_len == nullptr) return SCOUT_EINVAL;
   if (p->d != 64 && p->d != 128) return SCOUT_EUNSUPPORTED;
   if (p->S != 16 && p->S != 32 && p->S != 64) return SCOUT_EUNSUPPORTED;
@@ -67,6 +69,7 @@ static int check_problem(const scout_problem* p, Dims* D) {
   D->n_sink = p->n_sink;
   D->n_tail = p->n_tail;
   D->group_max = p->group_max;
+  D->digest_kind = p->digest_kind;
   D->share = 1;
   if (p->per_head) {  // every query head is a pair of its own that reads its KV head's digest and table rows
     D->share = D->G;

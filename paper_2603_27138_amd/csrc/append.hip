@@ -1,6 +1,6 @@
 // Decode append: the key and value of the token that decode just produced join the cache, and the
-// digest of the block they fall into (Sec. 2.2: channel-wise min/max over the block's keys) is kept
-// up to date, so that the digests of all blocks stay on the GPU as Sec. 3.2 requires while the
+// digest of the block they fall into (Sec. 2.2: channel-wise min/max over the block's keys, or their
+// sum for mean pooling) is kept up to date, so that the digests of all blocks stay on the GPU as Sec. 3.2 requires while the
 // sequence grows.
 //
 // One workgroup per sequence, one thread per (KV head, channel) element: a few kilobytes per call,
@@ -39,7 +39,12 @@ __global__ __launch_bounds__(1024) void append_kernel(Dims D, int32_t* ctx_len, 
       const int slot = r == 0 ? new_slot[pair] : *entry;
       const E k = kn[pair * D.d + c], v = vn[pair * D.d + c];
       const size_t i_min = ((pair * D.max_blocks + j) * 2) * D.d + c, i_max = i_min + D.d;
-      if (r == 0) {
+      if (D.digest_kind == 1) {  // mean pooling: the block's running sum in binary32, one addition per token
+        float* sums = static_cast<float*>(digest);
+        const size_t i_sum = (pair * D.max_blocks + j) * D.d + c;
+        const float kf = load1<DT>(kn, pair * D.d + c);
+        sums[i_sum] = r == 0 ? kf : sums[i_sum] + kf;
+      } else if (r == 0) {
         dg[i_min] = k;
         dg[i_max] = k;
       } else {

@@ -17,6 +17,7 @@ struct Dims {
   float sm_scale;
   int n_sink, n_tail;  // always-kept blocks at the start and at the end of a sequence
   int group_max;       // block importance: 0 = sum over the group's heads, 1 = their maximum
+  int digest_kind;     // 0 = channel-wise min and max in the element type, 1 = binary32 sums of the keys (mean pooling)
   int share;           // consecutive pairs that share one digest / block-table row: 1, or with a selection
                        // per query head the real group size (then Hkv = Hq and G = 1 here)
   const int32_t* ctx_len;

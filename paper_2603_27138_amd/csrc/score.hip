@@ -69,6 +69,34 @@ __global__ __launch_bounds__(256) void digest_kernel(Dims D, const void* __restr
   }
 }
 
+// Mean pooling (Sec. 2.2 names it next to min/max pooling): the digest of a block is the sum of its
+// valid keys in binary32, added in token order, one rounding per token, so that the append of a token
+// is one addition and gives the bits a rebuild would give; the mean is sum / count where it is used.
+template <int DT>
+__global__ __launch_bounds__(256) void digest_sum_kernel(Dims D, const void* __restrict__ k_blocks,
+                                                         float* __restrict__ digest) {
+  const int pair = blockIdx.y;
+  const int b = pair / D.Hkv;
+  const int cpt = D.d / 8;
+  const int j = blockIdx.x * (blockDim.x / cpt) + threadIdx.x / cpt;
+  const int c0 = (threadIdx.x % cpt) * 8;
+  const int nb = num_blocks_of(D, b);
+  if (j >= nb) return;
+  int valid = D.ctx_len[b] - j * D.S;
+  if (valid > D.S) valid = D.S;
+  const size_t row0 = ((size_t)pair * D.max_blocks + j) * D.S;
+  float sum[8], x[8];
+  load8<DT>(k_blocks, row0 * D.d + c0, sum);
+  for (int t = 1; t < valid; ++t) {
+    load8<DT>(k_blocks, (row0 + t) * D.d + c0, x);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sum[i] = sum[i] + x[i];
+  }
+  float4* out = reinterpret_cast<float4*>(digest + ((size_t)pair * D.max_blocks + j) * D.d + c0);
+  out[0] = make_float4(sum[0], sum[1], sum[2], sum[3]);
+  out[1] = make_float4(sum[4], sum[5], sum[6], sum[7]);
+}
+
 // ------------------------------------------------------------------- score
 
 constexpr int kScoreWaves = 4;      // waves per workgroup
@@ -96,12 +124,18 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 // deliberately not marked restrict: loads that the compiler knows to be invariant float freely, and
 // here the order of issue matters (queries first, then batch by batch), because a wait for one load
 // is a wait for every load issued before it.
-template <int DT, int DH>
+//
+// MEAN: the digest entry is one row of binary32 sums of the block's keys (mean pooling) whatever the
+// element type of the queries; the score is (sum over heads of q) . sums / count, so there is one
+// coefficient vector instead of two and a division by the block's token count at the end.
+template <int DT, int DH, bool MEAN>
 __global__ __launch_bounds__(kScoreWaves* kWave) void score_kernel(
     Dims D, const void* q, const void* digest, float* scores) {
-  constexpr int EPL = (DT == SCOUT_BF16) ? 8 : 4;  // elements per 16-byte load
-  constexpr int ESZ = (DT == SCOUT_BF16) ? 2 : 4;
-  constexpr int EB = 2 * DH * ESZ;                 // bytes per digest entry
+  constexpr bool DIG16 = DT == SCOUT_BF16 && !MEAN;  // digest elements are bf16
+  constexpr int EPL = DIG16 ? 8 : 4;               // digest elements per 16-byte load
+  constexpr int ESZ = (DT == SCOUT_BF16) ? 2 : 4;  // bytes per query element
+  constexpr int DSZ = DIG16 ? 2 : 4;               // bytes per digest element
+  constexpr int EB = (MEAN ? 1 : 2) * DH * DSZ;    // bytes per digest entry
   constexpr int NL = EB / 128;                     // 128-byte lines per entry
   constexpr int NG = kScoreBatch / NL;             // 8-entry groups per batch
   constexpr int BLK_PER_WAVE = NG * 8 * kScoreBatches;
@@ -153,17 +187,19 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_kernel(
     double f = 0.0;
 #pragma unroll
     for (int h = 0; h < 16; ++h)
-      if (h < D.G) f += (double)(fpos ? fmaxf(qv[h], 0.0f) : fminf(qv[h], 0.0f));
-    if (threadIdx.x < 2 * DH) coef_lds[fpos ? 1 : 0][fc] = f;
+      if (h < D.G) f += MEAN ? (double)qv[h] : (double)(fpos ? fmaxf(qv[h], 0.0f) : fminf(qv[h], 0.0f));
+    if (threadIdx.x < 2 * DH) coef_lds[fpos ? 1 : 0][fc] = f;  // MEAN: both rows hold the plain sum
   }
   __syncthreads();
-  // line u of an entry: min row for u < NL/2, max row after; channels (u % (NL/2))*128/ESZ + 8 lanes x EPL
+  // line u of an entry: min row for u < NL/2, max row after (MEAN: the one row of sums);
+  // channels (u % lines per row) * 128/DSZ + 8 lanes x EPL
+  constexpr int LPR = MEAN ? NL : NL / 2;  // lines per digest row
   double coef[NL][EPL];
 #pragma unroll
   for (int u = 0; u < NL; ++u)
 #pragma unroll
     for (int i = 0; i < EPL; ++i)
-      coef[u][i] = coef_lds[u >= NL / 2 ? 1 : 0][(u % (NL / 2)) * (128 / ESZ) + (lane & 7) * EPL + i];
+      coef[u][i] = coef_lds[u >= LPR ? 1 : 0][(u % LPR) * (128 / DSZ) + (lane & 7) * EPL + i];
 
   const bool hi2 = (lane >> 2) & 1, hi1 = (lane >> 1) & 1;
   const int my_g = NG == 4 ? (hi2 ? 2 : 0) + (hi1 ? 1 : 0) : NG == 2 ? (hi2 ? 1 : 0) : 0;
@@ -179,7 +215,7 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_kernel(
 #pragma unroll
       for (int u = 0; u < NL; ++u) {
         const u32x4 w = cur[gq * NL + u];
-        if (DT == SCOUT_BF16) {
+        if (DIG16) {
           acc = fma(coef[u][0], (double)bf16_lo(w[0]), acc);
           acc = fma(coef[u][1], (double)bf16_hi(w[0]), acc);
           acc = fma(coef[u][2 % EPL], (double)bf16_lo(w[1]), acc);
@@ -225,7 +261,13 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_kernel(
     const int j = j_wave + (t * NG + my_g) * 8 + (lane >> 3);
     if (writer && j < D.max_blocks) {
       const bool kept = j < D.n_sink || j >= nb - D.n_tail;  // always-kept blocks rank above every score
-      scores[(size_t)pair * D.max_blocks + j] = j < nb ? (kept ? INFINITY : (float)a[0]) : -INFINITY;
+      double sc = a[0];
+      if (MEAN) {  // sums -> means: the block's token count (the last block may be partly filled)
+        int cnt = D.ctx_len[b] - j * D.S;
+        cnt = cnt > D.S ? D.S : (cnt < 1 ? 1 : cnt);
+        sc = sc / (double)cnt;
+      }
+      scores[(size_t)pair * D.max_blocks + j] = j < nb ? (kept ? INFINITY : (float)sc) : -INFINITY;
     }
   }
 }
@@ -333,6 +375,14 @@ int launch_digest(const Dims& D, int dtype, const void* k_blocks, void* digest, 
   const int blocks_per_wg = 256 / cpt;
   dim3 grid((D.max_blocks + blocks_per_wg - 1) / blocks_per_wg, D.B * D.Hkv);
   if (grid.x == 0 || grid.y == 0) return SCOUT_OK;
+  if (D.digest_kind == 1) {
+    float* sums = static_cast<float*>(digest);
+    if (dtype == SCOUT_BF16)
+      hipLaunchKernelGGL(digest_sum_kernel<SCOUT_BF16>, grid, dim3(256), 0, st, D, k_blocks, sums);
+    else
+      hipLaunchKernelGGL(digest_sum_kernel<SCOUT_F32>, grid, dim3(256), 0, st, D, k_blocks, sums);
+    return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
+  }
   if (dtype == SCOUT_BF16)
     hipLaunchKernelGGL(digest_kernel<SCOUT_BF16>, grid, dim3(256), 0, st, D, k_blocks, digest);
   else
@@ -359,25 +409,33 @@ int launch_score_max(const Dims& D, int dtype, const void* q, const void* digest
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
 }
 
-int launch_score(const Dims& D, int dtype, const void* q, const void* digest, float* scores,
-                 hipStream_t st) {
-  if (D.group_max) return launch_score_max(D, dtype, q, digest, scores, st);
-  const int lines = 2 * D.d * (dtype == SCOUT_BF16 ? 2 : 4) / 128;  // 128-byte lines per digest entry
+template <bool MEAN>
+static int launch_score_sum(const Dims& D, int dtype, const void* q, const void* digest, float* scores,
+                            hipStream_t st) {
+  const int entry_bytes = MEAN ? D.d * 4 : 2 * D.d * (dtype == SCOUT_BF16 ? 2 : 4);
+  const int lines = entry_bytes / 128;  // 128-byte lines per digest entry
   const int blocks_per_wg = kScoreBatch / lines * 8 * kScoreBatches * kScoreWaves;
   dim3 grid((D.max_blocks + blocks_per_wg - 1) / blocks_per_wg, D.B * D.Hkv);
   dim3 block(kScoreWaves * kWave);
   if (grid.x == 0 || grid.y == 0) return SCOUT_OK;
   if (dtype == SCOUT_BF16 && D.d == 128)
-    hipLaunchKernelGGL((score_kernel<SCOUT_BF16, 128>), grid, block, 0, st, D, q, digest, scores);
+    hipLaunchKernelGGL((score_kernel<SCOUT_BF16, 128, MEAN>), grid, block, 0, st, D, q, digest, scores);
   else if (dtype == SCOUT_BF16 && D.d == 64)
-    hipLaunchKernelGGL((score_kernel<SCOUT_BF16, 64>), grid, block, 0, st, D, q, digest, scores);
+    hipLaunchKernelGGL((score_kernel<SCOUT_BF16, 64, MEAN>), grid, block, 0, st, D, q, digest, scores);
   else if (dtype == SCOUT_F32 && D.d == 128)
-    hipLaunchKernelGGL((score_kernel<SCOUT_F32, 128>), grid, block, 0, st, D, q, digest, scores);
+    hipLaunchKernelGGL((score_kernel<SCOUT_F32, 128, MEAN>), grid, block, 0, st, D, q, digest, scores);
   else if (dtype == SCOUT_F32 && D.d == 64)
-    hipLaunchKernelGGL((score_kernel<SCOUT_F32, 64>), grid, block, 0, st, D, q, digest, scores);
+    hipLaunchKernelGGL((score_kernel<SCOUT_F32, 64, MEAN>), grid, block, 0, st, D, q, digest, scores);
   else
     return SCOUT_EUNSUPPORTED;
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
+}
+
+int launch_score(const Dims& D, int dtype, const void* q, const void* digest, float* scores,
+                 hipStream_t st) {
+  if (D.digest_kind == 1) return D.group_max ? SCOUT_EUNSUPPORTED : launch_score_sum<true>(D, dtype, q, digest, scores, st);
+  if (D.group_max) return launch_score_max(D, dtype, q, digest, scores, st);
+  return launch_score_sum<false>(D, dtype, q, digest, scores, st);
 }
 
 }  // namespace scout
