@@ -283,14 +283,13 @@ int recall_fetch(const scout_problem* p, const void* src_k, const void* src_v,
  * goes to pool slot recall_slot[i]; entries whose recall_blk is outside
  * [0, max_blocks) or whose slot is outside [0, n_slots) are skipped, so the
  * result equals recall_fetch's.
- *   staged    e   [tiles][2][S][d]   DEVICE, 16-byte aligned
- *   tile_off  i32 [B][Hkv]           DEVICE: first tile of each pair (the
- *                                    exclusive prefix sum of min(n_recall, k))
+ *   staged    e   [n_tiles][2][S][d]   DEVICE, 16-byte aligned
+ *   tile_off  i32 [B][Hkv]             DEVICE: first tile of each pair (the
+ *                                      exclusive prefix sum of min(n_recall, k))
  *   the other arguments as for recall_fetch
- * The caller guarantees that the buffer holds tile_off[pair] + min(n_recall, k)
- * tiles for every pair.
+ * An entry whose tile index falls outside [0, n_tiles) moves nothing.
  */
-int recall_scatter(const scout_problem* p, const void* staged, const int32_t* tile_off,
+int recall_scatter(const scout_problem* p, const void* staged, int64_t n_tiles, const int32_t* tile_off,
                    const int32_t* recall_blk, const int32_t* recall_slot, const int32_t* n_recall,
                    void* k_pool, void* v_pool, int64_t n_slots, void* stream);
 

@@ -66,7 +66,7 @@ def lib():
         L.merge_partials.argtypes = [pp] + [vp] * 9
         L.periodic_recall.argtypes = [pp] + [vp] * 8 + [sz, vp]
         L.recall_fetch.argtypes = [pp] + [vp] * 7 + [i64, vp]
-        L.recall_scatter.argtypes = [pp] + [vp] * 7 + [i64, vp]
+        L.recall_scatter.argtypes = [pp, vp, i64] + [vp] * 6 + [i64, vp]
         L.scout_calib_copy.argtypes = [vp, vp, sz, vp]
         L.scout_calib_read.argtypes = [vp, sz, vp, vp]
         L.scout_calib_gather.argtypes = [pp, vp, vp, i64, vp, vp, vp, vp]
@@ -242,7 +242,10 @@ def recall_fetch(p: Problem, src_k, src_v, recall_blk, recall_slot, n_recall, k_
 
 def recall_scatter(p: Problem, staged, tile_off, recall_blk, recall_slot, n_recall, k_pool, v_pool, n_slots):
     """staged: device buffer of packed tiles [tiles][2][S][d]; tile_off: first tile of each pair."""
-    _call("recall_scatter", lib().recall_scatter, ctypes.byref(p), _ptr(staged), _ptr(tile_off), _ptr(recall_blk),
+    tile_elems = p.S * p.d * 2
+    assert staged.numel() % tile_elems == 0
+    _call("recall_scatter", lib().recall_scatter, ctypes.byref(p), _ptr(staged), staged.numel() // tile_elems,
+          _ptr(tile_off), _ptr(recall_blk),
           _ptr(recall_slot), _ptr(n_recall), _ptr(k_pool), _ptr(v_pool), int(n_slots), _stream())
 
 

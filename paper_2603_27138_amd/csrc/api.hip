@@ -12,7 +12,7 @@ int launch_digest(const Dims&, int, const void*, void*, hipStream_t);
 int launch_score(const Dims&, int, const void*, const void*, float*, hipStream_t);
 int launch_recall_fetch(const Dims&, int, const void*, const void*, const int32_t*, const int32_t*, const int32_t*,
                         void*, void*, long long, hipStream_t);
-int launch_recall_scatter(const Dims&, int, const void*, const int32_t*, const int32_t*, const int32_t*,
+int launch_recall_scatter(const Dims&, int, const void*, long long, const int32_t*, const int32_t*, const int32_t*,
                           const int32_t*, void*, void*, long long, hipStream_t);
 int launch_append(const Dims&, int, int32_t*, const void*, const void*, const int32_t*, void*, int32_t*, void*, void*,
                   long long, void*, void*, hipStream_t);
@@ -480,15 +480,15 @@ int recall_fetch(const scout_problem* p, const void* src_k, const void* src_v, c
                              n_slots, static_cast<hipStream_t>(stream));
 }
 
-int recall_scatter(const scout_problem* p, const void* staged, const int32_t* tile_off,
+int recall_scatter(const scout_problem* p, const void* staged, int64_t n_tiles, const int32_t* tile_off,
                    const int32_t* recall_blk, const int32_t* recall_slot, const int32_t* n_recall, void* k_pool,
                    void* v_pool, int64_t n_slots, void* stream) {
   Dims D;
   int rc = check_problem_kv(p, &D);
   if (rc != SCOUT_OK) return rc;
   if (!staged || !tile_off || !recall_blk || !recall_slot || !n_recall || !k_pool || !v_pool) return SCOUT_EINVAL;
-  if (!aligned16(staged) || !aligned16(k_pool) || !aligned16(v_pool) || n_slots < 0) return SCOUT_EINVAL;
-  return launch_recall_scatter(D, p->dtype, staged, tile_off, recall_blk, recall_slot, n_recall, k_pool, v_pool,
+  if (!aligned16(staged) || !aligned16(k_pool) || !aligned16(v_pool) || n_slots < 0 || n_tiles < 0) return SCOUT_EINVAL;
+  return launch_recall_scatter(D, p->dtype, staged, (long long)n_tiles, tile_off, recall_blk, recall_slot, n_recall, k_pool, v_pool,
                                n_slots, static_cast<hipStream_t>(stream));
 }
 

@@ -76,19 +76,20 @@ __global__ __launch_bounds__(kFetchThreads) void recall_fetch_kernel(
 // deal the pair's entries round robin (a recall moves a fraction of the budget, so a workgroup per
 // possible entry would mostly launch workgroups that find nothing to do).
 __global__ __launch_bounds__(kFetchThreads) void recall_scatter_kernel(
-    Dims D, int tile_bytes, const char* __restrict__ staged, const int32_t* __restrict__ tile_off,
-    const int32_t* __restrict__ recall_blk, const int32_t* __restrict__ recall_slot,
-    const int32_t* __restrict__ n_recall, char* __restrict__ k_pool, char* __restrict__ v_pool,
-    long long n_slots) {
+    Dims D, int tile_bytes, const char* __restrict__ staged, long long n_tiles,
+    const int32_t* __restrict__ tile_off, const int32_t* __restrict__ recall_blk,
+    const int32_t* __restrict__ recall_slot, const int32_t* __restrict__ n_recall, char* __restrict__ k_pool,
+    char* __restrict__ v_pool, long long n_slots) {
   const int pair = blockIdx.y;
   int n = n_recall[pair];
   n = n < D.k ? n : D.k;
   if ((int)blockIdx.x >= n) return;
-  const size_t first = (size_t)tile_off[pair];
+  const long long first = tile_off[pair];
   for (int i = blockIdx.x; i < n; i += gridDim.x) {
     const int blk = recall_blk[(size_t)pair * D.k + i], slot = recall_slot[(size_t)pair * D.k + i];
     if (blk < 0 || blk >= D.max_blocks || slot < 0 || slot >= n_slots) continue;
-    const char* from = staged + (first + i) * 2 * tile_bytes;
+    if (first < 0 || first + i >= n_tiles) continue;  // an offset that points outside the buffer moves nothing
+    const char* from = staged + (size_t)(first + i) * 2 * tile_bytes;
     const size_t dst = (size_t)slot * tile_bytes;
     move_tiles(from, from + tile_bytes, k_pool + dst, v_pool + dst, tile_bytes / 16);
   }
@@ -111,7 +112,7 @@ int launch_recall_fetch(const Dims& D, int dtype, const void* src_k, const void*
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
 }
 
-int launch_recall_scatter(const Dims& D, int dtype, const void* staged, const int32_t* tile_off,
+int launch_recall_scatter(const Dims& D, int dtype, const void* staged, long long n_tiles, const int32_t* tile_off,
                           const int32_t* recall_blk, const int32_t* recall_slot, const int32_t* n_recall,
                           void* k_pool, void* v_pool, long long n_slots, hipStream_t st) {
   const int tile_bytes = D.S * D.d * (dtype == SCOUT_BF16 ? 2 : 4);
@@ -119,7 +120,7 @@ int launch_recall_scatter(const Dims& D, int dtype, const void* staged, const in
   dim3 grid(D.k < 16 ? D.k : 16, D.B * D.Hkv);
   if (grid.x == 0 || grid.y == 0) return SCOUT_OK;
   hipLaunchKernelGGL(recall_scatter_kernel, grid, dim3(kFetchThreads), 0, st, D, tile_bytes,
-                     static_cast<const char*>(staged), tile_off, recall_blk, recall_slot, n_recall,
+                     static_cast<const char*>(staged), n_tiles, tile_off, recall_blk, recall_slot, n_recall,
                      static_cast<char*>(k_pool), static_cast<char*>(v_pool), n_slots);
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
 }

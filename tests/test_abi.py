@@ -96,9 +96,10 @@ def test_null_misaligned_and_workspace_errors(lib):
     # host partial must be given completely or not at all
     assert L.merge_partials(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, None, None, FAKE, None, None) == lib.EINVAL
     assert L.periodic_recall(ctypes.byref(p), FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == lib.EINVAL
-    assert L.recall_scatter(ctypes.byref(p), None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 4, None) == lib.EINVAL
-    assert L.recall_scatter(ctypes.byref(p), odd, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 4, None) == lib.EINVAL
-    assert L.recall_scatter(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, -1, None) == lib.EINVAL
+    assert L.recall_scatter(ctypes.byref(p), None, 4, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 4, None) == lib.EINVAL
+    assert L.recall_scatter(ctypes.byref(p), odd, 4, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 4, None) == lib.EINVAL
+    assert L.recall_scatter(ctypes.byref(p), FAKE, 4, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, -1, None) == lib.EINVAL
+    assert L.recall_scatter(ctypes.byref(p), FAKE, -4, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 4, None) == lib.EINVAL
     assert L.recall_fetch(ctypes.byref(p), FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, 4, None) == lib.EINVAL
     assert L.scout_set_attn_mode(4, 0, 0) == lib.EINVAL and L.scout_set_attn_mode(0, 0, 4) == lib.EINVAL and L.scout_set_attn_mode(0, 0, 0) == 0
     # MFMA family forced on a shape it does not cover

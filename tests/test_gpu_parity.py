@@ -542,7 +542,8 @@ def test_recall_staged_route_bit_exact(cfg):
 
     hp = H.HostProblem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, H.F32 if cfg.dtype == "f32" else H.BF16, cfg.max_blocks,
                        cfg.k, 0.0)
-    staged = torch.zeros(max(1, want_staged.size), dtype=torch.from_numpy(_bits16(want_staged)).dtype).pin_memory()
+    staged = torch.zeros(max(2 * cfg.S * cfg.d, want_staged.size),
+                         dtype=torch.from_numpy(_bits16(want_staged)).dtype).pin_memory()
     off = torch.zeros(max(1, pairs), dtype=torch.int32).pin_memory()
     worker = H.HostWorker(4)
     try:
@@ -564,6 +565,13 @@ def test_recall_staged_route_bit_exact(cfg):
     torch.cuda.synchronize()
     assert np.array_equal(_bits(to_np(k2)), _bits(kp)) and np.array_equal(_bits(to_np(v2)), _bits(vp))
     assert placed > 0 or not _can_move(cfg)
+    # offsets that point outside the packed buffer move nothing and fault nothing
+    k3, v3 = dev.k_pool.clone(), dev.v_pool.clone()
+    far = torch.full_like(d_off, 2 ** 30)
+    B.recall_scatter(dev.p, d_staged, far, d_rb, d_rs, d_nr, k3, v3, dev.n_slots)
+    B.recall_scatter(dev.p, d_staged, -far, d_rb, d_rs, d_nr, k3, v3, dev.n_slots)
+    torch.cuda.synchronize()
+    assert np.array_equal(_bits(to_np(k3)), _bits(wl.k_pool)) and np.array_equal(_bits(to_np(v3)), _bits(wl.v_pool))
 
 
 def test_recall_then_select_leaves_nothing_on_host():
