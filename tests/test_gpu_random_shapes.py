@@ -75,3 +75,90 @@ def test_random_shape(i):
             r = oracle.rank(s)
             gaps = [abs(s[r[j]] - s[r[j + 1]]) / max(abs(s[r[j]]), 1e-300) for j in range(len(s) - 1)]
             assert gaps and min(gaps) < 1e-6, (cfg, b, g)
+
+
+def _unit_oracle(wl, b, heads, g, sums, variant):
+    """One selection unit (the heads that share a selection) with the variant's scoring: returns
+    (decision scores after always-kept blocks, selection, per-head (out, lse), per-head host partial)."""
+    cfg = wl.cfg
+    K, V, ctx = wl.K[(b, g)], wl.V[(b, g)], int(cfg.ctx[b])
+    qu = wl.q[b, heads[0]:heads[-1] + 1]
+    if variant["digest_kind"]:
+        s = oracle.score_mean(qu, sums[(b, g)], ctx, cfg.S)
+    elif variant["group_max"]:
+        s = oracle.score_max(qu, oracle.digest(K, ctx, cfg.S))
+    else:
+        s = oracle.score(qu, oracle.digest(K, ctx, cfg.S))
+    f = oracle.force_blocks(oracle.decision_scores(s), variant["n_sink"], variant["n_tail"])
+    sel = oracle.select(f, cfg.k)
+    sg, ng, sh, nh = oracle.split(sel, wl.block_table[b, g])
+    outs, hosts = [], []
+    for hq in heads:
+        pg = oracle.partial_attn(wl.q[b, hq], K, V, sg, ctx, cfg.S, cfg.sm_scale)
+        ph = oracle.partial_attn(wl.q[b, hq], K, V, sh, ctx, cfg.S, cfg.sm_scale)
+        ph32 = (ph[0].astype(np.float32).astype(np.float64), float(np.float32(ph[1])), float(np.float32(ph[2])))
+        hosts.append(ph32)
+        outs.append(oracle.merge(pg[0], pg[1], pg[2], *ph32))
+    return f, sel, outs, hosts
+
+
+@pytest.mark.parametrize("i", range(24))
+def test_random_shape_with_random_variant(i):
+    """The selection variants in random combination on random shapes: always-kept blocks, maximum over
+    the group's heads, a selection per query head, mean-pooled digests (the last not with the maximum)."""
+    from paper_2603_27138_amd import binding as B
+    cfg = random_config(100 + i)
+    rng = np.random.default_rng([4242, i])
+    variant = dict(n_sink=int(rng.integers(0, 3)), n_tail=int(rng.integers(0, 3)), per_head=int(rng.integers(2)),
+                   digest_kind=int(rng.integers(2)), group_max=0)
+    if not variant["digest_kind"]:
+        variant["group_max"] = int(rng.integers(2))
+    print(f"[random variant] {cfg.name} {cfg.dtype} d{cfg.d} S{cfg.S} B{cfg.B} Hq{cfg.Hq} Hkv{cfg.Hkv} ctx{cfg.ctx} k{cfg.k} {variant}",
+          flush=True)
+    wl = W.generate(cfg)
+    dev = Dev(wl, k_blocks=True)
+    code = B.F32 if cfg.dtype == "f32" else B.BF16
+    p = B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, code, cfg.max_blocks, cfg.k, dev.ctx_len, 0.0, **variant)
+    ws = B.alloc_workspace(p)
+    sums = {}
+    if variant["digest_kind"]:
+        digest = torch.zeros(cfg.B, cfg.Hkv, cfg.max_blocks, cfg.d, dtype=torch.float32, device="cuda")
+        sums = {(b, g): oracle.digest_sum(wl.K[(b, g)], int(cfg.ctx[b]), cfg.S) for (b, g) in wl.K}
+    else:
+        digest = dev.digest
+    B.build_digests(p, dev.k_blocks, digest)
+    rows = cfg.Hq if variant["per_head"] else cfg.Hkv
+    units = {}
+    for b in range(cfg.B):
+        for r in range(rows):
+            heads = [r] if variant["per_head"] else list(range(r * cfg.G, (r + 1) * cfg.G))
+            units[(b, r)] = (heads, _unit_oracle(wl, b, heads, heads[0] // cfg.G, sums, variant))
+    ho = np.zeros((cfg.B, cfg.Hq, cfg.d), dtype=np.float32)
+    hm = np.full((cfg.B, cfg.Hq), -np.inf, dtype=np.float32)
+    hl = np.zeros((cfg.B, cfg.Hq), dtype=np.float32)
+    for (b, r), (heads, (_, _, _, hosts)) in units.items():
+        for hq, hp in zip(heads, hosts):
+            ho[b, hq], hm[b, hq], hl[b, hq] = hp
+    host = [torch.from_numpy(a).cuda() for a in (ho, hm, hl)]
+    i32 = dict(dtype=torch.int32, device="cuda")
+    scores = torch.full((cfg.B, rows, cfg.max_blocks), float("nan"), dtype=torch.float32, device="cuda")
+    sel_all, sel_gpu, slot_gpu, sel_host = (torch.full((cfg.B, rows, cfg.k), -7, **i32) for _ in range(4))
+    n_gpu, n_host = torch.full((cfg.B, rows), -7, **i32), torch.full((cfg.B, rows), -7, **i32)
+    B.layer_step(p, dev.q, digest, dev.block_table, dev.k_pool, dev.v_pool, dev.n_slots, *host, scores, sel_all, sel_gpu,
+                 slot_gpu, n_gpu, sel_host, n_host, dev.out, dev.lse, ws)
+    torch.cuda.synchronize()
+    sel = sel_all.cpu().numpy()
+    out = W.storage_to_f32(to_np(dev.out)).astype(np.float64)
+    lse = dev.lse.cpu().numpy()
+    for (b, r), (heads, (f, wsel, outs, _)) in units.items():
+        if not np.array_equal(sel[b, r], wsel):
+            fin = np.sort(f[np.isfinite(f)])[::-1]
+            gaps = np.abs(np.diff(fin)) / np.maximum(np.abs(fin[:-1]), 1e-300)
+            assert len(gaps) and gaps.min() < 1e-6, (cfg, variant, b, r)
+            continue
+        for hq, (want, wlse) in zip(heads, outs):
+            assert np.abs(out[b, hq] - want).max() <= TOL[cfg.dtype], (cfg, variant, b, hq)
+            if np.isneginf(wlse):
+                assert np.isneginf(lse[b, hq])
+            else:
+                assert abs(lse[b, hq] - wlse) <= 2e-3 * max(1.0, abs(wlse)), (cfg, variant, b, hq)
