@@ -151,6 +151,13 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_kernel(
   const int nb = num_blocks_of(D, b);
   const int j_wave = (blockIdx.x * kScoreWaves + wave) * BLK_PER_WAVE;
   const bool active = j_wave < D.max_blocks;  // a wave past the row still helps with the fold
+  if ((int)blockIdx.x * kScoreWaves * BLK_PER_WAVE >= nb) {
+    // the whole workgroup lies beyond the sequence's last block (a ragged batch has many of these):
+    // nothing to read, only the row's tail to mark
+    const int j = (int)blockIdx.x * kScoreWaves * BLK_PER_WAVE + threadIdx.x;
+    if (threadIdx.x < kScoreWaves * BLK_PER_WAVE && j < D.max_blocks) scores[(size_t)pair * D.max_blocks + j] = -INFINITY;
+    return;
+  }
 
   // the group's queries first: thread t takes channel t % DH, negative (t < DH) or positive parts
   const int fc = threadIdx.x % DH;
@@ -297,6 +304,11 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_max_kernel(Dims D, c
   const int nb = num_blocks_of(D, b);
   const int j_wave = (blockIdx.x * kScoreWaves + wave) * BLK_PER_WAVE;
   const bool active = j_wave < D.max_blocks;
+  if ((int)blockIdx.x * kScoreWaves * BLK_PER_WAVE >= nb) {  // as in score_kernel: only the row's tail to mark
+    const int j = (int)blockIdx.x * kScoreWaves * BLK_PER_WAVE + threadIdx.x;
+    if (threadIdx.x < kScoreWaves * BLK_PER_WAVE && j < D.max_blocks) scores[(size_t)pair * D.max_blocks + j] = -INFINITY;
+    return;
+  }
 
   // queries first (see score_kernel for why the order of issue matters)
   constexpr int QPT = (16 * DH + NT - 1) / NT;  // elements per thread
