@@ -71,8 +71,10 @@ static int check_problem(const scout_problem* p, Dims* D) {
   D->group_max = p->group_max;
   D->digest_kind = p->digest_kind;
   D->share = 1;
+  D->share_magic = 0;
   if (p->per_head) {  // every query head is a pair of its own that reads its KV head's digest and table rows
     D->share = D->G;
+    D->share_magic = D->G > 1 ? (uint32_t)(((1ull << 32) + D->G - 1) / D->G) : 0;
     D->Hkv = D->Hq;
     D->G = 1;
   }

@@ -20,6 +20,7 @@ struct Dims {
   int digest_kind;     // 0 = channel-wise min and max in the element type, 1 = binary32 sums of the keys (mean pooling)
   int share;           // consecutive pairs that share one digest / block-table row: 1, or with a selection
                        // per query head the real group size (then Hkv = Hq and G = 1 here)
+  uint32_t share_magic;  // ceil(2^32 / share) for share > 1: pair / share without a division
   const int32_t* ctx_len;
 };
 
@@ -64,6 +65,12 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float x) {
   if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
   u += 0x7fffu + ((u >> 16) & 1u);
   return u >> 16;
+}
+
+// Index of the digest / block-table row a pair reads: pair / share.  Exact for pair < 2^16 and
+// share <= 16 (the multiplication's error stays below 1 / share).
+__device__ __forceinline__ int kv_row(const Dims& D, int pair) {
+  return D.share == 1 ? pair : (int)__umulhi((uint32_t)pair, D.share_magic);
 }
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }

@@ -151,13 +151,6 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_kernel(
   const int nb = num_blocks_of(D, b);
   const int j_wave = (blockIdx.x * kScoreWaves + wave) * BLK_PER_WAVE;
   const bool active = j_wave < D.max_blocks;  // a wave past the row still helps with the fold
-  if ((int)blockIdx.x * kScoreWaves * BLK_PER_WAVE >= nb) {
-    // the whole workgroup lies beyond the sequence's last block (a ragged batch has many of these):
-    // nothing to read, only the row's tail to mark
-    const int j = (int)blockIdx.x * kScoreWaves * BLK_PER_WAVE + threadIdx.x;
-    if (threadIdx.x < kScoreWaves * BLK_PER_WAVE && j < D.max_blocks) scores[(size_t)pair * D.max_blocks + j] = -INFINITY;
-    return;
-  }
 
   // the group's queries first: thread t takes channel t % DH, negative (t < DH) or positive parts
   const int fc = threadIdx.x % DH;
@@ -173,7 +166,15 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_kernel(
       qv[h] = *reinterpret_cast<const float*>(qbase + (size_t)hs * DH * ESZ);
   }
 
-  const char* dpair = static_cast<const char*>(digest) + (size_t)(pair / D.share) * D.max_blocks * EB;
+  // (the query loads above do not wait for the sequence's length; this is the first thing that does)
+  if ((int)blockIdx.x * kScoreWaves * BLK_PER_WAVE >= nb) {
+    // the whole workgroup lies beyond the sequence's last block (a ragged batch has many of these):
+    // nothing to read, only the row's tail to mark
+    const int j = (int)blockIdx.x * kScoreWaves * BLK_PER_WAVE + threadIdx.x;
+    if (threadIdx.x < kScoreWaves * BLK_PER_WAVE && j < D.max_blocks) scores[(size_t)pair * D.max_blocks + j] = -INFINITY;
+    return;
+  }
+  const char* dpair = static_cast<const char*>(digest) + (size_t)kv_row(D, pair) * D.max_blocks * EB;
   const __amdgpu_buffer_rsrc_t rs =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(dpair), 0, active ? nb * EB : 0, 0x00020000);
   const int voff0 = (j_wave + (lane >> 3)) * EB + (lane & 7) * 16;
@@ -319,7 +320,7 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_max_kernel(Dims D, c
     const int e = threadIdx.x + i * NT;
     qreg[i] = load1<DT>(q, ((size_t)b * D.Hq + g * D.G) * DH + (e < n_q ? e : n_q - 1));
   }
-  const char* dpair = static_cast<const char*>(digest) + (size_t)(pair / D.share) * D.max_blocks * EB;
+  const char* dpair = static_cast<const char*>(digest) + (size_t)kv_row(D, pair) * D.max_blocks * EB;
   const __amdgpu_buffer_rsrc_t rs =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(dpair), 0, active ? nb * EB : 0, 0x00020000);
   const int voff0 = (j_wave + (lane >> 3)) * EB + (lane & 7) * 16;

@@ -279,7 +279,7 @@ __device__ __forceinline__ void load_keys(const Dims& D, const float* __restrict
                                           const int32_t* __restrict__ table, int pair, int nb, int wave,
                                           int lane, uint32_t (&key)[KPL], int (&slot)[KPL]) {
   const size_t row = (size_t)pair * D.max_blocks;
-  const size_t trow = (size_t)(pair / D.share) * D.max_blocks;  // the table belongs to the KV head
+  const size_t trow = (size_t)kv_row(D, pair) * D.max_blocks;  // the table belongs to the KV head
   float sc[KPL];
 #pragma unroll
   for (int r = 0; r < KPL; ++r) {
