@@ -70,6 +70,7 @@ static int check_problem(const scout_problem* p, Dims* D) {
   D->n_tail = p->n_tail;
   D->group_max = p->group_max;
   D->digest_kind = p->digest_kind;
+  D->s_shift = p->S == 16 ? 4 : (p->S == 32 ? 5 : 6);
   D->share = 1;
   D->share_magic = 0;
   if (p->per_head) {  // every query head is a pair of its own that reads its KV head's digest and table rows
@@ -160,10 +161,12 @@ static int plan_attn(const Dims& D, int dtype, AttnPlan* out) {
   return SCOUT_OK;
 }
 
-static Partials carve(void* ws, const WsLayout& L, int nsplit) {
+static Partials carve(void* ws, const WsLayout& L, const AttnPlan& A) {
   char* base = static_cast<char*>(ws);
+  const uint32_t n_waves = (uint32_t)A.nsplit * (uint32_t)A.waves;  // waves that share a pair (MFMA family)
+  const uint32_t magic = n_waves > 1 ? (uint32_t)(((1ull << 32) + n_waves - 1) / n_waves) : 0;
   return Partials{reinterpret_cast<float*>(base + L.part_o), reinterpret_cast<float*>(base + L.part_m),
-                  reinterpret_cast<float*>(base + L.part_l), nsplit};
+                  reinterpret_cast<float*>(base + L.part_l), A.nsplit, magic};
 }
 
 // Attention over the listed blocks, then what E asks for.  One launch when a single MFMA workgroup
@@ -172,7 +175,7 @@ static int run_attn(const Dims& D, int dtype, const AttnPlan& A, const void* q, 
                     const void* v_pool, long long n_slots, const int32_t* sel_gpu,
                     const int32_t* slot_gpu, const int32_t* n_gpu, void* ws, const WsLayout& L,
                     Epilogue E, hipStream_t st) {
-  Partials P = carve(ws, L, A.nsplit);
+  Partials P = carve(ws, L, A);
   if (A.family == 2 && A.nsplit == 1)  // one workgroup per pair finishes the pair itself
     return launch_attn(D, dtype, 2, A.waves, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, P, E, st);
   Epilogue part{};
@@ -383,7 +386,7 @@ int scout_attn_partials(const scout_problem* p, const void* q, const void* k_poo
   Epilogue part{};
   part.mode = 0;
   return launch_attn(D, p->dtype, A.family, A.waves, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu,
-                     carve(ws, L, A.nsplit), part, static_cast<hipStream_t>(stream));
+                     carve(ws, L, A), part, static_cast<hipStream_t>(stream));
 }
 
 int scout_attn_finish(const scout_problem* p, const float* host_o, const float* host_m, const float* host_l,
@@ -408,7 +411,7 @@ int scout_attn_finish(const scout_problem* p, const float* host_o, const float* 
   E.out = out;
   E.lse = lse;
   E.dtype_out = p->dtype;
-  return launch_combine(D, carve(ws, L, A.nsplit), E, static_cast<hipStream_t>(stream));
+  return launch_combine(D, carve(ws, L, A), E, static_cast<hipStream_t>(stream));
 }
 
 int sparse_decode_attn(const scout_problem* p, const void* q, const void* k_pool, const void* v_pool,
@@ -530,7 +533,7 @@ int scout_layer_step(const scout_problem* p, const void* q, const void* digest,
   E.dtype_out = p->dtype;
   if (g_fuse_select && A.family == 2 && A.waves == 8 && select_attend_supported(D, p->dtype)) {
     // selection rides in the head of the attention kernel: two launches for the whole step
-    Partials P = carve(ws, L, A.nsplit);
+    Partials P = carve(ws, L, A);
     if (A.nsplit == 1)
       return launch_select_attend(D, q, scores, block_table, k_pool, v_pool, n_slots, sel_all, sel_gpu,
                                   slot_gpu, n_gpu, sel_host, n_host, P, E, st);

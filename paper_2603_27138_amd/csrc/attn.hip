@@ -141,10 +141,10 @@ struct Entry {
 
 // sel / slot_list point at the pair's list (global memory or LDS); u is wave-uniform.
 __device__ __forceinline__ Entry read_entry(const int32_t* sel, const int32_t* slot_list, int u, int u_end,
-                                            int upb, int S, int ctx, long long n_slots) {
+                                            int ush, int S, int ctx, long long n_slots) {
   Entry e{0, 0};
   if (u < u_end) {
-    const int i = u / upb, sub = u - i * upb;
+    const int i = u >> ush, sub = u - (i << ush);  // ush = log2(units per block)
     const int j = __builtin_amdgcn_readfirstlane(sel[i]);
     const long long slot = __builtin_amdgcn_readfirstlane(slot_list[i]);
     int valid = ctx - j * S - sub * kUnitTokens;
@@ -250,14 +250,14 @@ __device__ __forceinline__ void load_q(u32x4 (&qreg)[4], const Dims& D, const ui
 // The attention of one workgroup: its share (split) of the pair's list, folded over the waves
 // through LDS, then the epilogue.  sel / slot_list: the pair's list in global memory or LDS.
 template <int WAVES>
-__device__ __forceinline__ void attend_pair(const Dims& D, int pair, int split, const u32x4 (&qreg)[4],
+__device__ __forceinline__ void attend_pair(const Dims& D, int b, int g, int split, const u32x4 (&qreg)[4],
                                             const uint16_t* __restrict__ k_pool,
                                             const uint16_t* __restrict__ v_pool, long long n_slots,
                                             const int32_t* sel, const int32_t* slot_list, int n,
                                             const Partials& P, const Epilogue& E, float* smem) {
   // per wave: [G][132] floats of o (padded rows), then m[16], l[16]
   constexpr int ROW = kMfmaD + 4;
-  const int b = pair / D.Hkv, g = pair % D.Hkv;
+  const int pair = b * D.Hkv + g;
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int ln = lane & 15, kg = lane >> 4;
@@ -268,14 +268,17 @@ __device__ __forceinline__ void attend_pair(const Dims& D, int pair, int split, 
   if (n_slots <= 0) n = 0;
   const int ctx = D.ctx_len[b];
   const float scale2 = D.sm_scale * kLog2e;
-  const int S = D.S, upb = S / kUnitTokens;
+  const int S = D.S, ush = D.s_shift - 4;  // a block is 2^ush units of 16 tokens
 
-  // this wave's contiguous share of the pair's units
-  const int n_units = n * upb, n_waves = P.nsplit * WAVES, v = split * WAVES + wave;
-  // at most 1024 waves share at most 4096 units: the products fit 32 bits (a 64-bit division is a
-  // few hundred instructions here)
-  const int u0 = (int)((uint32_t)(v * n_units) / (uint32_t)n_waves);
-  const int u1 = (int)((uint32_t)((v + 1) * n_units) / (uint32_t)n_waves);
+  // this wave's contiguous share of the pair's units: the first (units mod waves) waves take one unit
+  // more than the others.  The quotient comes from a multiplication with a reciprocal made on the host
+  // (at most 4096 units over at most 1024 waves: exact); an integer division here delays the first
+  // tile request by a noticeable fraction of a microsecond.
+  const int n_units = n << ush, n_waves = P.nsplit * WAVES, v = split * WAVES + wave;
+  const int per = P.waves_magic ? (int)__umulhi((uint32_t)n_units, P.waves_magic) : n_units;
+  const int extra = n_units - per * n_waves;
+  const int u0 = v * per + (v < extra ? v : extra);
+  const int u1 = u0 + per + (v < extra ? 1 : 0);
 
   WaveState W;
 #pragma unroll
@@ -291,13 +294,13 @@ __device__ __forceinline__ void attend_pair(const Dims& D, int pair, int split, 
   Entry ent[DEPTH];
 #pragma unroll
   for (int d = 0; d < DEPTH; ++d) {
-    ent[d] = read_entry(sel, slot_list, u0 + d, u1, upb, S, ctx, n_slots);
+    ent[d] = read_entry(sel, slot_list, u0 + d, u1, ush, S, ctx, n_slots);
     issue_unit(buf[d], k_pool, v_pool, ent[d], ln, kg);
   }
   for (int u = u0; u < u1; u += DEPTH) {
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) {
-      const Entry nx = read_entry(sel, slot_list, u + d + DEPTH, u1, upb, S, ctx, n_slots);
+      const Entry nx = read_entry(sel, slot_list, u + d + DEPTH, u1, ush, S, ctx, n_slots);
       consume_unit(W, buf[d], qreg, ent[d].valid, scale2, kg);
       ent[d] = nx;
       issue_unit(buf[d], k_pool, v_pool, nx, ln, kg);
@@ -401,7 +404,7 @@ __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
     const uint16_t* __restrict__ v_pool, long long n_slots, const int32_t* __restrict__ sel_gpu,
     const int32_t* __restrict__ slot_gpu, const int32_t* __restrict__ n_gpu, Partials P, Epilogue E) {
   extern __shared__ float smem[];
-  const int pair = blockIdx.y, split = blockIdx.x;
+  const int b = blockIdx.z, g = blockIdx.y, pair = grid_pair(), split = blockIdx.x;
   const int lane = lane_id();
   // The pair's whole list is copied to LDS by all threads at once, in the same round trip that
   // brings the count and the queries: which entries a wave needs depends on the count, and a
@@ -415,9 +418,9 @@ __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
     l_slot[t] = slot_gpu[list0 + t];
   }
   u32x4 qreg[4];
-  load_q(qreg, D, q, pair / D.Hkv, pair % D.Hkv, lane & 15, lane >> 4);
+  load_q(qreg, D, q, b, g, lane & 15, lane >> 4);
   __syncthreads();
-  attend_pair<WAVES>(D, pair, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, n, P, E, smem);
+  attend_pair<WAVES>(D, b, g, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, n, P, E, smem);
 }
 
 // Selection and attention of a pair in one launch (the non-pipelined description of Sec. 3.2:
@@ -436,8 +439,7 @@ __global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
     int32_t* __restrict__ sel_host, int32_t* __restrict__ n_host, Partials P, Epilogue E) {
   constexpr int WAVES = 8;
   extern __shared__ float smem[];
-  const int pair = blockIdx.y, split = blockIdx.x;
-  const int b = pair / D.Hkv;
+  const int b = blockIdx.z, g = blockIdx.y, pair = grid_pair(), split = blockIdx.x;
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   // LDS after the fold area: resident list (block, slot), the selector's exchange words, the count
@@ -448,7 +450,7 @@ __global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
   int* l_n = l_x + selector_lds_ints<WAVES>();
 
   u32x4 qreg[4];
-  load_q(qreg, D, q, b, pair % D.Hkv, lane & 15, lane >> 4);
+  load_q(qreg, D, q, b, g, lane & 15, lane >> 4);
 
   if (SEL_WAVES == WAVES || wave == 0) {  // wave-uniform
     const int sw = SEL_WAVES == WAVES ? wave : 0;
@@ -504,7 +506,7 @@ __global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
     if (tid == 0) l_n[0] = ng;
   }
   __syncthreads();
-  attend_pair<WAVES>(D, pair, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, l_n[0], P, E, smem);
+  attend_pair<WAVES>(D, b, g, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, l_n[0], P, E, smem);
 }
 
 // ---------------------------------------------------------------- VALU family
@@ -629,9 +631,9 @@ __global__ __launch_bounds__(kWave) void attn_valu_kernel(
 // partial or go straight on to the merge with the host's partial (Epilogue modes
 // 1 and 2).  One workgroup of d threads per head.
 __global__ void combine_kernel(Dims D, Partials P, Epilogue E) {
-  const int bh = blockIdx.x;  // b * Hq + hq
-  const int b = bh / D.Hq, hq = bh % D.Hq;
-  const int pair = b * D.Hkv + hq / D.G, h = hq % D.G;
+  // grid (G, Hkv, B): head within the group, KV head, sequence
+  const int h = blockIdx.x;
+  const int pair = grid_pair(), bh = pair * D.G + h;
   const int c = threadIdx.x;
   const size_t p0 = (size_t)pair * P.nsplit;
   const HostPart hp = load_host(D, E, bh, c);
@@ -717,7 +719,7 @@ int launch_attn(const Dims& D, int dtype, int family, int waves, const void* q, 
   const int pairs = D.B * D.Hkv;
   if (pairs == 0) return SCOUT_OK;
   if (family == 2) {
-    dim3 grid(P.nsplit, pairs), block(waves * kWave);
+    dim3 grid(P.nsplit, D.Hkv, D.B), block(waves * kWave);
     const size_t lds = mfma_smem_bytes(D, waves) + 2 * (size_t)D.k * sizeof(int);
     const uint16_t* q16 = static_cast<const uint16_t*>(q);
     const uint16_t* k16 = static_cast<const uint16_t*>(k_pool);
@@ -762,7 +764,7 @@ int launch_select_attend(const Dims& D, const void* q, const float* scores, cons
                          int32_t* n_host, Partials P, Epilogue E, hipStream_t st) {
   const int pairs = D.B * D.Hkv;
   if (pairs == 0) return SCOUT_OK;
-  dim3 grid(P.nsplit, pairs), block(8 * kWave);
+  dim3 grid(P.nsplit, D.Hkv, D.B), block(8 * kWave);
   const size_t lds = mfma_smem_bytes(D, 8) + (2 * (size_t)((D.k + 3) & ~3) + selector_lds_ints<8>() + 4) * sizeof(int);
   const uint16_t* q16 = static_cast<const uint16_t*>(q);
   const uint16_t* k16 = static_cast<const uint16_t*>(k_pool);
@@ -788,8 +790,8 @@ int launch_select_attend(const Dims& D, const void* q, const float* scores, cons
 }
 
 int launch_combine(const Dims& D, Partials P, Epilogue E, hipStream_t st) {
-  dim3 grid(D.B * D.Hq), block(D.d);
-  if (grid.x == 0) return SCOUT_OK;
+  dim3 grid(D.G, D.Hkv, D.B), block(D.d);
+  if (grid.z == 0) return SCOUT_OK;
   hipLaunchKernelGGL(combine_kernel, grid, block, 0, st, D, P, E);
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
 }

@@ -21,6 +21,7 @@ struct Dims {
   int share;           // consecutive pairs that share one digest / block-table row: 1, or with a selection
                        // per query head the real group size (then Hkv = Hq and G = 1 here)
   uint32_t share_magic;  // ceil(2^32 / share) for share > 1: pair / share without a division
+  int s_shift;         // log2(S): integer divisions are slow enough here to show in the launch heads
   const int32_t* ctx_len;
 };
 
@@ -33,6 +34,7 @@ struct Partials {
   float* m;
   float* l;
   int nsplit;
+  uint32_t waves_magic;  // MFMA family: ceil(2^32 / (nsplit * waves per workgroup)), 0 if that is 1
 };
 
 // What happens to a finished (sequence, query head) result.
@@ -73,12 +75,16 @@ __device__ __forceinline__ int kv_row(const Dims& D, int pair) {
   return D.share == 1 ? pair : (int)__umulhi((uint32_t)pair, D.share_magic);
 }
 
+// Kernels that work pair by pair are launched with the KV head in grid dimension y and the sequence
+// in z, so that neither has to be divided out of a pair index.
+__device__ __forceinline__ int grid_pair() { return blockIdx.z * gridDim.y + blockIdx.y; }
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
 __device__ __forceinline__ int num_blocks_of(const Dims& D, int b) {
   int ctx = D.ctx_len[b];
   if (ctx < 0) ctx = 0;
-  int nb = (ctx + D.S - 1) / D.S;
+  int nb = (ctx + D.S - 1) >> D.s_shift;
   return nb < D.max_blocks ? nb : D.max_blocks;
 }
 

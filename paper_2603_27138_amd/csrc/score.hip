@@ -19,8 +19,8 @@ namespace scout {
 template <int DT>
 __global__ __launch_bounds__(256) void digest_kernel(Dims D, const void* __restrict__ k_blocks,
                                                      void* __restrict__ digest) {
-  const int pair = blockIdx.y;
-  const int b = pair / D.Hkv;
+  const int pair = grid_pair();  // grid (x, Hkv, B)
+  const int b = blockIdx.z;
   const int cpt = D.d / 8;  // 8-channel chunks per token row
   const int j = blockIdx.x * (blockDim.x / cpt) + threadIdx.x / cpt;
   const int c0 = (threadIdx.x % cpt) * 8;
@@ -75,8 +75,8 @@ __global__ __launch_bounds__(256) void digest_kernel(Dims D, const void* __restr
 template <int DT>
 __global__ __launch_bounds__(256) void digest_sum_kernel(Dims D, const void* __restrict__ k_blocks,
                                                          float* __restrict__ digest) {
-  const int pair = blockIdx.y;
-  const int b = pair / D.Hkv;
+  const int pair = grid_pair();  // grid (x, Hkv, B)
+  const int b = blockIdx.z;
   const int cpt = D.d / 8;
   const int j = blockIdx.x * (blockDim.x / cpt) + threadIdx.x / cpt;
   const int c0 = (threadIdx.x % cpt) * 8;
@@ -144,8 +144,8 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_kernel(
 
   __shared__ __align__(16) double coef_lds[2][DH];  // [0]: N_c (goes with the min row), [1]: P_c
 
-  const int pair = blockIdx.y;
-  const int b = pair / D.Hkv, g = pair % D.Hkv;
+  const int pair = grid_pair();  // grid (x, Hkv, B)
+  const int b = blockIdx.z, g = blockIdx.y;
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int nb = num_blocks_of(D, b);
@@ -298,8 +298,8 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_max_kernel(Dims D, c
 
   __shared__ __align__(16) float q_lds[16 * DH];  // the group's queries as binary32, [head][channel]
 
-  const int pair = blockIdx.y;
-  const int b = pair / D.Hkv, g = pair % D.Hkv;
+  const int pair = grid_pair();  // grid (x, Hkv, B)
+  const int b = blockIdx.z, g = blockIdx.y;
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int nb = num_blocks_of(D, b);
@@ -386,8 +386,8 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_max_kernel(Dims D, c
 int launch_digest(const Dims& D, int dtype, const void* k_blocks, void* digest, hipStream_t st) {
   const int cpt = D.d / 8;
   const int blocks_per_wg = 256 / cpt;
-  dim3 grid((D.max_blocks + blocks_per_wg - 1) / blocks_per_wg, D.B * D.Hkv);
-  if (grid.x == 0 || grid.y == 0) return SCOUT_OK;
+  dim3 grid((D.max_blocks + blocks_per_wg - 1) / blocks_per_wg, D.Hkv, D.B);
+  if (grid.x == 0 || grid.y == 0 || grid.z == 0) return SCOUT_OK;
   if (D.digest_kind == 1) {
     float* sums = static_cast<float*>(digest);
     if (dtype == SCOUT_BF16)
@@ -406,9 +406,9 @@ int launch_digest(const Dims& D, int dtype, const void* k_blocks, void* digest, 
 int launch_score_max(const Dims& D, int dtype, const void* q, const void* digest, float* scores, hipStream_t st) {
   const int lines = 2 * D.d * (dtype == SCOUT_BF16 ? 2 : 4) / 128;
   const int blocks_per_wg = kScoreBatch / lines * 8 * kScoreWaves;
-  dim3 grid((D.max_blocks + blocks_per_wg - 1) / blocks_per_wg, D.B * D.Hkv);
+  dim3 grid((D.max_blocks + blocks_per_wg - 1) / blocks_per_wg, D.Hkv, D.B);
   dim3 block(kScoreWaves * kWave);
-  if (grid.x == 0 || grid.y == 0) return SCOUT_OK;
+  if (grid.x == 0 || grid.y == 0 || grid.z == 0) return SCOUT_OK;
   if (dtype == SCOUT_BF16 && D.d == 128)
     hipLaunchKernelGGL((score_max_kernel<SCOUT_BF16, 128>), grid, block, 0, st, D, q, digest, scores);
   else if (dtype == SCOUT_BF16 && D.d == 64)
@@ -428,9 +428,9 @@ static int launch_score_sum(const Dims& D, int dtype, const void* q, const void*
   const int entry_bytes = MEAN ? D.d * 4 : 2 * D.d * (dtype == SCOUT_BF16 ? 2 : 4);
   const int lines = entry_bytes / 128;  // 128-byte lines per digest entry
   const int blocks_per_wg = kScoreBatch / lines * 8 * kScoreBatches * kScoreWaves;
-  dim3 grid((D.max_blocks + blocks_per_wg - 1) / blocks_per_wg, D.B * D.Hkv);
+  dim3 grid((D.max_blocks + blocks_per_wg - 1) / blocks_per_wg, D.Hkv, D.B);
   dim3 block(kScoreWaves * kWave);
-  if (grid.x == 0 || grid.y == 0) return SCOUT_OK;
+  if (grid.x == 0 || grid.y == 0 || grid.z == 0) return SCOUT_OK;
   if (dtype == SCOUT_BF16 && D.d == 128)
     hipLaunchKernelGGL((score_kernel<SCOUT_BF16, 128, MEAN>), grid, block, 0, st, D, q, digest, scores);
   else if (dtype == SCOUT_BF16 && D.d == 64)

@@ -11,7 +11,7 @@ __global__ __launch_bounds__(WAVES* kWave) void topk_kernel(
     int32_t* __restrict__ sel_all, int32_t* __restrict__ sel_gpu, int32_t* __restrict__ slot_gpu,
     int32_t* __restrict__ n_gpu, int32_t* __restrict__ sel_host, int32_t* __restrict__ n_host) {
   __shared__ __attribute__((aligned(16))) int lds[selector_lds_ints<WAVES>()];
-  const int pair = blockIdx.x, b = pair / D.Hkv;
+  const int b = blockIdx.z, pair = grid_pair();  // grid (1, Hkv, B)
   const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int nb = num_blocks_of(D, b);
   const int k_eff = D.k < nb ? D.k : nb;
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(WAVES* kWave) void recall_kernel(
     int32_t* __restrict__ evict_blk, int32_t* __restrict__ n_recall) {
   __shared__ __attribute__((aligned(16))) int lds[selector_lds_ints<WAVES>()];
   __shared__ int freed[kMaxK];  // slots of the evicted blocks, in ascending block order
-  const int pair = blockIdx.x, b = pair / D.Hkv;
+  const int b = blockIdx.z, pair = grid_pair();  // grid (1, Hkv, B)
   const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int nb = num_blocks_of(D, b);
   const int k_eff = D.k < nb ? D.k : nb;
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(WAVES* kWave) void recall_kernel(
 
 #define SCOUT_TOPK_DISPATCH(KERNEL, ...)                                                     \
   do {                                                                                       \
-    dim3 grid(D.B* D.Hkv);                                                                   \
+    dim3 grid(1, D.Hkv, D.B);                                                                   \
     if (grid.x == 0) return SCOUT_OK;                                                        \
     if (D.max_blocks <= 256)                                                                 \
       hipLaunchKernelGGL((KERNEL<1, 4>), grid, dim3(kWave), 0, st, __VA_ARGS__);             \
