@@ -23,7 +23,7 @@ __global__ __launch_bounds__(1024) void append_kernel(Dims D, int32_t* ctx_len, 
   const int t = ctx_len[b];
   const bool room = t >= 0 && t < D.max_blocks * D.S;  // a full sequence is left as it is
   if (room) {
-    const int j = t / D.S, r = t % D.S;
+    const int j = t >> D.s_shift, r = t & (D.S - 1);  // S and d are powers of two
     const E* kn = static_cast<const E*>(k_new);
     const E* vn = static_cast<const E*>(v_new);
     E* dg = static_cast<E*>(digest);
@@ -31,8 +31,9 @@ __global__ __launch_bounds__(1024) void append_kernel(Dims D, int32_t* ctx_len, 
     E* vp = static_cast<E*>(v_pool);
     E* hk = static_cast<E*>(host_k);  // the host's copy of every block (pinned memory), or null
     E* hv = static_cast<E*>(host_v);
+    const int d_shift = D.d == 64 ? 6 : 7;
     for (int e = threadIdx.x; e < D.Hkv * D.d; e += blockDim.x) {
-      const int g = e / D.d, c = e % D.d;
+      const int g = e >> d_shift, c = e & (D.d - 1);
       const size_t pair = (size_t)b * D.Hkv + g;
       int32_t* entry = block_table + pair * D.max_blocks + j;
       // a block's first token opens it with the slot the caller chose; later tokens follow the table
