@@ -253,7 +253,7 @@ template <int WAVES>
 __device__ __forceinline__ void attend_pair(const Dims& D, int b, int g, int split, const u32x4 (&qreg)[4],
                                             const uint16_t* __restrict__ k_pool,
                                             const uint16_t* __restrict__ v_pool, long long n_slots,
-                                            const int32_t* sel, const int32_t* slot_list, int n,
+                                            const int32_t* sel, const int32_t* slot_list, int n, int ctx,
                                             const Partials& P, const Epilogue& E, float* smem) {
   // per wave: [G][132] floats of o (padded rows), then m[16], l[16]
   constexpr int ROW = kMfmaD + 4;
@@ -266,7 +266,8 @@ __device__ __forceinline__ void attend_pair(const Dims& D, int b, int g, int spl
 
   n = n < 0 ? 0 : (n > D.k ? D.k : n);
   if (n_slots <= 0) n = 0;
-  const int ctx = D.ctx_len[b];
+  // ctx (the sequence's length) is handed in: read here, after the caller's barrier and its stores, it
+  // would be a fresh trip to memory in front of the first tile request
   const float scale2 = D.sm_scale * kLog2e;
   const int S = D.S, ush = D.s_shift - 4;  // a block is 2^ush units of 16 tokens
 
@@ -413,6 +414,7 @@ __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
   int* l_slot = l_sel + D.k;
   const size_t list0 = (size_t)pair * D.k;
   const int n = n_gpu[pair];
+  const int ctx = D.ctx_len[b];
   for (int t = threadIdx.x; t < D.k; t += WAVES * kWave) {
     l_sel[t] = sel_gpu[list0 + t];
     l_slot[t] = slot_gpu[list0 + t];
@@ -420,7 +422,7 @@ __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
   u32x4 qreg[4];
   load_q(qreg, D, q, b, g, lane & 15, lane >> 4);
   __syncthreads();
-  attend_pair<WAVES>(D, b, g, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, n, P, E, smem);
+  attend_pair<WAVES>(D, b, g, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, n, ctx, P, E, smem);
 }
 
 // Selection and attention of a pair in one launch (the non-pipelined description of Sec. 3.2:
@@ -451,10 +453,12 @@ __global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
 
   u32x4 qreg[4];
   load_q(qreg, D, q, b, g, lane & 15, lane >> 4);
+  const int ctx = D.ctx_len[b];  // once, here: the attention below must not wait for it again
 
   if (SEL_WAVES == WAVES || wave == 0) {  // wave-uniform
     const int sw = SEL_WAVES == WAVES ? wave : 0;
-    const int nb = num_blocks_of(D, b);
+    int nb = (ctx < 0 ? 0 : ctx + D.S - 1) >> D.s_shift;
+    nb = nb < D.max_blocks ? nb : D.max_blocks;
     const int k_eff = D.k < nb ? D.k : nb;
     uint32_t key[KPL];
     int slot[KPL];
@@ -506,7 +510,7 @@ __global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
     if (tid == 0) l_n[0] = ng;
   }
   __syncthreads();
-  attend_pair<WAVES>(D, b, g, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, l_n[0], P, E, smem);
+  attend_pair<WAVES>(D, b, g, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, l_n[0], ctx, P, E, smem);
 }
 
 // ---------------------------------------------------------------- VALU family
