@@ -176,6 +176,12 @@ struct Selector {
       vo |= key[r];
       va &= key[r] ? key[r] : 0xffffffffu;
     }
+    if constexpr (WAVES > 1) {
+      // the first two bin arrays of the histogram rounds below are cleared here, so that the barrier
+      // inside or_and also publishes the zeros
+      int* hist = lds + 4 * WAVES;
+      for (int i = wave * kWave + lane_id(); i < 2 * 256; i += WAVES * kWave) hist[i] = 0;
+    }
     uint32_t all_or, all_and;
     or_and(vo, va, all_or, all_and);
     const uint32_t diff = all_or ^ all_and;
@@ -201,8 +207,6 @@ struct Selector {
       // Three bin arrays rotate: the one for the round after next is cleared while this round's is read.
       int* hist = lds + 4 * WAVES;
       const int tid = wave * kWave + lane_id();
-      for (int i = tid; i < 2 * 256; i += WAVES * kWave) hist[i] = 0;
-      __syncthreads();
       int n_above = 0;  // keys whose settled bits are larger than T's
       int bit = diff ? 31 - __builtin_clz(diff) : -1;
       int round = 0;
