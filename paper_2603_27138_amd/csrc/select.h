@@ -79,6 +79,16 @@ struct Selector {
   int* lds;
   int phase;
   int wave;
+  // Histogram rounds done so far by this Selector, over all its best() calls (several waves only).
+  // Round r counts into bin array r % 3 and, after its barrier, clears array (r + 2) % 3 for round
+  // r + 2.  The numbering runs on from one call to the next, which is what makes back-to-back calls
+  // safe without a barrier between them: a call that ends with round r (its reads of array r % 3 are
+  // followed by no barrier) leaves array (r + 1) % 3 clean (cleared in round r - 1, or by the first
+  // call's opening clear) and array (r + 2) % 3 being cleared; the next call starts with round r + 1,
+  // touches array r % 3 only after the barrier of that round (its clear for round r + 3), and a wave
+  // still reading array r % 3 for the previous call has not yet arrived at the barriers (the common
+  // prefix exchange, then round r + 1) that every wave must pass before that clear.  Wave-uniform.
+  int hround = 0;
 
   // number of keys >= cand over the whole workgroup
   __device__ __forceinline__ int count_ge(const uint32_t (&key)[KPL], uint32_t cand) {
@@ -177,10 +187,13 @@ struct Selector {
       va &= key[r] ? key[r] : 0xffffffffu;
     }
     if constexpr (WAVES > 1) {
-      // the first two bin arrays of the histogram rounds below are cleared here, so that the barrier
-      // inside or_and also publishes the zeros
-      int* hist = lds + 4 * WAVES;
-      for (int i = wave * kWave + lane_id(); i < 2 * 256; i += WAVES * kWave) hist[i] = 0;
+      // Before the first histogram round of this Selector, bin arrays 0 and 1 are cleared here, so that
+      // the barrier inside or_and also publishes the zeros.  Later calls find their arrays clean (see
+      // hround) and must not clear here: a slower wave may still be reading the last round's array.
+      if (hround == 0) {
+        int* hist = lds + 4 * WAVES;
+        for (int i = wave * kWave + lane_id(); i < 2 * 256; i += WAVES * kWave) hist[i] = 0;
+      }
     }
     uint32_t all_or, all_and;
     or_and(vo, va, all_or, all_and);
@@ -209,12 +222,13 @@ struct Selector {
       const int tid = wave * kWave + lane_id();
       int n_above = 0;  // keys whose settled bits are larger than T's
       int bit = diff ? 31 - __builtin_clz(diff) : -1;
-      int round = 0;
       while (bit >= 0) {
         const int nbits = bit >= 7 ? 8 : bit + 1;
         const int shift = bit - nbits + 1;
-        int* h = hist + (round % 3) * 256;
-        int* hz = hist + ((round + 2) % 3) * 256;
+        const int hslot = hround % 3;
+        int* h = hist + hslot * 256;
+        int* hz = hist + (hslot == 0 ? 2 : hslot - 1) * 256;  // (hround + 2) % 3
+        ++hround;  // counted whether or not this round ends the search
         const uint32_t hi_mask = bit == 31 ? 0u : ~((2u << bit) - 1u);  // bits above this round's digit
 #pragma unroll
         for (int r = 0; r < KPL; ++r) {
@@ -248,7 +262,6 @@ struct Selector {
           break;
         }
         bit -= nbits;
-        ++round;
       }
     }
     uint32_t ge = 0;
