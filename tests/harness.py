@@ -56,7 +56,7 @@ def run_pair(wl: W.Workload, b: int, g: int, q=None, table=None, attention: bool
     return res
 
 
-def run_head(wl: W.Workload, b: int, hq: int, q=None, table=None) -> OraclePair:
+def run_head(wl: W.Workload, b: int, hq: int, q=None, table=None, attention: bool = True) -> OraclePair:
     """Selection per query head (a variant of Alg. 1's TopK argument: the block importance of one
     head alone decides that head's blocks): the head is a group of one on its KV head's cache."""
     cfg = wl.cfg
@@ -71,6 +71,8 @@ def run_head(wl: W.Workload, b: int, hq: int, q=None, table=None) -> OraclePair:
     sel = oracle.select(s32, cfg.k)
     sg, ng, sh, nh = oracle.split(sel, table[b, g])
     res = OraclePair(dig, s, s32, sel, sg, ng, sh, nh)
+    if not attention:
+        return res
     pg = oracle.partial_attn(q[b, hq], K, V, sg, ctx, cfg.S, cfg.sm_scale)
     ph = oracle.partial_attn(q[b, hq], K, V, sh, ctx, cfg.S, cfg.sm_scale)
     ph32 = (ph[0].astype(np.float32).astype(np.float64), float(np.float32(ph[1])), float(np.float32(ph[2])))
@@ -92,3 +94,49 @@ def boundary_gap(op: OraclePair, k: int) -> float:
     r = oracle.rank(op.s32)
     a, b = op.s[r[k - 1]], op.s[r[k]]
     return abs(a - b) / max(abs(a), abs(b), 1e-300)
+
+
+def rel_gap(a: float, b: float) -> float:
+    """Relative distance of two scores; infinite when either is not finite (an always-kept block's
+    +inf or a padded -inf is never a near-tie)."""
+    if not (np.isfinite(a) and np.isfinite(b)):
+        return np.inf
+    return abs(a - b) / max(abs(a), abs(b), 1e-300)
+
+
+def selection_gap(s64: np.ndarray, decision: np.ndarray, k: int) -> float:
+    """The one gap that decides a top-k selection: between the last kept and the first dropped block in
+    the ranking of `decision` (the scores the selection saw), measured on the exact scores `s64`."""
+    nb = len(decision)
+    if k >= nb:
+        return np.inf
+    r = oracle.rank(decision)
+    return rel_gap(s64[r[k - 1]], s64[r[k]])
+
+
+def plan_gap(s64: np.ndarray, decision: np.ndarray, k: int, table_row: np.ndarray) -> float:
+    """The smallest of the gaps that decide a recall plan (Sec. 3.4) in the oracle's ranking: k-th vs
+    (k+1)-th block overall; n-th vs (n+1)-th best of the missing blocks (top-k, not resident) when
+    only n of them fit; n-th vs (n+1)-th worst of the spare blocks (resident, not in the top-k) when
+    only n of them go.  A device plan that differs from the oracle's is excused only if this is
+    below the tolerance: no other pair of scores can change the plan."""
+    nb = len(decision)
+    ke = min(k, nb)
+    r = oracle.rank(decision)
+    gaps = [selection_gap(s64, decision, k)]
+    top = np.zeros(nb, dtype=bool)
+    top[r[:ke]] = True
+    res = np.asarray(table_row[:nb]) >= 0
+    missing = [j for j in r if top[j] and not res[j]]          # best first
+    spare = [j for j in r[::-1] if res[j] and not top[j]]      # worst first
+    n = min(len(missing), len(spare))
+    if 0 < n < len(missing):
+        gaps.append(rel_gap(s64[missing[n - 1]], s64[missing[n]]))
+    if 0 < n < len(spare):
+        gaps.append(rel_gap(s64[spare[n - 1]], s64[spare[n]]))
+    return min(gaps)
+
+
+def few(excused: int, total: int) -> bool:
+    """Excused mismatches must stay rare: at most one, or one in a hundred."""
+    return excused <= max(1, total // 100)

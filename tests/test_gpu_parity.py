@@ -44,8 +44,15 @@ def small_configs():
     empty32 = W.shrink(W.tiny(), name="f32-empty-sequence", B=2, Hq=4, Hkv=2, ctx=(0, 40), k=3, p_host=0.5)
     # the largest shape the library takes: 16384 blocks per pair (524288 tokens), a budget of 1024 blocks
     biggest = W.shrink(W.long_context(B=1, ctx=524288), name="bf16-max-sizes", Hq=2, Hkv=1, k=1024, p_host=0.6)
+    # a cache far smaller than the budget, so that a recall can bring back only the best-ranked part of
+    # the missing blocks (Sec. 3.4 with fewer spare resident blocks than missing ones): rows long enough
+    # for the selector with 4 waves (4096 blocks) and with 16 waves (16384 blocks)
+    small4 = W.shrink(W.long_context(B=2, ctx=0), name="bf16-small-cache-4-waves", Hq=2, Hkv=1, ctx=(131072, 40000),
+                      k=128, p_host=0.98)
+    small16 = W.shrink(W.long_context(B=1, ctx=524288), name="bf16-small-cache-16-waves", Hq=2, Hkv=1, k=256,
+                       p_host=0.985)
     return [W.tiny(), c2, c3, c4, c5, ragged, ragged32, d64, s64, s16, g16, g1, allhost, allgpu, kbig, onetok, huge,
-            empty, empty32, biggest]
+            empty, empty32, biggest, small4, small16]
 
 
 _CACHE = {}
@@ -257,10 +264,11 @@ def test_layer_step_end_to_end(cfg):
                 assert (slot_gpu[b, g, op.n_gpu:] == -1).all()
         out = _f64(to_np(dev.out))
         lse = dev.lse.cpu().numpy()
-        worst = 0.0
+        worst, excused = 0.0, 0
         for (b, g), op in res.items():
             if not np.array_equal(sel_all[b, g], op.sel):
                 assert harness.boundary_gap(op, cfg.k) < 1e-6
+                excused += 1
                 continue   # a different (excused) selection has different host partials
             for h in range(cfg.G):
                 hq = g * cfg.G + h
@@ -272,7 +280,8 @@ def test_layer_step_end_to_end(cfg):
                     assert np.isneginf(lse[b, hq]) and (out[b, hq] == 0).all()
                 else:
                     assert abs(lse[b, hq] - wlse) <= LSE_TOL[cfg.dtype] * max(1.0, abs(wlse))
-        print(f"{cfg.name} mode {mode}: layer step max |out - oracle| = {worst:.3e}")
+        assert harness.few(excused, len(res)), (mode, excused)
+        print(f"{cfg.name} mode {mode}: layer step max |out - oracle| = {worst:.3e}, {excused} selections excused")
 
 
 def test_periodic_recall_plan_bit_exact(cfg):
@@ -284,24 +293,31 @@ def test_periodic_recall_plan_bit_exact(cfg):
     dev.recall(to_dev(q1))
     got_t = dev.block_table.cpu().numpy()
     rb, rs, eb, nr = (t.cpu().numpy() for t in (dev.recall_blk, dev.recall_slot, dev.evict_blk, dev.n_recall))
-    moved = 0
+    moved = excused = second_selection = 0
     for (b, g), op in res.items():
-        s = oracle.decision_scores(oracle.score(q1[b, g * cfg.G:(g + 1) * cfg.G], op.dig))
+        s64 = oracle.score(q1[b, g * cfg.G:(g + 1) * cfg.G], op.dig)
+        s = oracle.decision_scores(s64)
         t = table0[b, g].copy()
         wrb, wrs, web, n = oracle.recall_plan(s, cfg.k, t[:len(s)])
         ok = (nr[b, g] == n and np.array_equal(rb[b, g], wrb) and np.array_equal(rs[b, g], wrs)
               and np.array_equal(eb[b, g], web) and np.array_equal(got_t[b, g], t))
         if not ok:
-            # only a sub-1e-6 boundary gap may differ (scores are recomputed on the device)
-            r = oracle.rank(s)
-            ke = min(cfg.k, len(s))
-            gaps = [abs(s[r[i]] - s[r[i + 1]]) / max(abs(s[r[i]]), 1e-300) for i in range(len(s) - 1)]
-            assert min(gaps) < 1e-6, (b, g)
+            # scores are recomputed on the device: only a sub-1e-6 gap at one of the places that decide
+            # the plan may make it differ
+            assert harness.plan_gap(s64, s, cfg.k, table0[b, g]) < 1e-6, (b, g)
+            excused += 1
         moved += n
+        sel = oracle.select(s, cfg.k)
+        second_selection += int(n < int(((sel >= 0) & (table0[b, g][np.maximum(sel, 0)] < 0)).sum()))
         # structural invariants on what the device produced
         tt = got_t[b, g]
         assert sorted(tt[tt >= 0].tolist()) == sorted(table0[b, g][table0[b, g] >= 0].tolist())
+    print(f"{cfg.name}: recall moved {moved} blocks, {second_selection} pairs with a cache smaller than the "
+          f"missing set, {excused} of {len(res)} plans excused")
+    assert harness.few(excused, len(res))
     assert moved > 0 or not _can_move(cfg)
+    if cfg.name.startswith("bf16-small-cache"):
+        assert second_selection == len(res)      # the shapes made for that branch do reach it
     dev.block_table.copy_(torch.from_numpy(table0))
 
 
@@ -320,34 +336,48 @@ def test_always_kept_blocks(cfg, n_sink, n_tail):
     B.select_topk(p2, dev.scores, dev.block_table, dev.sel_all, dev.sel_gpu, dev.slot_gpu, dev.n_gpu, dev.sel_host,
                   dev.n_host, dev.ws)
     got_s, got_sel = dev.scores.cpu().numpy(), dev.sel_all.cpu().numpy()
-    want = {}
+    want, gap = {}, {}
+    excused = score_off = 0
     for (b, g), op in res.items():
         nb = len(op.s32)
         f = oracle.force_blocks(op.s32, n_sink, n_tail)
         want[(b, g)] = oracle.select(f, cfg.k)
         kept = np.isposinf(f)
+        # the gap between the last kept and the first dropped block with the always-kept ones at +inf
+        gap[(b, g)] = harness.selection_gap(np.where(kept, np.inf, op.s), f, cfg.k)
         assert np.array_equal(np.isposinf(got_s[b, g, :nb]), kept), (b, g)
-        assert np.array_equal(got_s[b, g, :nb][~kept].astype(np.float64), op.s32[~kept]) or harness.boundary_gap(op, cfg.k) < 1e-6
-        assert np.array_equal(got_sel[b, g], want[(b, g)]) or harness.boundary_gap(op, cfg.k) < 1e-6, (b, g)
+        # the other scores are score_blocks' own (binary64 sums rounded once: half an ulp, see test_score_blocks)
+        rest = np.abs(got_s[b, g, :nb][~kept].astype(np.float64) - op.s[~kept])
+        assert (rest <= np.spacing(np.abs(op.s32[~kept]).astype(np.float32)).astype(np.float64) * 0.5000001 + 1e-300).all(), (b, g)
+        score_off += int((got_s[b, g, :nb][~kept].astype(np.float64) != op.s32[~kept]).sum())
+        if not np.array_equal(got_sel[b, g], want[(b, g)]):
+            assert gap[(b, g)] < 1e-6, (b, g)
+            excused += 1
         for j in [j for j in range(nb) if kept[j]][:cfg.k]:
             assert j in got_sel[b, g]
+    assert score_off <= 2
     B.layer_step(p2, dev.q, dev.digest, dev.block_table, dev.k_pool, dev.v_pool, dev.n_slots, dev.host_o, dev.host_m,
                  dev.host_l, dev.scores, dev.sel_all, dev.sel_gpu, dev.slot_gpu, dev.n_gpu, dev.sel_host, dev.n_host,
                  dev.out, dev.lse, dev.ws)
     got_sel = dev.sel_all.cpu().numpy()
     for (b, g), op in res.items():
-        assert np.array_equal(got_sel[b, g], want[(b, g)]) or harness.boundary_gap(op, cfg.k) < 1e-6, (b, g)
+        if not np.array_equal(got_sel[b, g], want[(b, g)]):
+            assert gap[(b, g)] < 1e-6, (b, g)
+            excused += 1
+    assert harness.few(excused, 2 * len(res)), excused
 
 
 def test_group_max_aggregation(cfg):
     """group_max = 1: the maximum over the group's heads instead of their sum, in score_blocks alone and
     through the fused layer-step (selection, both partials, merged output)."""
-    if cfg.max_blocks > 4096:
-        pytest.skip("the oracle's attention over the longest pair is run once, in the sum variant")
     wl, _, dev = setup(cfg)
-    res = harness.run_all(wl, agg="max")
+    # above 4096 blocks per pair the oracle's attention (run once, in the sum variant) is left out: what
+    # this variant changes, scores and selection, is compared at every size
+    attention = cfg.max_blocks <= 4096
+    res = harness.run_all(wl, agg="max", attention=attention)
     dev.set_digest_from_oracle(res)
-    dev.set_host_partials_from_oracle(res)
+    if attention:
+        dev.set_host_partials_from_oracle(res)
     code = B.F32 if cfg.dtype == "f32" else B.BF16
     p2 = B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, code, cfg.max_blocks, cfg.k, dev.ctx_len, 0.0, group_max=1)
     B.score_blocks(p2, dev.q, dev.digest, dev.scores, dev.ws)
@@ -361,14 +391,20 @@ def test_group_max_aggregation(cfg):
                  dev.host_l, dev.scores, dev.sel_all, dev.sel_gpu, dev.slot_gpu, dev.n_gpu, dev.sel_host, dev.n_host,
                  dev.out, dev.lse, dev.ws)
     sel = dev.sel_all.cpu().numpy()
+    sg, ng, sh, nh = dev.sel_gpu.cpu().numpy(), dev.n_gpu.cpu().numpy(), dev.sel_host.cpu().numpy(), dev.n_host.cpu().numpy()
     out = _f64(to_np(dev.out))
+    excused = 0
     for (b, g), op in res.items():
         if not np.array_equal(sel[b, g], op.sel):
             assert harness.boundary_gap(op, cfg.k) < 1e-6, (b, g)
+            excused += 1
             continue
-        for h in range(cfg.G):
+        assert ng[b, g] == op.n_gpu and nh[b, g] == op.n_host, (b, g)
+        assert np.array_equal(sg[b, g], op.sel_gpu) and np.array_equal(sh[b, g], op.sel_host), (b, g)
+        for h in range(cfg.G if attention else 0):
             want, _ = op.out[h]
             assert np.abs(out[b, g * cfg.G + h] - want).max() <= TOL[cfg.dtype], (b, g, h)
+    assert harness.few(excused, len(res)), excused
     # restore what the other tests of this config expect
     res0 = _CACHE[cfg.name][1]
     dev.set_host_partials_from_oracle(res0)
@@ -377,11 +413,12 @@ def test_group_max_aggregation(cfg):
 def test_per_head_selection(cfg):
     """per_head = 1: every query head scores, selects and attends on its own (lists per query head, the
     KV head's digest, table and pools shared), step by step and through the fused layer-step."""
-    if cfg.max_blocks > 1024 or cfg.B * cfg.Hq > 200:
-        pytest.skip("the oracle runs every head's attention; the larger shapes add nothing for this variant")
     wl, res0, dev = setup(cfg)
     dev.set_digest_from_oracle(res0)
-    heads = {(b, hq): harness.run_head(wl, b, hq) for b in range(cfg.B) for hq in range(cfg.Hq)}
+    # the oracle's attention of every head is left out above 1024 blocks per pair: what this variant
+    # changes (scores, selections and lists per query head) is compared at every size
+    attention = cfg.max_blocks <= 1024 and cfg.B * cfg.Hq <= 200
+    heads = {(b, hq): harness.run_head(wl, b, hq, attention=attention) for b in range(cfg.B) for hq in range(cfg.Hq)}
     code = B.F32 if cfg.dtype == "f32" else B.BF16
     p2 = B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, code, cfg.max_blocks, cfg.k, dev.ctx_len, 0.0, per_head=1)
     ws = B.alloc_workspace(p2)
@@ -394,8 +431,10 @@ def test_per_head_selection(cfg):
     hm = np.full((cfg.B, cfg.Hq), -np.inf, dtype=np.float32)
     hl = np.zeros((cfg.B, cfg.Hq), dtype=np.float32)
     for (b, hq), op in heads.items():
-        ho[b, hq], hm[b, hq], hl[b, hq] = op.host_part[0]
+        if attention:
+            ho[b, hq], hm[b, hq], hl[b, hq] = op.host_part[0]
     host = [torch.from_numpy(a).cuda() for a in (ho, hm, hl)]
+    n_excused = [0]
 
     def check(tag):
         got_s, sel = scores.cpu().numpy(), sel_all.cpu().numpy()
@@ -408,10 +447,13 @@ def test_per_head_selection(cfg):
                 assert rel.max() <= 2e-7, (tag, b, hq)
             if not np.array_equal(sel[b, hq], op.sel):
                 assert harness.boundary_gap(op, cfg.k) < 1e-6, (tag, b, hq)
+                n_excused[0] += 1
                 continue
             assert ng[b, hq] == op.n_gpu and nh[b, hq] == op.n_host, (tag, b, hq)
             assert np.array_equal(sg[b, hq], op.sel_gpu) and np.array_equal(sh[b, hq], op.sel_host), (tag, b, hq)
-            assert np.abs(out[b, hq] - op.out[0][0]).max() <= TOL[cfg.dtype], (tag, b, hq)
+            if attention:
+                assert np.abs(out[b, hq] - op.out[0][0]).max() <= TOL[cfg.dtype], (tag, b, hq)
+        assert harness.few(n_excused[0], 2 * len(heads)), n_excused
 
     B.score_blocks(p2, dev.q, dev.digest, scores, ws)
     B.select_topk(p2, scores, dev.block_table, sel_all, sel_gpu, slot_gpu, n_gpu, sel_host, n_host, ws)
@@ -572,6 +614,46 @@ def test_recall_staged_route_bit_exact(cfg):
     B.recall_scatter(dev.p, d_staged, -far, d_rb, d_rs, d_nr, k3, v3, dev.n_slots)
     torch.cuda.synchronize()
     assert np.array_equal(_bits(to_np(k3)), _bits(wl.k_pool)) and np.array_equal(_bits(to_np(v3)), _bits(wl.v_pool))
+
+
+@pytest.mark.parametrize("which", ["4-waves", "16-waves"])
+def test_recalls_in_a_row_with_a_cache_smaller_than_the_missing_set(which):
+    """Six recalls with a drifting query on a table that evolves (Sec. 3.4), rows of 4096 and 16384
+    blocks (selector with 4 and 16 waves), a cache that never holds all of the missing blocks: top-k,
+    best of the missing and worst of the spare are three selections in a row in one workgroup.  Every
+    plan and table against the oracle's, excused only below a 1e-6 gap at a place that decides the plan."""
+    cfg = next(c for c in CFGS if c.name == f"bf16-small-cache-{which}")
+    wl, res, dev = setup(cfg)
+    dev.set_digest_from_oracle(res)
+    table = wl.block_table.copy()
+    dev.block_table.copy_(torch.from_numpy(table))
+    excused = total = second = 0
+    for step in range(1, 7):
+        q1 = W.gen_q(cfg, 0, step=step)
+        dev.recall(to_dev(q1))
+        got_t = dev.block_table.cpu().numpy()
+        rb, rs, eb, nr = (t.cpu().numpy() for t in (dev.recall_blk, dev.recall_slot, dev.evict_blk, dev.n_recall))
+        for (b, g), op in res.items():
+            s64 = oracle.score(q1[b, g * cfg.G:(g + 1) * cfg.G], op.dig)
+            s = oracle.decision_scores(s64)
+            before = table[b, g].copy()
+            sel = oracle.select(s, cfg.k)
+            missing = int(((sel >= 0) & (before[np.maximum(sel, 0)] < 0)).sum())
+            t = np.ascontiguousarray(before[:len(s)])
+            wrb, wrs, web, n = oracle.recall_plan(s, cfg.k, t)
+            table[b, g, :len(s)] = t
+            second += int(0 < n < missing)
+            total += 1
+            ok = (nr[b, g] == n and np.array_equal(rb[b, g], wrb) and np.array_equal(rs[b, g], wrs)
+                  and np.array_equal(eb[b, g], web) and np.array_equal(got_t[b, g], table[b, g]))
+            if not ok:
+                assert harness.plan_gap(s64, s, cfg.k, before) < 1e-6, (step, b, g)
+                excused += 1
+                table[b, g] = got_t[b, g]          # go on from what the device did
+        print(f"{cfg.name} recall {step}: moved {int(nr.sum())} blocks", flush=True)
+    print(f"{cfg.name}: {second} of {total} plans ran the selection among the missing blocks, {excused} excused")
+    assert second >= total // 2 and harness.few(excused, total)
+    dev.block_table.copy_(torch.from_numpy(wl.block_table))
 
 
 def test_recall_then_select_leaves_nothing_on_host():

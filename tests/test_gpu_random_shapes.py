@@ -46,9 +46,11 @@ def test_random_shape(i):
     ng, nh = dev.n_gpu.cpu().numpy(), dev.n_host.cpu().numpy()
     out = W.storage_to_f32(to_np(dev.out)).astype(np.float64)
     lse = dev.lse.cpu().numpy()
+    excused = 0
     for (b, g), op in res.items():
         if not np.array_equal(sel[b, g], op.sel):
             assert harness.boundary_gap(op, cfg.k) < 1e-6, (cfg, b, g)
+            excused += 1
             continue
         assert ng[b, g] == op.n_gpu and nh[b, g] == op.n_host, (cfg, b, g)
         for h in range(cfg.G):
@@ -66,15 +68,16 @@ def test_random_shape(i):
     got_t = dev.block_table.cpu().numpy()
     rb, rs, eb, nr = (t.cpu().numpy() for t in (dev.recall_blk, dev.recall_slot, dev.evict_blk, dev.n_recall))
     for (b, g), op in res.items():
-        s = oracle.decision_scores(oracle.score(q1[b, g * cfg.G:(g + 1) * cfg.G], op.dig))
+        s64 = oracle.score(q1[b, g * cfg.G:(g + 1) * cfg.G], op.dig)
+        s = oracle.decision_scores(s64)
         t = table0[b, g].copy()
         wrb, wrs, web, n = oracle.recall_plan(s, cfg.k, t[:len(s)])
         ok = (nr[b, g] == n and np.array_equal(rb[b, g], wrb) and np.array_equal(rs[b, g], wrs)
               and np.array_equal(eb[b, g], web) and np.array_equal(got_t[b, g], t))
-        if not ok:
-            r = oracle.rank(s)
-            gaps = [abs(s[r[j]] - s[r[j + 1]]) / max(abs(s[r[j]]), 1e-300) for j in range(len(s) - 1)]
-            assert gaps and min(gaps) < 1e-6, (cfg, b, g)
+        if not ok:      # only a gap that decides the plan may excuse
+            assert harness.plan_gap(s64, s, cfg.k, table0[b, g]) < 1e-6, (cfg, b, g)
+            excused += 1
+    assert harness.few(excused, 2 * len(res)), excused
 
 
 def _unit_oracle(wl, b, heads, g, sums, variant):
@@ -90,6 +93,7 @@ def _unit_oracle(wl, b, heads, g, sums, variant):
     else:
         s = oracle.score(qu, oracle.digest(K, ctx, cfg.S))
     f = oracle.force_blocks(oracle.decision_scores(s), variant["n_sink"], variant["n_tail"])
+    s = np.where(np.isfinite(f), s, f)      # exact scores, always-kept blocks at +inf like the decision's
     sel = oracle.select(f, cfg.k)
     sg, ng, sh, nh = oracle.split(sel, wl.block_table[b, g])
     outs, hosts = [], []
@@ -99,7 +103,7 @@ def _unit_oracle(wl, b, heads, g, sums, variant):
         ph32 = (ph[0].astype(np.float32).astype(np.float64), float(np.float32(ph[1])), float(np.float32(ph[2])))
         hosts.append(ph32)
         outs.append(oracle.merge(pg[0], pg[1], pg[2], *ph32))
-    return f, sel, outs, hosts
+    return (f, s), sel, outs, hosts
 
 
 @pytest.mark.parametrize("i", range(24))
@@ -150,11 +154,12 @@ def test_random_shape_with_random_variant(i):
     sel = sel_all.cpu().numpy()
     out = W.storage_to_f32(to_np(dev.out)).astype(np.float64)
     lse = dev.lse.cpu().numpy()
-    for (b, r), (heads, (f, wsel, outs, _)) in units.items():
+    excused = 0
+    for (b, r), (heads, ((f, s64), wsel, outs, _)) in units.items():
         if not np.array_equal(sel[b, r], wsel):
-            fin = np.sort(f[np.isfinite(f)])[::-1]
-            gaps = np.abs(np.diff(fin)) / np.maximum(np.abs(fin[:-1]), 1e-300)
-            assert len(gaps) and gaps.min() < 1e-6, (cfg, variant, b, r)
+            # only the gap between the last kept and the first dropped block may excuse
+            assert harness.selection_gap(s64, f, cfg.k) < 1e-6, (cfg, variant, b, r)
+            excused += 1
             continue
         for hq, (want, wlse) in zip(heads, outs):
             assert np.abs(out[b, hq] - want).max() <= TOL[cfg.dtype], (cfg, variant, b, hq)
@@ -162,3 +167,4 @@ def test_random_shape_with_random_variant(i):
                 assert np.isneginf(lse[b, hq])
             else:
                 assert abs(lse[b, hq] - wlse) <= 2e-3 * max(1.0, abs(wlse)), (cfg, variant, b, hq)
+    assert harness.few(excused, len(units)), excused

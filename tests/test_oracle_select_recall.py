@@ -261,3 +261,34 @@ def test_forced_blocks_then_topk_is_the_brute_force_rule(nb, k, n_sink, n_tail):
     assert np.array_equal(s, s)   # the input is not modified
     f = oracle.force_blocks(s, n_sink, n_tail)
     assert all(np.isposinf(f[j]) for j in forced) and all(f[j] == s[j] for j in range(nb) if j not in forced)
+
+
+def test_plan_gap_names_the_only_score_pairs_that_can_change_a_plan():
+    """tests/harness.plan_gap is what the GPU parity tests use to excuse a differing plan: scores that
+    move by less than a quarter of it (relative) must leave the oracle's plan as it is, and closing
+    the deciding gap must be able to change it (so the rule neither hides nor invents mismatches)."""
+    from tests import harness
+    rng = np.random.default_rng(11)
+    changed = 0
+    for trial in range(300):
+        nb, k = int(rng.integers(4, 60)), int(rng.integers(1, 12))
+        s = rng.standard_normal(nb) * 10 + 100
+        table = np.where(rng.random(nb) < rng.choice([0.1, 0.5, 0.9]), -1, 0).astype(np.int32)
+        table[table >= 0] = rng.permutation(int((table >= 0).sum()))
+        g = harness.plan_gap(s, s, k, table)
+        t0 = table.copy()
+        base = oracle.recall_plan(s, k, t0)
+        if not np.isfinite(g):
+            continue
+        for _ in range(5):
+            s2 = s * (1.0 + (rng.random(nb) * 2 - 1) * g / 4)
+            t1 = table.copy()
+            got = oracle.recall_plan(s2, k, t1)
+            assert got[3] == base[3] and all(np.array_equal(a, b) for a, b in zip(got[:3], base[:3])), trial
+            assert np.array_equal(t0, t1)
+        # noise five times the gap does change some plans
+        s3 = s * (1.0 + (rng.random(nb) * 2 - 1) * g * 5)
+        t2 = table.copy()
+        got = oracle.recall_plan(s3, k, t2)
+        changed += int(not all(np.array_equal(a, b) for a, b in zip(got[:3], base[:3])))
+    assert changed > 10
