@@ -19,13 +19,16 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "scout_oracle.c")
-_LIB = os.path.join(_HERE, "libscout_oracle.so")
+# SCOUT_ORACLE_LIB names another build of the same source (the tests' sanitizer build) to load instead
+_LIB = os.environ.get("SCOUT_ORACLE_LIB") or os.path.join(_HERE, "libscout_oracle.so")
 
 F32, BF16 = 0, 1
 
 
 def build(force: bool = False) -> str:
     """Compile the C oracle with gcc (-O2, no fast-math). Returns the library path."""
+    if os.environ.get("SCOUT_ORACLE_LIB"):
+        return _LIB
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
     if force or stale:
         cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-Wall", "-Wextra",

@@ -11,7 +11,8 @@ import os
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libscout_host.so")
+# SCOUT_HOST_LIB names another build of the same source (the tests' sanitizer build) to load instead
+LIB_PATH = os.environ.get("SCOUT_HOST_LIB") or os.path.join(HERE, "libscout_host.so")
 EXPORTS = ["scout_host_create", "scout_host_destroy", "scout_host_submit", "scout_host_stage_recall", "scout_host_wait",
            "scout_host_done"]
 F32, BF16 = 0, 1

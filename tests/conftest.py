@@ -26,3 +26,13 @@ def oracle_lib():
     import oracle
     oracle.build()
     return oracle
+
+
+@pytest.fixture(autouse=True)
+def _output_guards(request):
+    """After every GPU test: no entry point wrote outside an output tensor of the test harness
+    (tests/gpu_harness.Arena), also for the calls a test made on those tensors directly."""
+    yield
+    if request.node.get_closest_marker("gpu") is not None:
+        from tests import gpu_harness
+        gpu_harness.check_all_guards()
