@@ -596,9 +596,12 @@ def main():
     attn_gbps = attn_bytes / us_attn_kernel * 1e-3
     score_gbps = digest_bytes / us_score * 1e-3
 
+    # HBM bytes per launch of the roofline kernel from the stored rocprofv3 counter summary of THIS
+    # configuration at its default shape (a counter run is a run of its own); null when there is none
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "attn_mfma_c3_traffic.json")
-    if os.path.exists(tpath):
+    tpath = os.path.join(ROOT, "profiles", f"attn_mfma_{args.config.lower()}_traffic.json")
+    default_shape = args.config != "C3" or (args.batch == 16 and args.ctx == 32768)
+    if os.path.exists(tpath) and default_shape and not args.group_max:
         try:
             traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
         except Exception:
@@ -647,7 +650,8 @@ def main():
                               "score_frac_of_stream": round(us_stream * digest_bytes / s0_digest_bytes / us_score, 4)},
         "roofline": {"bound": "hbm", "kernel": "attn_mfma_kernel", "achieved": round(attn_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": traffic, "algorithmic_bytes": attn_bytes},
+                     "traffic": traffic, "traffic_source": None if traffic is None else os.path.relpath(tpath, ROOT),
+                     "algorithmic_bytes": attn_bytes},
         "wall_s_timed_region": round(t_wall, 3),
         "gen_s": round(st.gen_s, 1),
     }
@@ -700,8 +704,10 @@ def cpu_baseline(st):
         list(ex.map(one, digs.items()))
         dt_mt = time.perf_counter() - t0
     st.cpu_baseline_mt = {"value": round(dt_mt * 1e6, 1), "unit": "us/layer-step", "cores": n_thr, "kind": "oracle",
+                          "host_cpu_count": os.cpu_count(),
                           "sample": "the same layer-step, pairs dealt over threads"}
     return {"value": round(dt * 1e6, 1), "unit": "us/layer-step", "cores": 1, "kind": "oracle",
+            "host_cpu_count": os.cpu_count(),
             "sample": f"one full layer-step, all {len(digs)} (sequence, KV head) pairs, single thread",
             "device_vs_oracle_max_abs_err": worst, "selection_mismatches": sel_bad}
 
