@@ -121,6 +121,8 @@ class Dev:
 
     # ---- the calls, one per boundary entry point
     def check_guards(self):
+        if torch.cuda.is_current_stream_capturing():      # a call being recorded into a graph has not run
+            return
         torch.cuda.synchronize()
         self.arena.check()
 
