@@ -50,7 +50,9 @@ enum {
   SCOUT_EINVAL = -1,       /* null pointer, bad shape, misaligned pointer          */
   SCOUT_EUNSUPPORTED = -2, /* valid request outside what the kernels cover          */
   SCOUT_EWORKSPACE = -3,   /* workspace missing, misaligned or too small            */
-  SCOUT_EHIP = -4          /* the HIP runtime reported an error at launch           */
+  SCOUT_EHIP = -4,         /* the HIP runtime reported an error at launch           */
+  SCOUT_ESCRATCH = -5      /* sparse_decode_attn_static: the problem needs more scratch
+                              than SCOUT_STATIC_SCRATCH_BYTES                         */
 };
 
 enum { SCOUT_F32 = 0, SCOUT_BF16 = 1 };
@@ -192,6 +194,34 @@ int sparse_decode_attn(const scout_problem* p, const void* q, const void* k_pool
                        const void* v_pool, int64_t n_slots, const int32_t* sel_gpu,
                        const int32_t* slot_gpu, const int32_t* n_gpu, float* o, float* m,
                        float* l, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * sparse_decode_attn for callers that cannot allocate device memory and have no
+ * workspace to hand over: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments without `ws`, same kernels,
+ * same results bit for bit.  The per-split partials that the two passes exchange
+ * live in a buffer of SCOUT_STATIC_SCRATCH_BYTES that is part of the library's
+ * device image (every GPU the library runs on holds its own copy until the
+ * process ends); the call allocates nothing, frees nothing and calls no
+ * allocating routine.
+ *   - A problem whose partials do not fit returns SCOUT_ESCRATCH and launches
+ *     nothing.  They take about  B * Hkv * nsplit * G * (d + 2) * 4  bytes, where
+ *     nsplit is the number of workgroups the library spreads a pair over: about
+ *     256 / (B * Hkv) for bf16 with d = 128 (none at all from 192 pairs on, where
+ *     a workgroup finishes its pair), at most 64.  All five benchmark
+ *     configurations need at most 1.1 MiB.
+ *   - The buffer's device address is looked up on the first call on each device
+ *     (hipGetSymbolAddress); make that first call outside a graph capture.
+ *   - Every call on a GPU uses that GPU's one buffer, which keeps the last
+ *     call's contents.  Nothing in it has to be cleared between calls (each call
+ *     writes every word it later reads), but two calls that overlap in time on
+ *     one GPU (different streams, different threads) race: order them.
+ */
+#define SCOUT_STATIC_SCRATCH_BYTES (8u << 20)
+int sparse_decode_attn_static(const scout_problem* p, const void* q, const void* k_pool,
+                              const void* v_pool, int64_t n_slots, const int32_t* sel_gpu,
+                              const int32_t* slot_gpu, const int32_t* n_gpu, float* o, float* m,
+                              float* l, void* stream);
 
 /*
  * First half of sparse_decode_attn on its own: the pass that streams the K/V

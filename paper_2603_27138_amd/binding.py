@@ -17,12 +17,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libscout.so")
 
 F32, BF16 = 0, 1
-OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP = 0, -1, -2, -3, -4
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP, ESCRATCH = 0, -1, -2, -3, -4, -5
+STATIC_SCRATCH_BYTES = 8 << 20
 
 EXPORTS = ["scout_version", "scout_strerror", "scout_workspace_bytes", "build_digests", "append_token", "score_blocks",
            "select_topk", "sparse_decode_attn", "merge_partials", "periodic_recall", "recall_fetch", "recall_scatter",
            "scout_layer_step", "scout_set_attn_mode", "scout_calib_copy", "scout_attn_partials",
-           "scout_calib_read", "scout_calib_gather", "scout_attn_finish"]
+           "scout_calib_read", "scout_calib_gather", "scout_attn_finish", "sparse_decode_attn_static"]
 
 
 class ScoutError(RuntimeError):
@@ -63,6 +64,7 @@ def lib():
         L.score_blocks.argtypes = [pp, vp, vp, vp, vp, sz, vp]
         L.select_topk.argtypes = [pp] + [vp] * 9 + [sz, vp]
         L.sparse_decode_attn.argtypes = [pp, vp, vp, vp, i64] + [vp] * 7 + [sz, vp]
+        L.sparse_decode_attn_static.argtypes = [pp, vp, vp, vp, i64] + [vp] * 6 + [vp]
         L.merge_partials.argtypes = [pp] + [vp] * 9
         L.periodic_recall.argtypes = [pp] + [vp] * 8 + [sz, vp]
         L.recall_fetch.argtypes = [pp] + [vp] * 7 + [i64, vp]
@@ -209,6 +211,12 @@ def sparse_decode_attn(p: Problem, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu
     _call("sparse_decode_attn", lib().sparse_decode_attn, ctypes.byref(p), _ptr(q), _ptr(k_pool), _ptr(v_pool), int(n_slots),
           _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu), _ptr(o), _ptr(m), _ptr(l),
           _ptr(ws), ws.numel(), _stream())
+
+
+def sparse_decode_attn_static(p: Problem, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, o, m, l):
+    """sparse_decode_attn without a workspace: the library's own static scratch buffer (no allocation)."""
+    _call("sparse_decode_attn_static", lib().sparse_decode_attn_static, ctypes.byref(p), _ptr(q), _ptr(k_pool),
+          _ptr(v_pool), int(n_slots), _ptr(sel_gpu), _ptr(slot_gpu), _ptr(n_gpu), _ptr(o), _ptr(m), _ptr(l), _stream())
 
 
 def attn_partials(p: Problem, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, ws):

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <mutex>
 
 #include "common.h"
 
@@ -161,12 +162,16 @@ static int plan_attn(const Dims& D, int dtype, AttnPlan* out) {
   return SCOUT_OK;
 }
 
+// ceil(2^32 / waves that share a pair) for the MFMA family's division of a pair's units; 0 if one wave
+static uint32_t waves_magic(const AttnPlan& A) {
+  const uint32_t n_waves = (uint32_t)A.nsplit * (uint32_t)A.waves;
+  return n_waves > 1 ? (uint32_t)(((1ull << 32) + n_waves - 1) / n_waves) : 0;
+}
+
 static Partials carve(void* ws, const WsLayout& L, const AttnPlan& A) {
   char* base = static_cast<char*>(ws);
-  const uint32_t n_waves = (uint32_t)A.nsplit * (uint32_t)A.waves;  // waves that share a pair (MFMA family)
-  const uint32_t magic = n_waves > 1 ? (uint32_t)(((1ull << 32) + n_waves - 1) / n_waves) : 0;
   return Partials{reinterpret_cast<float*>(base + L.part_o), reinterpret_cast<float*>(base + L.part_m),
-                  reinterpret_cast<float*>(base + L.part_l), A.nsplit, magic};
+                  reinterpret_cast<float*>(base + L.part_l), A.nsplit, waves_magic(A)};
 }
 
 // Attention over the listed blocks, then what E asks for.  One launch when a single MFMA workgroup
@@ -184,6 +189,46 @@ static int run_attn(const Dims& D, int dtype, const AttnPlan& A, const void* q, 
                        part, st);
   if (rc != SCOUT_OK) return rc;
   return launch_combine(D, P, E, st);
+}
+
+// ---- sparse_decode_attn_static: the per-split partials in a buffer the library image holds itself.
+//
+// `scratch` is device memory that exists on every GPU the library's code object is loaded on, from
+// then until the process ends.  In host code the NAME below is only a stand-in for the symbol: the
+// address a kernel may use comes from hipGetSymbolAddress, per device (each GPU has its own copy at
+// its own address), and is what every launch gets as an argument.
+static __device__ __align__(256) unsigned char scratch[SCOUT_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];  // zero-initialised; filled once per device, under the mutex
+
+// Address of this device's copy of `scratch` (the current device), or nullptr with *rc set.
+static void* static_scratch(int* rc) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    *rc = SCOUT_EHIP;
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+      *rc = SCOUT_EHIP;
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+
+// Partials of exactly A.nsplit splits, packed (the caller's workspace is laid out for the largest
+// split count instead, so that its size does not depend on the plan).
+static size_t static_layout(const Dims& D, const AttnPlan& A, size_t* off_m, size_t* off_l) {
+  const size_t rows = (size_t)D.B * D.Hkv * A.nsplit * D.G;
+  *off_m = round256(rows * D.d * sizeof(float));
+  *off_l = *off_m + round256(rows * sizeof(float));
+  return *off_l + round256(rows * sizeof(float));
 }
 
 // Reference for HBM byte counters: a plain copy with the same 16-byte accesses the kernels use.
@@ -252,6 +297,7 @@ const char* scout_strerror(int code) {
     case SCOUT_EUNSUPPORTED: return "shape or type not supported by the kernels";
     case SCOUT_EWORKSPACE: return "workspace missing, misaligned or too small";
     case SCOUT_EHIP: return "HIP runtime error at launch";
+    case SCOUT_ESCRATCH: return "problem needs more scratch than the library's static buffer holds";
     default: return "unknown error";
   }
 }
@@ -437,6 +483,42 @@ int sparse_decode_attn(const scout_problem* p, const void* q, const void* k_pool
   E.l = l;
   return run_attn(D, p->dtype, A, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, ws, L, E,
                   static_cast<hipStream_t>(stream));
+}
+
+int sparse_decode_attn_static(const scout_problem* p, const void* q, const void* k_pool, const void* v_pool,
+                              int64_t n_slots, const int32_t* sel_gpu, const int32_t* slot_gpu,
+                              const int32_t* n_gpu, float* o, float* m, float* l, void* stream) {
+  Dims D;
+  int rc = check_problem(p, &D);
+  if (rc != SCOUT_OK) return rc;
+  if (!q || !sel_gpu || !slot_gpu || !n_gpu || !o || !m || !l || n_slots < 0) return SCOUT_EINVAL;
+  if (n_slots > 0 && (!k_pool || !v_pool)) return SCOUT_EINVAL;
+  if (!aligned16(q) || !aligned16(k_pool) || !aligned16(v_pool) || !aligned16(o)) return SCOUT_EINVAL;
+  AttnPlan A;
+  rc = plan_attn(D, p->dtype, &A);
+  if (rc != SCOUT_OK) return rc;
+  Epilogue E{};
+  E.mode = 1;
+  E.o = o;
+  E.m = m;
+  E.l = l;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (A.family == 2 && A.nsplit == 1)  // one workgroup per pair finishes the pair itself: no scratch at all
+    return launch_attn(D, p->dtype, 2, A.waves, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu,
+                       Partials{nullptr, nullptr, nullptr, 1, waves_magic(A)}, E, st);
+  size_t off_m, off_l;
+  if (static_layout(D, A, &off_m, &off_l) > (size_t)SCOUT_STATIC_SCRATCH_BYTES) return SCOUT_ESCRATCH;
+  char* base = static_cast<char*>(static_scratch(&rc));
+  if (base == nullptr) return rc;
+  // Nothing in the buffer has to start at zero: the first pass writes the partial of every (pair, split,
+  // head) it was launched for, an empty share included, before the combine pass reads any of them.
+  const Partials P{reinterpret_cast<float*>(base), reinterpret_cast<float*>(base + off_m),
+                   reinterpret_cast<float*>(base + off_l), A.nsplit, waves_magic(A)};
+  Epilogue part{};
+  part.mode = 0;
+  rc = launch_attn(D, p->dtype, A.family, A.waves, q, k_pool, v_pool, n_slots, sel_gpu, slot_gpu, n_gpu, P, part, st);
+  if (rc != SCOUT_OK) return rc;
+  return launch_combine(D, P, E, st);
 }
 
 int merge_partials(const scout_problem* p, const float* o_a, const float* m_a, const float* l_a,

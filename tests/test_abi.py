@@ -119,3 +119,24 @@ def test_product_package_does_not_touch_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in text and "from oracle" not in text and "scout_oracle" not in text, f
+
+
+def test_static_scratch_entry_point_rejects_on_the_host(lib):
+    """sparse_decode_attn_static validates like sparse_decode_attn, and a problem whose per-split partials
+    exceed the static buffer gets SCOUT_ESCRATCH before anything is looked up or launched."""
+    L = lib.lib()
+    p = _problem(lib)
+    args = [FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE]
+    assert L.sparse_decode_attn_static(ctypes.byref(p), None, *args[1:], None) == lib.EINVAL
+    assert L.sparse_decode_attn_static(ctypes.byref(p), ctypes.c_void_p(0x10004), *args[1:], None) == lib.EINVAL
+    bad = list(args)
+    bad[3] = -1
+    assert L.sparse_decode_attn_static(ctypes.byref(p), *bad, None) == lib.EINVAL
+    assert L.sparse_decode_attn_static(ctypes.byref(_problem(lib, d=96)), *args, None) == lib.EUNSUPPORTED
+    # fp32, 512 pairs of 16 heads: two splits per pair make 16384 rows of 128 floats = 8 MiB of o alone
+    big = _problem(lib, B=64, Hq=128, Hkv=8, dtype=lib.F32)
+    assert L.sparse_decode_attn_static(ctypes.byref(big), *args, None) == lib.ESCRATCH
+    assert b"static" in L.scout_strerror(lib.ESCRATCH)
+    assert lib.STATIC_SCRATCH_BYTES == 8 << 20
+    text = open(os.path.join(ROOT, "include", "scout.h")).read()
+    assert "#define SCOUT_STATIC_SCRATCH_BYTES (8u << 20)" in text
