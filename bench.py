@@ -50,6 +50,11 @@ def parse(argv=None):
     ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--pmc-calib", action="store_true",
                     help="also run a plain 256 MiB device copy (a known-size reference for HBM byte counters)")
+    ap.add_argument("--gather-study", action="store_true",
+                    help="instead of the layer-step benchmark: the bare tile gather and the attention kernel over the "
+                         "same bytes in several pool layouts (what limits a gather of 8 KiB tiles), one JSON line")
+    ap.add_argument("--study-variants", default="",
+                    help="with --gather-study: comma-separated subset of the layouts (default: all)")
     ap.add_argument("--pipeline", action="store_true",
                     help="instead of the layer-step benchmark, time the layer-ahead GPU+host pipeline "
                          "(Sec. 3.3) over --pipe-layers layers and print its own JSON line")
@@ -390,6 +395,131 @@ def recall_overlap(st, n, us_recall, us_step, route):
     return e0.elapsed_time(e1) * 1e3 / n, f0.elapsed_time(f1) * 1e3 / n_rec
 
 
+def gather_study(args):
+    """What limits a gather of K/V tiles (Sec. 3.2: the GPU attends to blocks scattered over a paged
+    pool)?  The same number of bytes as config 3's attention launch, read by the bare gather kernel
+    (scout_calib_gather: nothing computed) and by the attention kernel, with the tiles laid out in
+    different ways.  Every layout rotates over the same number of copies, so no read is served from
+    the last-level cache.  Layouts:
+      paged        the benchmark's own: slots shuffled over a K pool and a V pool of 0.55 GiB each
+      kv_adjacent  the K tile and the V tile of a slot next to each other (one 16 KiB region per block,
+                   pools interleaved: v_pool = k_pool + one tile, even slot numbers)
+      sorted       paged, each pair's list in ascending slot order
+      small_pool   the same shuffle confined to pools that hold exactly the tiles read (32 MiB each)
+      ascending    each pair's tiles consecutive and ascending (a stream in tile-sized pieces)
+      tile16k      blocks of 64 tokens: half as many tiles of 16 KiB (K) + 16 KiB (V), shuffled
+      tile4k       blocks of 16 tokens: twice as many tiles of 4 KiB + 4 KiB, shuffled"""
+    st = setup(args)
+    torch, B, cfg, wl = st.torch, st.B, st.cfg, st.wl
+    assert cfg.S == 32 and cfg.d == 128
+    want = [v for v in args.study_variants.split(",") if v] or ["paged", "kv_adjacent", "sorted", "small_pool",
+                                                                "ascending", "tile16k", "tile4k"]
+    for i in range(len(st.sets)):          # the lists of every copy (setup leaves the host's lists in them)
+        step(st, i)
+    torch.cuda.synchronize()
+    s0 = st.sets[0]
+    n_gpu = s0.n_gpu.cpu().numpy()
+    slot = s0.slot_gpu.cpu().numpy()
+    sel = s0.sel_gpu.cpu().numpy()
+    pairs = cfg.B * cfg.Hkv
+    total = int(n_gpu.sum())
+    tile = cfg.S * cfg.d                    # elements of one K (or V) tile
+    rng = np.random.default_rng(99)
+    i32 = dict(dtype=torch.int32, device="cuda")
+
+    def lists(fn):
+        """A slot list per pair from fn(pair index, count, first position in the flattened order)."""
+        out, at = np.full_like(slot, -1), 0
+        for pi in range(pairs):
+            b, g = divmod(pi, cfg.Hkv)
+            n = int(n_gpu[b, g])
+            out[b, g, :n] = fn(pi, n, at)
+            at += n
+        return torch.from_numpy(out).cuda()
+
+    perm = rng.permutation(total).astype(np.int32)
+    variants = {}
+    if "paged" in want:
+        variants["paged"] = dict(pools=[(s.k_pool, s.v_pool) for s in st.sets], slots=s0.slot_gpu, n_slots=wl.n_slots)
+    if "sorted" in want:
+        srt = lists(lambda pi, n, at: np.sort(slot[pi // cfg.Hkv, pi % cfg.Hkv, :n]))
+        variants["sorted"] = dict(pools=[(s.k_pool, s.v_pool) for s in st.sets], slots=srt, n_slots=wl.n_slots)
+    if "kv_adjacent" in want:
+        pools = []
+        for s in st.sets:
+            kv = torch.empty(wl.n_slots, 2, cfg.S, cfg.d, dtype=torch.bfloat16, device="cuda")
+            kv[:, 0], kv[:, 1] = s.k_pool, s.v_pool
+            flat = kv.view(-1)
+            pools.append((flat, flat[tile:]))
+        variants["kv_adjacent"] = dict(pools=pools, slots=(s0.slot_gpu * 2).where(s0.slot_gpu >= 0, s0.slot_gpu),
+                                       n_slots=2 * wl.n_slots - 1)
+    small = [(torch.randn(total, cfg.S, cfg.d, device="cuda").to(torch.bfloat16),
+              torch.randn(total, cfg.S, cfg.d, device="cuda").to(torch.bfloat16)) for _ in st.sets] \
+        if {"small_pool", "ascending"} & set(want) else None
+    if "small_pool" in want:
+        variants["small_pool"] = dict(pools=small, slots=lists(lambda pi, n, at: perm[at:at + n]), n_slots=total)
+    if "ascending" in want:
+        variants["ascending"] = dict(pools=small, slots=lists(lambda pi, n, at: np.arange(at, at + n)), n_slots=total)
+    probs = {v: st.probs for v in variants}
+    counts = {v: s0.n_gpu for v in variants}
+    sels = {v: s0.sel_gpu for v in variants}
+    for name, S2 in (("tile16k", 64), ("tile4k", 16)):
+        if name not in want:
+            continue
+        # the same bytes in tiles of another size: the pools are the paged ones, seen as [slots'][S2][d]
+        f = S2 / cfg.S
+        k2 = max(1, int(round(cfg.k / f)))
+        ns2 = int(wl.n_slots / f)
+        n2 = np.minimum(np.maximum(np.round(n_gpu / f).astype(np.int32), 0), k2)
+        sl2 = np.full((cfg.B, cfg.Hkv, k2), -1, dtype=np.int32)
+        se2 = np.full((cfg.B, cfg.Hkv, k2), -1, dtype=np.int32)
+        p2 = rng.permutation(ns2).astype(np.int32)
+        at = 0
+        for b in range(cfg.B):
+            for g in range(cfg.Hkv):
+                n = int(n2[b, g])
+                sl2[b, g, :n] = p2[at:at + n]
+                se2[b, g, :n] = np.arange(n)                 # logical ids only mask a partial last block
+                at += n
+        variants[name] = dict(pools=[(s.k_pool, s.v_pool) for s in st.sets], slots=torch.from_numpy(sl2).cuda(), n_slots=ns2)
+        probs[name] = [B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, S2, B.BF16, max(1, int(cfg.max_blocks / f)), k2, s.ctx_len)
+                       for s in st.sets]
+        counts[name] = torch.from_numpy(n2).cuda()
+        sels[name] = torch.from_numpy(se2).cuda()
+
+    def timed_calls(calls, n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(8):
+            calls[i % len(calls)]()
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n):
+            calls[i % len(calls)]()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / n
+
+    out = {}
+    for name, v in variants.items():
+        S2 = probs[name][0].S
+        nbytes = int(counts[name].sum().item()) * 2 * S2 * cfg.d * 2
+        g_calls = [B.prepare(B.calib_gather, probs[name][j], kp, vp, v["n_slots"], v["slots"], counts[name])
+                   for j, (kp, vp) in enumerate(v["pools"])]
+        ws = B.alloc_workspace(probs[name][0])
+        a_calls = [B.prepare(B.attn_partials, probs[name][j], st.sets[j].q, kp, vp, v["n_slots"], sels[name], v["slots"],
+                             counts[name], ws) for j, (kp, vp) in enumerate(v["pools"])]
+        us_g, us_a = timed_calls(g_calls, args.steps), timed_calls(a_calls, args.steps)
+        out[name] = {"bytes": nbytes, "gather_us": round(us_g, 3), "gather_gbps": round(nbytes / us_g * 1e-3, 1),
+                     "attn_us": round(us_a, 3), "attn_gbps": round(nbytes / us_a * 1e-3, 1)}
+    us_stream = timed(st, stream_only, args.steps)
+    sbytes = s0.digest.numel() * 2
+    print(json.dumps({"metric": "gather study: us per launch over config 3's attention bytes by pool layout",
+                      "config": {"workload": "C3 qwen3-32b-shaped single layer", "layer_copies": len(st.sets),
+                                 "tiles": total}, "steps": args.steps,
+                      "stream": {"bytes": sbytes, "us": round(us_stream, 3), "gbps": round(sbytes / us_stream * 1e-3, 1)},
+                      "layouts": out}))
+
+
 def pipeline_main(args):
     """Layer-ahead pipeline (Sec. 3.3, Algorithm 1) at config 3's shape: per layer the selection with the
     predicted query, the host worker on the offloaded selected blocks, the GPU's partial and the merge;
@@ -521,6 +651,8 @@ def main():
     args = parse()
     if args.pipeline and args.gpus == 1:
         return pipeline_main(args)
+    if args.gather_study and args.gpus == 1:
+        return gather_study(args)
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only; every (sequence, KV head) pair is independent, so "
               "more GPUs would each run this same path on their share. Run with --gpus 1.", file=sys.stderr)

@@ -344,7 +344,7 @@ int scout_layer_step(const scout_problem* p, const void* q, const void* digest,
  * SCOUT_EUNSUPPORTED at the call), 3 = as 2, but scout_layer_step launches the
  * selection on its own instead of inside the attention kernel.
  * nsplit: 0 = automatic, else 1..64.
- * waves: 0 = automatic, else 8 or 16 waves per workgroup (MFMA family).
+ * waves: 0 = automatic, else 4, 8 or 16 waves per workgroup (MFMA family).
  * Process-wide, not thread-safe.
  */
 int scout_set_attn_mode(int family, int nsplit, int waves);

@@ -135,7 +135,7 @@ static int plan_attn(const Dims& D, int dtype, AttnPlan* out) {
   const long long pairs = (long long)D.B * D.Hkv;
   int ns = g_nsplit, waves = 1;
   if (fam == 2) {
-    // Eight waves per workgroup, four 16-token units in flight per wave.  A compute unit sustains
+    // Eight waves per workgroup, one 16-token unit in flight per wave.  A compute unit sustains
     // only a fraction of the HBM rate on its own, so the launch should cover all 256 of them: a
     // pair's units are split over ceil(256 / pairs) workgroups (folded by the small combine pass)
     // unless the pairs alone nearly fill the chip.
@@ -307,7 +307,7 @@ int scout_set_attn_mode(int family, int nsplit, int waves) {
   g_fuse_select = family != 3;
   if (family == 3) family = 2;
   if (family < 0 || family > 2 || nsplit < 0 || nsplit > kMaxSplit) return SCOUT_EINVAL;
-  if (waves != 0 && waves != 8 && waves != 16) return SCOUT_EINVAL;
+  if (waves != 0 && waves != 4 && waves != 8 && waves != 16) return SCOUT_EINVAL;
   g_family = family;
   g_nsplit = nsplit;
   g_waves = waves;

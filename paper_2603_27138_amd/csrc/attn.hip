@@ -249,7 +249,7 @@ __device__ __forceinline__ void load_q(u32x4 (&qreg)[4], const Dims& D, const ui
 
 // The attention of one workgroup: its share (split) of the pair's list, folded over the waves
 // through LDS, then the epilogue.  sel / slot_list: the pair's list in global memory or LDS.
-template <int WAVES>
+template <int WAVES, int DEPTH>
 __device__ __forceinline__ void attend_pair(const Dims& D, int b, int g, int split, const u32x4 (&qreg)[4],
                                             const uint16_t* __restrict__ k_pool,
                                             const uint16_t* __restrict__ v_pool, long long n_slots,
@@ -288,9 +288,9 @@ __device__ __forceinline__ void attend_pair(const Dims& D, int b, int g, int spl
   W.l = 0.0f;
 
   // DEPTH units are kept in flight per wave: the loads of the next ones are issued before a unit is
-  // consumed, so a wave with up to DEPTH units has everything requested up front.  Eight waves per
-  // workgroup run two to a SIMD and can hold four units (128 registers); sixteen hold two.
-  constexpr int DEPTH = WAVES <= 8 ? 4 : 2;
+  // consumed.  Measured at the benchmark shapes, one unit in flight per wave with eight waves per
+  // workgroup (64 KiB requested per compute unit at any time) beats two, three and four (17.0, 17.4,
+  // 17.7 and 19.0 us for 64.5 MiB of tiles).
   UnitRegs buf[DEPTH];
   Entry ent[DEPTH];
 #pragma unroll
@@ -399,7 +399,7 @@ __device__ __forceinline__ void attend_pair(const Dims& D, int b, int g, int spl
   }
 }
 
-template <int WAVES>
+template <int WAVES, int DEPTH>
 __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
     Dims D, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_pool,
     const uint16_t* __restrict__ v_pool, long long n_slots, const int32_t* __restrict__ sel_gpu,
@@ -422,7 +422,7 @@ __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
   u32x4 qreg[4];
   load_q(qreg, D, q, b, g, lane & 15, lane >> 4);
   __syncthreads();
-  attend_pair<WAVES>(D, b, g, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, n, ctx, P, E, smem);
+  attend_pair<WAVES, DEPTH>(D, b, g, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, n, ctx, P, E, smem);
 }
 
 // Selection and attention of a pair in one launch (the non-pipelined description of Sec. 3.2:
@@ -510,7 +510,7 @@ __global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
     if (tid == 0) l_n[0] = ng;
   }
   __syncthreads();
-  attend_pair<WAVES>(D, b, g, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, l_n[0], ctx, P, E, smem);
+  attend_pair<WAVES, 1>(D, b, g, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, l_n[0], ctx, P, E, smem);
 }
 
 // ---------------------------------------------------------------- VALU family
@@ -634,6 +634,7 @@ __global__ __launch_bounds__(kWave) void attn_valu_kernel(
 // Fold the nsplit partials of every (sequence, query head), then export the GPU
 // partial or go straight on to the merge with the host's partial (Epilogue modes
 // 1 and 2).  One workgroup of d threads per head.
+template <int GROUP>
 __global__ void combine_kernel(Dims D, Partials P, Epilogue E) {
   // grid (G, Hkv, B): head within the group, KV head, sequence
   const int h = blockIdx.x;
@@ -641,13 +642,13 @@ __global__ void combine_kernel(Dims D, Partials P, Epilogue E) {
   const int c = threadIdx.x;
   const size_t p0 = (size_t)pair * P.nsplit;
   const HostPart hp = load_host(D, E, bh, c);
-  // one pass with a running maximum, four splits at a time: every load of a group is independent
-  // of the others, so a group costs one trip to memory
+  // one pass with a running maximum, GROUP splits at a time: every load of a group is independent
+  // of the others, so a group costs one trip to memory (GROUP covers the split count where it can)
   float M = -INFINITY, acc = 0.0f, l = 0.0f;
-  for (int s0 = 0; s0 < P.nsplit; s0 += 4) {
-    float ms[4], ls[4], os[4];
+  for (int s0 = 0; s0 < P.nsplit; s0 += GROUP) {
+    float ms[GROUP], ls[GROUP], os[GROUP];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < GROUP; ++j) {
       const int sp = s0 + j < P.nsplit ? s0 + j : P.nsplit - 1;
       const size_t r = (p0 + sp) * D.G + h;
       ms[j] = P.m[r];
@@ -656,13 +657,13 @@ __global__ void combine_kernel(Dims D, Partials P, Epilogue E) {
     }
     float Mn = M;
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < GROUP; ++j)
       if (s0 + j < P.nsplit) Mn = fmaxf(Mn, ms[j]);
     const float f0 = exp2_diff(M, Mn);
     acc *= f0;
     l *= f0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < GROUP; ++j) {
       if (s0 + j < P.nsplit) {
         const float f = exp2_diff(ms[j], Mn);
         acc += f * os[j];
@@ -728,14 +729,21 @@ int launch_attn(const Dims& D, int dtype, int family, int waves, const void* q, 
     const uint16_t* q16 = static_cast<const uint16_t*>(q);
     const uint16_t* k16 = static_cast<const uint16_t*>(k_pool);
     const uint16_t* v16 = static_cast<const uint16_t*>(v_pool);
+#define SCOUT_ATTN(W, DP)                                                                               \
+  hipLaunchKernelGGL((attn_mfma_kernel<W, DP>), grid, block, lds, st, D, q16, k16, v16, n_slots, sel_gpu, \
+                     slot_gpu, n_gpu, P, E)
+    // units in flight per wave: few.  Requests that only queue in the memory system buy nothing (a
+    // compute unit's loads return in the order they were issued), and fewer registers leave room for
+    // the next workgroup to start its head while this one folds.
     if (waves == 16)
-      hipLaunchKernelGGL((attn_mfma_kernel<16>), grid, block, lds, st, D, q16, k16, v16, n_slots, sel_gpu,
-                         slot_gpu, n_gpu, P, E);
+      SCOUT_ATTN(16, 1);
     else if (waves == 8)
-      hipLaunchKernelGGL((attn_mfma_kernel<8>), grid, block, lds, st, D, q16, k16, v16, n_slots, sel_gpu,
-                         slot_gpu, n_gpu, P, E);
+      SCOUT_ATTN(8, 1);
+    else if (waves == 4)
+      SCOUT_ATTN(4, 2);
     else
       return SCOUT_EINVAL;
+#undef SCOUT_ATTN
   } else {
     if (E.mode != 0) return SCOUT_EINVAL;
     dim3 grid(P.nsplit, pairs, (D.G + kValuHeads - 1) / kValuHeads), block(kWave);
@@ -796,7 +804,12 @@ int launch_select_attend(const Dims& D, const void* q, const float* scores, cons
 int launch_combine(const Dims& D, Partials P, Epilogue E, hipStream_t st) {
   dim3 grid(D.G, D.Hkv, D.B), block(D.d);
   if (grid.z == 0) return SCOUT_OK;
-  hipLaunchKernelGGL(combine_kernel, grid, block, 0, st, D, P, E);
+  if (P.nsplit <= 2)
+    hipLaunchKernelGGL(combine_kernel<2>, grid, block, 0, st, D, P, E);
+  else if (P.nsplit <= 4)
+    hipLaunchKernelGGL(combine_kernel<4>, grid, block, 0, st, D, P, E);
+  else
+    hipLaunchKernelGGL(combine_kernel<8>, grid, block, 0, st, D, P, E);
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
 }
 

@@ -186,7 +186,7 @@ def test_sparse_decode_attn(cfg, family):
         assert ei.value.code == B.EUNSUPPORTED
         return
     dev.set_selection_from_oracle(res)
-    modes = [(0, 0), (1, 0), (3, 0)] if family == 1 else [(0, 0), (1, 16), (1, 8), (2, 8), (3, 8), (7, 8), (5, 16)]
+    modes = [(0, 0), (1, 0), (3, 0)] if family == 1 else [(0, 0), (1, 16), (1, 8), (2, 8), (3, 8), (7, 8), (5, 16), (1, 4), (2, 4), (9, 4)]
     for nsplit, waves in modes:
         B.set_attn_mode(family, nsplit, waves)
         try:
@@ -244,7 +244,7 @@ def test_layer_step_end_to_end(cfg):
     dev.set_digest_from_oracle(res)
     dev.set_host_partials_from_oracle(res)
     mfma = cfg.dtype == "bf16" and cfg.d == 128
-    for mode in ([(0, 0, 0), (2, 1, 16), (2, 4, 16), (2, 1, 8), (2, 3, 8), (3, 1, 8), (3, 2, 8), (1, 2, 0)] if mfma else [(0, 0, 0), (1, 2, 0)]):
+    for mode in ([(0, 0, 0), (2, 1, 16), (2, 4, 16), (2, 1, 8), (2, 3, 8), (3, 1, 8), (3, 2, 8), (2, 2, 4), (1, 2, 0)] if mfma else [(0, 0, 0), (1, 2, 0)]):
         dev.out.zero_(); dev.lse.fill_(float("nan"))
         for t_ in (dev.sel_all, dev.sel_gpu, dev.slot_gpu, dev.sel_host, dev.n_gpu, dev.n_host):
             t_.fill_(-7)
