@@ -328,7 +328,12 @@ int recall_scatter(const scout_problem* p, const void* staged, int64_t n_tiles, 
  * score, select, attend, and combine the attention splits together with the
  * host partial.  Outputs are those of the four separate calls; host_* may be
  * all NULL (nothing offloaded).  sel_host / n_host tell the host which blocks
- * it has to cover for this query.
+ * it has to cover for this query.  `scores` may be NULL for a caller that does
+ * not need them (they then stay in the workspace or, where one workgroup does
+ * the whole step of a pair, on the chip).  Launches: three where a pair is
+ * spread over several workgroups (scoring; selection + attention; combine +
+ * merge), one where the pairs alone fill the chip (bf16, d = 128, at least 192
+ * pairs: every step of a pair in one workgroup).
  */
 int scout_layer_step(const scout_problem* p, const void* q, const void* digest,
                      const int32_t* block_table, const void* k_pool, const void* v_pool,
@@ -342,7 +347,8 @@ int scout_layer_step(const scout_problem* p, const void* q, const void* digest,
  * count per pair and the workgroup size.  family: 0 = automatic, 1 = generic
  * vector-ALU kernel, 2 = MFMA kernel (bf16 and d = 128 only; otherwise
  * SCOUT_EUNSUPPORTED at the call), 3 = as 2, but scout_layer_step launches the
- * selection on its own instead of inside the attention kernel.
+ * scoring and the selection on their own instead of inside the attention kernel,
+ * 4 = as 2, but only the scoring on its own.
  * nsplit: 0 = automatic, else 1..64.
  * waves: 0 = automatic, else 4, 8 or 16 waves per workgroup (MFMA family).
  * Process-wide, not thread-safe.

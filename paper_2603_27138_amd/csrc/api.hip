@@ -29,6 +29,9 @@ bool select_attend_supported(const Dims&, int);
 int launch_select_attend(const Dims&, const void*, const float*, const int32_t*, const void*, const void*,
                          long long, int32_t*, int32_t*, int32_t*, int32_t*, int32_t*, int32_t*, Partials,
                          Epilogue, hipStream_t);
+bool step_kernel_supported(const Dims&, int);
+int launch_step(const Dims&, const void*, const void*, const int32_t*, const void*, const void*, long long, float*,
+                int32_t*, int32_t*, int32_t*, int32_t*, int32_t*, int32_t*, Partials, Epilogue, hipStream_t);
 int launch_merge(const Dims&, int, const float*, const float*, const float*, const float*,
                  const float*, const float*, void*, float*, hipStream_t);
 
@@ -39,6 +42,7 @@ static int g_family = 0;  // 0 auto, 1 vector ALU, 2 MFMA
 static int g_nsplit = 0;  // 0 auto
 static int g_waves = 0;   // 0 auto; MFMA family only
 static int g_fuse_select = 1;  // scout_layer_step: selection inside the attention launch
+static int g_fuse_step = 1;    // scout_layer_step: scoring too, where one workgroup per pair fills the chip
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -303,10 +307,12 @@ const char* scout_strerror(int code) {
 }
 
 int scout_set_attn_mode(int family, int nsplit, int waves) {
-  // family 3 = MFMA family with select_topk as a launch of its own inside scout_layer_step
+  // family 3 = MFMA family with select_topk as a launch of its own inside scout_layer_step;
+  // family 4 = MFMA family with score_blocks as a launch of its own (selection still in the attention launch)
   g_fuse_select = family != 3;
-  if (family == 3) family = 2;
-  if (family < 0 || family > 2 || nsplit < 0 || nsplit > kMaxSplit) return SCOUT_EINVAL;
+  g_fuse_step = family != 3 && family != 4;
+  if (family == 3 || family == 4) family = 2;
+  if (family < 0 || family > 2 || nsplit < 0 || nsplit > kMaxSplit) return SCOUT_EINVAL;  // 3 and 4 were mapped to 2 above
   if (waves != 0 && waves != 4 && waves != 8 && waves != 16) return SCOUT_EINVAL;
   g_family = family;
   g_nsplit = nsplit;
@@ -588,7 +594,7 @@ int scout_layer_step(const scout_problem* p, const void* q, const void* digest,
   Dims D;
   int rc = check_problem(p, &D);
   if (rc != SCOUT_OK) return rc;
-  if (!q || !digest || !block_table || !scores || !sel_all || !sel_gpu || !slot_gpu || !n_gpu ||
+  if (!q || !digest || !block_table || !sel_all || !sel_gpu || !slot_gpu || !n_gpu ||
       !sel_host || !n_host || !out || n_slots < 0)
     return SCOUT_EINVAL;
   if (n_slots > 0 && (!k_pool || !v_pool)) return SCOUT_EINVAL;
@@ -603,8 +609,6 @@ int scout_layer_step(const scout_problem* p, const void* q, const void* digest,
   rc = plan_attn(D, p->dtype, &A);
   if (rc != SCOUT_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  rc = launch_score(D, p->dtype, q, digest, scores, st);
-  if (rc != SCOUT_OK) return rc;
   Epilogue E{};
   E.mode = 2;
   E.host_o = host_o;
@@ -613,6 +617,13 @@ int scout_layer_step(const scout_problem* p, const void* q, const void* digest,
   E.out = out;
   E.lse = lse;
   E.dtype_out = p->dtype;
+  if (g_fuse_select && g_fuse_step && A.family == 2 && A.waves == 8 && A.nsplit == 1 && step_kernel_supported(D, p->dtype))
+    // the pairs alone fill the chip: the whole step of a pair in one workgroup, one launch
+    return launch_step(D, q, digest, block_table, k_pool, v_pool, n_slots, scores, sel_all, sel_gpu, slot_gpu, n_gpu,
+                       sel_host, n_host, carve(ws, L, A), E, st);
+  if (scores == nullptr) scores = reinterpret_cast<float*>(static_cast<char*>(ws) + L.scores);
+  rc = launch_score(D, p->dtype, q, digest, scores, st);
+  if (rc != SCOUT_OK) return rc;
   if (g_fuse_select && A.family == 2 && A.waves == 8 && select_attend_supported(D, p->dtype)) {
     // selection rides in the head of the attention kernel: two launches for the whole step
     Partials P = carve(ws, L, A);

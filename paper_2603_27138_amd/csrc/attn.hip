@@ -513,6 +513,191 @@ __global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
   attend_pair<WAVES, 1>(D, b, g, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, l_n[0], ctx, P, E, smem);
 }
 
+// The whole layer-step of a pair in one launch (the non-pipelined sequence of Sec. 3.2: score every
+// block against its digest, keep the top-k, attend to the resident ones, merge with the host's
+// partial), for launches in which the pairs alone fill the chip (one workgroup per pair, nothing to
+// combine afterwards).  The workgroup streams the pair's digest rows, keeps the scores as selection
+// keys in LDS (they go to global memory only if the caller wants them), selects, and goes on to the
+// attention without a second launch or a trip of the scores through HBM.  bf16, d = 128, min/max
+// digests, the group's heads summed.
+//
+// Scoring repeats score_kernel's arithmetic operation for operation (the same stream layout, the same
+// order of the binary64 FMAs, the same three exchange steps), so a score has the same bits whichever
+// kernel made it.  A wave keeps one batch of 16 blocks (8 KiB) in flight, the next requested as soon
+// as one is scored (two or four in flight measured the same: 62.8, 62.0 against 62.2 us at batch 32).
+constexpr int kStepBatch = 8;         // wave-wide loads per batch: 16 blocks
+constexpr int kStepEntryBytes = 512;  // one digest entry: min row and max row of 128 bf16
+
+template <int KPL>
+__global__ __launch_bounds__(8 * kWave) void step_kernel(
+    Dims D, const uint16_t* q, const char* digest, const int32_t* __restrict__ table,
+    const uint16_t* __restrict__ k_pool, const uint16_t* __restrict__ v_pool, long long n_slots,
+    float* scores, int32_t* __restrict__ sel_all, int32_t* __restrict__ sel_gpu,
+    int32_t* __restrict__ slot_gpu, int32_t* __restrict__ n_gpu, int32_t* __restrict__ sel_host,
+    int32_t* __restrict__ n_host, Partials P, Epilogue E) {
+  constexpr int WAVES = 8;
+  extern __shared__ float smem[];
+  const int b = blockIdx.z, g = blockIdx.y, pair = grid_pair();
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int kpad = (D.k + 3) & ~3;
+  int* l_sel = reinterpret_cast<int*>(smem + WAVES * (D.G * (kMfmaD + 4) + 32));
+  int* l_slot = l_sel + kpad;
+  int* l_x = l_slot + kpad;
+  int* l_n = l_x + selector_lds_ints<WAVES>();
+  uint32_t* l_key = reinterpret_cast<uint32_t*>(l_n + 4);                       // [WAVES * 64 * KPL]
+  double* coef_lds = reinterpret_cast<double*>(l_key + WAVES * kWave * KPL);    // [2][128]: N_c, P_c
+
+  // table entries of the elements this thread will hold in the selection: requested first, used last
+  const size_t trow = (size_t)kv_row(D, pair) * D.max_blocks;
+  int slot[KPL];
+#pragma unroll
+  for (int r = 0; r < KPL; ++r) {
+    const int i = (wave * KPL + r) * kWave + lane;
+    slot[r] = table[trow + (i < D.max_blocks ? i : D.max_blocks - 1)];
+  }
+  // the group's queries: thread t < 256 folds channel t % 128, negative (t < 128) or positive parts
+  const int fc = threadIdx.x & (kMfmaD - 1);
+  const bool fpos = threadIdx.x >= kMfmaD;
+  const uint16_t* qbase = q + ((size_t)b * D.Hq + g * D.G) * kMfmaD + fc;
+  float qv[16];
+  if (threadIdx.x < 2 * kMfmaD) {
+#pragma unroll
+    for (int h = 0; h < 16; ++h) qv[h] = bf16_bits_to_f32(qbase[(size_t)(h < D.G ? h : D.G - 1) * kMfmaD]);
+  }
+  const int ctx = D.ctx_len[b];
+  int nb = (ctx < 0 ? 0 : ctx + D.S - 1) >> D.s_shift;
+  nb = nb < D.max_blocks ? nb : D.max_blocks;
+
+  const char* dpair = digest + trow * kStepEntryBytes;
+  const __amdgpu_buffer_rsrc_t rs =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(dpair), 0, nb * kStepEntryBytes, 0x00020000);
+  const int n_batches = (nb + 15) >> 4;
+  // byte offset of load `it` of the batch that starts at block j0: group it / 4, line it % 4 of its entries
+  const int voff0 = (lane >> 3) * kStepEntryBytes + (lane & 7) * 16;
+  auto load_batch = [&](u32x4(&dst)[kStepBatch], int batch) {
+    const int base = batch < n_batches ? batch * 16 * kStepEntryBytes + voff0 : nb * kStepEntryBytes;  // beyond: reads zeros
+#pragma unroll
+    for (int it = 0; it < kStepBatch; ++it)
+      dst[it] = __builtin_bit_cast(
+          u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, base + (it >> 2) * 8 * kStepEntryBytes + (it & 3) * 128, 0, 0));
+  };
+  u32x4 raw[kStepBatch];
+  load_batch(raw, wave);
+
+  if (threadIdx.x < 2 * kMfmaD) {
+    double f = 0.0;
+#pragma unroll
+    for (int h = 0; h < 16; ++h)
+      if (h < D.G) f += (double)(fpos ? fmaxf(qv[h], 0.0f) : fminf(qv[h], 0.0f));
+    coef_lds[(fpos ? kMfmaD : 0) + fc] = f;
+  }
+  // rows of the key array that no batch will write
+  for (int i = n_batches * 16 + threadIdx.x; i < WAVES * kWave * KPL; i += WAVES * kWave) l_key[i] = 0u;
+  __syncthreads();
+  double coef[4][8];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) coef[u][i] = coef_lds[(u >= 2 ? kMfmaD : 0) + (u & 1) * 64 + (lane & 7) * 8 + i];
+
+  const bool hi2 = (lane >> 2) & 1;
+  const size_t srow = (size_t)pair * D.max_blocks;
+  // scores of the 16 blocks of one batch from its eight loads; a batch beyond the last one holds zeros
+  // and only marks rows beyond the sequence
+  auto score_batch = [&](const u32x4(&cur)[kStepBatch], int batch) {
+    double a[2];
+#pragma unroll
+    for (int gq = 0; gq < 2; ++gq) {
+      double acc = 0.0;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const u32x4 w = cur[gq * 4 + u];
+        acc = fma(coef[u][0], (double)bf16_lo(w[0]), acc);
+        acc = fma(coef[u][1], (double)bf16_hi(w[0]), acc);
+        acc = fma(coef[u][2], (double)bf16_lo(w[1]), acc);
+        acc = fma(coef[u][3], (double)bf16_hi(w[1]), acc);
+        acc = fma(coef[u][4], (double)bf16_lo(w[2]), acc);
+        acc = fma(coef[u][5], (double)bf16_hi(w[2]), acc);
+        acc = fma(coef[u][6], (double)bf16_lo(w[3]), acc);
+        acc = fma(coef[u][7], (double)bf16_hi(w[3]), acc);
+      }
+      a[gq] = acc;
+    }
+    const double keep = hi2 ? a[1] : a[0], send = hi2 ? a[0] : a[1];
+    double sc = keep + partner_f64<2>(send);
+    sc += partner_f64<1>(sc);
+    sc += partner_f64<0>(sc);
+    const int j = batch * 16 + (hi2 ? 8 : 0) + (lane >> 3);
+    if ((lane & 3) == 0) {
+      const bool kept = j < D.n_sink || j >= nb - D.n_tail;  // always-kept blocks rank above every score
+      const float val = j < nb ? (kept ? INFINITY : (float)sc) : -INFINITY;
+      if (j < WAVES * kWave * KPL) l_key[j] = j < nb ? score_key(val) : 0u;
+      if (scores != nullptr && j < D.max_blocks) scores[srow + j] = val;
+    }
+  };
+  for (int batch = wave; batch < n_batches; batch += WAVES) {
+    score_batch(raw, batch);
+    load_batch(raw, batch + WAVES);
+  }
+  if (scores != nullptr)  // the row's tail beyond the last batch
+    for (int j = n_batches * 16 + threadIdx.x; j < D.max_blocks; j += WAVES * kWave) scores[srow + j] = -INFINITY;
+
+  u32x4 qreg[4];
+  load_q(qreg, D, q, b, g, lane & 15, lane >> 4);
+  __syncthreads();
+
+  const int k_eff = D.k < nb ? D.k : nb;
+  uint32_t key[KPL];
+#pragma unroll
+  for (int r = 0; r < KPL; ++r) {
+    const int i = (wave * KPL + r) * kWave + lane;
+    key[r] = l_key[i];  // 0 beyond nb
+    slot[r] = i < nb ? slot[r] : -1;
+  }
+  Selector<WAVES, KPL> S{l_x, 0, wave};
+  uint32_t sel = 0;
+  if (k_eff > 0) sel = S.best(key, k_eff, false);
+  uint32_t gpu = 0;
+#pragma unroll
+  for (int r = 0; r < KPL; ++r)
+    if (((sel >> r) & 1u) && slot[r] >= 0) gpu |= 1u << r;
+  int pos_all[KPL], pos_gpu[KPL];
+  const int ng = S.positions2(sel, pos_all, gpu, pos_gpu);
+  const int nh = k_eff - ng;
+  const size_t out0 = (size_t)pair * D.k;
+#pragma unroll
+  for (int r = 0; r < KPL; ++r) {
+    if ((sel >> r) & 1u) {
+      const int i = (wave * KPL + r) * kWave + lane;
+      sel_all[out0 + pos_all[r]] = i;
+      if ((gpu >> r) & 1u) {
+        l_sel[pos_gpu[r]] = i;
+        l_slot[pos_gpu[r]] = slot[r];
+        sel_gpu[out0 + pos_gpu[r]] = i;
+        slot_gpu[out0 + pos_gpu[r]] = slot[r];
+      } else {
+        sel_host[out0 + pos_all[r] - pos_gpu[r]] = i;
+      }
+    }
+  }
+  for (int t = threadIdx.x; t < D.k; t += WAVES * kWave) {
+    if (t >= k_eff) sel_all[out0 + t] = -1;
+    if (t >= ng) {
+      sel_gpu[out0 + t] = -1;
+      slot_gpu[out0 + t] = -1;
+    }
+    if (t >= nh) sel_host[out0 + t] = -1;
+  }
+  if (threadIdx.x == 0) {
+    n_gpu[pair] = ng;
+    n_host[pair] = nh;
+    l_n[0] = ng;
+  }
+  __syncthreads();
+  attend_pair<WAVES, 1>(D, b, g, 0, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, l_n[0], ctx, P, E, smem);
+}
+
 // ---------------------------------------------------------------- VALU family
 
 constexpr int kValuHeads = 4;  // query heads per wave
@@ -798,6 +983,43 @@ int launch_select_attend(const Dims& D, const void* q, const float* scores, cons
   else
     return SCOUT_EUNSUPPORTED;
 #undef SCOUT_SA
+  return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
+}
+
+// One workgroup streams its pair's whole digest row: worth it while a row is short enough that one
+// long sequence among short ones cannot hold the launch up for long (2048 blocks = 1 MiB of digest).
+bool step_kernel_supported(const Dims& D, int dtype) {
+  return select_attend_supported(D, dtype) && D.digest_kind == 0 && D.group_max == 0 && D.max_blocks <= 2048;
+}
+
+// Scoring, selection, attention and merge of every pair in one launch, one workgroup per pair
+// (P.nsplit must be 1, E.mode 2).  `scores` may be null.
+int launch_step(const Dims& D, const void* q, const void* digest, const int32_t* table, const void* k_pool,
+                const void* v_pool, long long n_slots, float* scores, int32_t* sel_all, int32_t* sel_gpu,
+                int32_t* slot_gpu, int32_t* n_gpu, int32_t* sel_host, int32_t* n_host, Partials P, Epilogue E,
+                hipStream_t st) {
+  if (D.B * D.Hkv == 0) return SCOUT_OK;
+  if (P.nsplit != 1 || E.mode != 2) return SCOUT_EINVAL;
+  dim3 grid(1, D.Hkv, D.B), block(8 * kWave);
+  const int per_lane = (D.max_blocks + 8 * kWave - 1) / (8 * kWave);
+  const int kpl = per_lane <= 2 ? 2 : per_lane <= 4 ? 4 : per_lane <= 8 ? 8 : 16;
+  const size_t lds = mfma_smem_bytes(D, 8) +
+                     (2 * (size_t)((D.k + 3) & ~3) + selector_lds_ints<8>() + 4 + 8 * kWave * kpl) * sizeof(int) +
+                     2 * kMfmaD * sizeof(double);
+  const uint16_t* q16 = static_cast<const uint16_t*>(q);
+  const char* dg = static_cast<const char*>(digest);
+  const uint16_t* k16 = static_cast<const uint16_t*>(k_pool);
+  const uint16_t* v16 = static_cast<const uint16_t*>(v_pool);
+#define SCOUT_STEP(KPL)                                                                                      \
+  hipLaunchKernelGGL((step_kernel<KPL>), grid, block, lds, st, D, q16, dg, table, k16, v16, n_slots, scores, \
+                     sel_all, sel_gpu, slot_gpu, n_gpu, sel_host, n_host, P, E)
+  if (kpl == 2)
+    SCOUT_STEP(2);
+  else if (kpl == 4)
+    SCOUT_STEP(4);
+  else  // rows beyond 2048 blocks: see step_kernel_supported
+    return SCOUT_EUNSUPPORTED;
+#undef SCOUT_STEP
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
 }
 

@@ -101,7 +101,7 @@ def test_null_misaligned_and_workspace_errors(lib):
     assert L.recall_scatter(ctypes.byref(p), FAKE, 4, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, -1, None) == lib.EINVAL
     assert L.recall_scatter(ctypes.byref(p), FAKE, -4, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 4, None) == lib.EINVAL
     assert L.recall_fetch(ctypes.byref(p), FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, 4, None) == lib.EINVAL
-    assert L.scout_set_attn_mode(4, 0, 0) == lib.EINVAL and L.scout_set_attn_mode(0, 0, 5) == lib.EINVAL and L.scout_set_attn_mode(0, 0, 0) == 0
+    assert L.scout_set_attn_mode(5, 0, 0) == lib.EINVAL and L.scout_set_attn_mode(0, 0, 5) == lib.EINVAL and L.scout_set_attn_mode(0, 0, 0) == 0
     # MFMA family forced on a shape it does not cover
     p32 = _problem(lib, dtype=lib.F32)
     assert L.scout_set_attn_mode(2, 0, 0) == 0

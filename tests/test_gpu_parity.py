@@ -244,8 +244,10 @@ def test_layer_step_end_to_end(cfg):
     dev.set_digest_from_oracle(res)
     dev.set_host_partials_from_oracle(res)
     mfma = cfg.dtype == "bf16" and cfg.d == 128
-    for mode in ([(0, 0, 0), (2, 1, 16), (2, 4, 16), (2, 1, 8), (2, 3, 8), (3, 1, 8), (3, 2, 8), (2, 2, 4), (1, 2, 0)] if mfma else [(0, 0, 0), (1, 2, 0)]):
-        dev.out.zero_(); dev.lse.fill_(float("nan"))
+    dev.score()
+    want_scores = dev.scores.clone()
+    for mode in ([(0, 0, 0), (2, 1, 16), (2, 4, 16), (2, 1, 8), (2, 3, 8), (3, 1, 8), (3, 2, 8), (4, 1, 8), (2, 2, 4), (1, 2, 0)] if mfma else [(0, 0, 0), (1, 2, 0)]):
+        dev.out.zero_(); dev.lse.fill_(float("nan")); dev.scores.fill_(float("nan"))
         for t_ in (dev.sel_all, dev.sel_gpu, dev.slot_gpu, dev.sel_host, dev.n_gpu, dev.n_host):
             t_.fill_(-7)
         B.set_attn_mode(*mode)
@@ -253,6 +255,8 @@ def test_layer_step_end_to_end(cfg):
             dev.layer_step()
         finally:
             B.set_attn_mode(0, 0, 0)
+        # the scores the step hands back are score_blocks' own, bit for bit, whichever kernel made them
+        assert torch.equal(dev.scores.view(torch.int32), want_scores.view(torch.int32)), mode
         sel_all = dev.sel_all.cpu().numpy()
         sel_gpu, slot_gpu, sel_host = dev.sel_gpu.cpu().numpy(), dev.slot_gpu.cpu().numpy(), dev.sel_host.cpu().numpy()
         n_gpu, n_host = dev.n_gpu.cpu().numpy(), dev.n_host.cpu().numpy()
@@ -705,3 +709,28 @@ def test_determinism_same_bits_on_repeat():
         assert torch.equal(dev.out, a[0]) and torch.equal(dev.lse, a[1])
         assert torch.equal(dev.sel_all, a[2]) and torch.equal(dev.scores, a[3])
 
+
+
+def test_layer_step_without_scores():
+    """scores = NULL: a caller that does not want the scores gets the same lists and outputs, from the
+    launch that keeps them on the chip (one workgroup per pair) and from the split path (workspace)."""
+    cfg = W.shrink(W.qwen3_32b(B=2, ctx=8192))
+    wl, res, dev = setup(cfg)
+    dev.set_digest_from_oracle(res)
+    dev.set_host_partials_from_oracle(res)
+    for mode in ((2, 1, 8), (0, 0, 0)):
+        B.set_attn_mode(*mode)
+        try:
+            dev.layer_step()
+            want = [t.clone() for t in (dev.out, dev.lse, dev.sel_all, dev.sel_gpu, dev.slot_gpu, dev.sel_host, dev.n_gpu, dev.n_host)]
+            dev.out.zero_(); dev.sel_all.fill_(-7); dev.scores.fill_(float("nan"))
+            B.layer_step(dev.p, dev.q, dev.digest, dev.block_table, dev.k_pool, dev.v_pool, dev.n_slots, dev.host_o,
+                         dev.host_m, dev.host_l, None, dev.sel_all, dev.sel_gpu, dev.slot_gpu, dev.n_gpu, dev.sel_host,
+                         dev.n_host, dev.out, dev.lse, dev.ws)
+            dev.check_guards()
+        finally:
+            B.set_attn_mode(0, 0, 0)
+        got = (dev.out, dev.lse, dev.sel_all, dev.sel_gpu, dev.slot_gpu, dev.sel_host, dev.n_gpu, dev.n_host)
+        for a, b in zip(want, got):
+            assert torch.equal(a, b), mode
+        assert torch.isnan(dev.scores).all()      # not written
