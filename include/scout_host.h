@@ -40,7 +40,7 @@ typedef struct scout_host_problem {
  */
 int scout_host_create(int n_threads, scout_host_worker** out);
 
-/* Stop the threads and free the pool.  Waits for a job in flight. */
+/* Stop the threads and free the pool.  Waits for the jobs handed in (the running one and the one behind it). */
 void scout_host_destroy(scout_host_worker* w);
 
 /*
@@ -57,8 +57,11 @@ void scout_host_destroy(scout_host_worker* w);
  *   ctx_len   i32 [B]             tokens per sequence (masks a partial last block)
  *   o f32 [B][Hq][d], m f32 [B][Hq], l f32 [B][Hq]   out
  * Inputs are read in their stored type; products and sums are binary32.
- * Returns at once (0), the pairs being dealt to the threads; -1 on a bad
- * argument, -6 if a job is already in flight.  Indices outside
+ * Returns at once (0); -1 on a bad argument.  One job runs at a time, the
+ * pairs being dealt to the threads; ONE more may be handed in while it runs and
+ * starts when it ends (Alg. 1 spawns the job of layer i+1 before the GPU has
+ * merged layer i's); -6 if one is waiting already.  The arrays of a job must
+ * stay as they are until scout_host_wait has reported it.  Indices outside
  * [0, max_blocks) and blocks beyond the context are skipped.
  */
 int scout_host_submit(scout_host_worker* w, const scout_host_problem* p, const void* q,
@@ -81,22 +84,23 @@ int scout_host_submit(scout_host_worker* w, const scout_host_problem* p, const v
  *               call returns
  *   total_tiles out: tiles in the packed buffer, written before the call returns
  * Only p's B, Hkv, d, S, dtype, max_blocks and k are read.  Asynchronous like
- * scout_host_submit and sharing its single job slot: 0 once the work is dealt
- * (wait with scout_host_wait), -1 on a bad argument or a buffer too small, -6
- * if a job is already in flight.
+ * scout_host_submit and sharing its two places (one running, one behind it): 0
+ * once the work is handed in (wait with scout_host_wait), -1 on a bad argument or
+ * a buffer too small, -6 if a job is waiting already.
  */
 int scout_host_stage_recall(scout_host_worker* w, const scout_host_problem* p, const void* k_blocks,
                             const void* v_blocks, const int32_t* recall_blk, const int32_t* n_recall,
                             void* staged, size_t staged_bytes, int32_t* tile_off, int64_t* total_tiles);
 
 /*
- * Block until the submitted job is done (0), or return 0 at once if none is
- * in flight.  *seconds, if not NULL, receives the time from submit to the
- * last pair's completion.
+ * Block until the OLDEST job not yet reported is done (0): jobs are reported in
+ * the order they were handed in, one per call.  Returns 0 at once if none is
+ * outstanding.  *seconds, if not NULL, receives the time from the job's start
+ * on the threads to its last pair's completion (0 if none was outstanding).
  */
 int scout_host_wait(scout_host_worker* w, double* seconds);
 
-/* 1 if the job in flight has finished (or none is in flight), else 0.  Never blocks. */
+/* 1 if every job handed in has finished (or none was), else 0.  Never blocks. */
 int scout_host_done(scout_host_worker* w);
 
 #ifdef __cplusplus

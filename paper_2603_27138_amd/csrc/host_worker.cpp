@@ -99,13 +99,29 @@ struct scout_host_worker {
   std::mutex mu;
   std::condition_variable cv_job, cv_done;
   Job job;
+  // One job runs; one more may wait behind it (Alg. 1 spawns layer i+1's job while layer i's may still
+  // be running).  The thread that finishes a job's last pair starts the queued one.  All under `mu`.
+  Job queued;
+  bool has_queued = false;
+  uint64_t submitted = 0, completed = 0, waited = 0;  // jobs handed in, finished, reported by wait()
+  std::chrono::steady_clock::time_point t_start[2], t_end[2];  // of job number n, at n % 2
   std::atomic<uint64_t> generation{0};  // bumped at every submit
   std::atomic<uint64_t> ticket{0};      // (generation << 32) | next pair: a thread still leaving the
                                         // previous job can never take a pair of the next one
   std::atomic<int> pairs_left{0};
   std::atomic<bool> stop{false};
   std::atomic<bool> in_flight{false};
-  std::chrono::steady_clock::time_point t_submit, t_done;
+
+  // Make J the running job.  Caller holds `mu` and notifies cv_job afterwards.
+  void start_locked(const Job& J, uint64_t number) {
+    job = J;
+    pairs_left.store(J.pairs, std::memory_order_relaxed);
+    in_flight.store(true, std::memory_order_release);
+    t_start[number & 1] = std::chrono::steady_clock::now();
+    const uint64_t gen = generation.load(std::memory_order_relaxed) + 1;
+    ticket.store((gen & 0xffffffffu) << 32, std::memory_order_release);
+    generation.store(gen, std::memory_order_release);
+  }
 
   void loop() {
     std::vector<float> kf((size_t)(kMaxS + 4) * kMaxD), vf((size_t)kMaxS * kMaxD);
@@ -136,31 +152,46 @@ struct scout_host_worker {
         const int pair = (int)(t & 0xffffffffu);
         run_pair(J, pair, kf.data(), vf.data());
         if (pairs_left.fetch_sub(1, std::memory_order_acq_rel) == 1) {
-          t_done = std::chrono::steady_clock::now();
+          const auto now = std::chrono::steady_clock::now();
+          bool next = false;
           {
             std::lock_guard<std::mutex> lk(mu);
-            in_flight.store(false, std::memory_order_release);
+            t_end[completed & 1] = now;
+            ++completed;
+            if (has_queued) {  // the job that waited behind this one starts now
+              has_queued = false;
+              start_locked(queued, completed);
+              next = true;
+            } else {
+              in_flight.store(false, std::memory_order_release);
+            }
           }
           cv_done.notify_all();
+          if (next) cv_job.notify_all();
         }
       }
     }
   }
 };
 
-// Hand a job to the threads (the caller has checked that none is in flight).
-static void publish(scout_host_worker* w, const Job& J) {
+// Hand a job to the threads: it starts at once if none is running, else it waits behind the running
+// one.  -6 if one is waiting already.
+static int publish(scout_host_worker* w, const Job& J) {
+  bool started = false;
   {
     std::lock_guard<std::mutex> lk(w->mu);
-    w->job = J;
-    w->pairs_left.store(J.pairs, std::memory_order_relaxed);
-    w->in_flight.store(true, std::memory_order_release);
-    w->t_submit = std::chrono::steady_clock::now();
-    const uint64_t gen = w->generation.load(std::memory_order_relaxed) + 1;
-    w->ticket.store((gen & 0xffffffffu) << 32, std::memory_order_release);
-    w->generation.store(gen, std::memory_order_release);
+    if (w->in_flight.load(std::memory_order_acquire)) {
+      if (w->has_queued) return -6;
+      w->queued = J;
+      w->has_queued = true;
+    } else {
+      w->start_locked(J, w->submitted);
+      started = true;
+    }
+    ++w->submitted;
   }
-  w->cv_job.notify_all();
+  if (started) w->cv_job.notify_all();
+  return 0;
 }
 
 extern "C" {
@@ -182,6 +213,7 @@ int scout_host_create(int n_threads, scout_host_worker** out) {
 void scout_host_destroy(scout_host_worker* w) {
   if (w == nullptr) return;
   scout_host_wait(w, nullptr);
+  scout_host_wait(w, nullptr);  // and the one that waited behind it
   {
     std::lock_guard<std::mutex> lk(w->mu);
     w->stop.store(true, std::memory_order_release);
@@ -199,7 +231,6 @@ int scout_host_submit(scout_host_worker* w, const scout_host_problem* p, const v
   if (p->B < 0 || p->Hq < 1 || p->Hkv < 1 || p->Hq % p->Hkv != 0 || p->Hq / p->Hkv > kMaxG) return -1;
   if (p->d < 8 || p->d % 8 != 0 || p->d > kMaxD || p->S < 1 || p->S > kMaxS) return -1;
   if ((p->dtype != 0 && p->dtype != 1) || p->max_blocks < 0 || p->k < 0) return -1;
-  if (w->in_flight.load(std::memory_order_acquire)) return -6;
   Job J;
   J.p = *p;
   J.q = q; J.kb = k_blocks; J.vb = v_blocks; J.sel = sel_host; J.n = n_host; J.ctx = ctx_len;
@@ -207,8 +238,7 @@ int scout_host_submit(scout_host_worker* w, const scout_host_problem* p, const v
   J.scale = p->sm_scale != 0.0f ? p->sm_scale : 1.0f / std::sqrt((float)p->d);
   J.pairs = p->B * p->Hkv;
   if (J.pairs == 0) return 0;
-  publish(w, J);
-  return 0;
+  return publish(w, J);
 }
 
 int scout_host_stage_recall(scout_host_worker* w, const scout_host_problem* p, const void* k_blocks,
@@ -218,7 +248,10 @@ int scout_host_stage_recall(scout_host_worker* w, const scout_host_problem* p, c
   if (p->B < 0 || p->Hkv < 1 || p->d < 1 || p->S < 1 || (p->dtype != 0 && p->dtype != 1) || p->max_blocks < 0 ||
       p->k < 0)
     return -1;
-  if (w->in_flight.load(std::memory_order_acquire)) return -6;
+  {
+    std::lock_guard<std::mutex> lk(w->mu);  // tile_off is written below: refuse before touching it
+    if (w->in_flight.load(std::memory_order_acquire) && w->has_queued) return -6;
+  }
   const int pairs = p->B * p->Hkv;
   const size_t tile = (size_t)p->S * p->d * (p->dtype == 1 ? 2 : 4);
   int64_t total = 0;
@@ -238,22 +271,39 @@ int scout_host_stage_recall(scout_host_worker* w, const scout_host_problem* p, c
   J.staged = static_cast<char*>(staged);
   J.tile_off = tile_off;
   J.pairs = pairs;
-  publish(w, J);
-  return 0;
+  return publish(w, J);
 }
 
 int scout_host_wait(scout_host_worker* w, double* seconds) {
   if (w == nullptr) return -1;
-  // spin first: the caller usually arrives when the job is nearly done
-  for (int spin = 0; spin < 20000 && w->in_flight.load(std::memory_order_acquire); ++spin) __builtin_ia32_pause();
-  if (w->in_flight.load(std::memory_order_acquire)) {
-    std::unique_lock<std::mutex> lk(w->mu);
-    w->cv_done.wait(lk, [&] { return !w->in_flight.load(); });
+  uint64_t mine;
+  {
+    std::lock_guard<std::mutex> lk(w->mu);
+    if (w->waited == w->submitted) {  // nothing outstanding
+      if (seconds != nullptr) *seconds = 0.0;
+      return 0;
+    }
+    mine = w->waited;
   }
-  if (seconds != nullptr) *seconds = std::chrono::duration<double>(w->t_done - w->t_submit).count();
+  // the oldest job not yet reported.  Spin first: the caller usually arrives when it is nearly done
+  auto finished = [&] {
+    std::lock_guard<std::mutex> lk(w->mu);
+    return w->completed > mine;
+  };
+  bool ok = false;
+  for (int spin = 0; spin < 2000 && !(ok = finished()); ++spin)
+    for (int i = 0; i < 10; ++i) __builtin_ia32_pause();
+  std::unique_lock<std::mutex> lk(w->mu);
+  if (!ok) w->cv_done.wait(lk, [&] { return w->completed > mine; });
+  if (seconds != nullptr) *seconds = std::chrono::duration<double>(w->t_end[mine & 1] - w->t_start[mine & 1]).count();
+  w->waited = mine + 1;
   return 0;
 }
 
-int scout_host_done(scout_host_worker* w) { return w == nullptr || !w->in_flight.load(std::memory_order_acquire) ? 1 : 0; }
+int scout_host_done(scout_host_worker* w) {
+  if (w == nullptr) return 1;
+  std::lock_guard<std::mutex> lk(w->mu);
+  return w->completed == w->submitted ? 1 : 0;
+}
 
 }  // extern "C"

@@ -62,14 +62,15 @@ class HostWorker:
         rc = lib().scout_host_create(int(n_threads), ctypes.byref(self._h))
         if rc != 0:
             raise RuntimeError(f"scout_host_create failed ({rc})")
-        self._keep = None
+        self._keep = []      # the arrays of the jobs handed in and not yet waited for
 
     def submit(self, p: HostProblem, q, k_blocks, v_blocks, sel_host, n_host, ctx_len, o, m, l):
         args = (q, k_blocks, v_blocks, sel_host, n_host, ctx_len, o, m, l)
         rc = lib().scout_host_submit(self._h, ctypes.byref(p), *[_addr(a) for a in args])
         if rc != 0:
             raise RuntimeError(f"scout_host_submit failed ({rc})")
-        self._keep = (p,) + args
+        if p.B * p.Hkv > 0:
+            self._keep.append((p,) + args)
 
     def stage_recall(self, p: HostProblem, k_blocks, v_blocks, recall_blk, n_recall, staged, tile_off) -> int:
         """Starts packing the tiles a recall plan names into `staged` (Sec. 3.4); tile_off is filled before
@@ -81,16 +82,19 @@ class HostWorker:
                                            _addr(tile_off), ctypes.byref(total))
         if rc != 0:
             raise RuntimeError(f"scout_host_stage_recall failed ({rc})")
-        self._keep = (p, k_blocks, v_blocks, recall_blk, n_recall, staged, tile_off)
+        if total.value:
+            self._keep.append((p, k_blocks, v_blocks, recall_blk, n_recall, staged, tile_off))
         return total.value
 
     def wait(self) -> float:
-        """Blocks until the job is done; returns seconds from submit to completion."""
+        """Blocks until the oldest job not yet waited for is done (up to two may be outstanding: one
+        running, one behind it); returns the seconds it ran."""
         sec = ctypes.c_double(0.0)
         rc = lib().scout_host_wait(self._h, ctypes.byref(sec))
         if rc != 0:
             raise RuntimeError(f"scout_host_wait failed ({rc})")
-        self._keep = None
+        if self._keep:
+            self._keep.pop(0)
         return sec.value
 
     def done(self) -> bool:

@@ -188,19 +188,23 @@ class LayerAheadPipeline:
             self._attend(i, qs[i])
             if self.filler is not None:
                 self.filler(i)
+            # Algorithm 1 spawns the host's job for layer i+1 as soon as its blocks are chosen, beside
+            # this layer's GPU attention: here, once this layer's GPU work is queued (the enqueueing
+            # thread then waits for the selection, which the GPU finished before it began the attention).
+            # The worker takes the job behind the one of layer i if that is still running.
+            if host and i + 1 < n:
+                self._spawn(i + 1)
             if pending is not None:           # the GPU has this layer's work queued: now see to the last one's tiles
                 self._move_recall(pending)
                 pending = None
             if host:
                 t0 = time.perf_counter()
-                self.host_seconds.append(self.worker.wait())
+                self.host_seconds.append(self.worker.wait())      # the oldest job: layer i's
                 self.wait_seconds.append(time.perf_counter() - t0)
             self._merge(i)
             if due:
                 self._plan_recall(i, qs[i])
                 pending = i
-            if host and i + 1 < n:
-                self._spawn(i + 1)
         if pending is not None:
             self._move_recall(pending)
         self.step_no += 1

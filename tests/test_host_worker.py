@@ -96,16 +96,25 @@ def test_host_worker_many_jobs_back_to_back_and_busy_refusal():
             case = _case("bf16", *shape, seed=it)
             out = _run(w, "bf16", *shape, *case)
             _check("bf16", *shape, *case, *out)
-        # a second submit while one is in flight is refused, not queued
+        # one job may wait behind the running one (see the test of two outstanding jobs below); a further
+        # one is refused
         shape = (64, 8, 8, 128, 32, 40, 40)
         ctx, q, kb, vb, sel, n = _case("bf16", *shape, seed=99, ctx=[40 * 32] * 64)
         p = H.HostProblem(*shape[:5], H.BF16, shape[5], shape[6], 0.0)
         o = np.zeros((64, 8, 128), np.float32); m = np.zeros((64, 8), np.float32); l = np.zeros((64, 8), np.float32)
+        o2, m2, l2 = o.copy(), m.copy(), l.copy()
         w.submit(p, q, kb, vb, sel, n, ctx, o, m, l)
+        w.submit(p, q, kb, vb, sel, n, ctx, o2, m2, l2)
         if not w.done():
-            with pytest.raises(RuntimeError):
-                w.submit(p, q, kb, vb, sel, n, ctx, o, m, l)
+            o3, m3, l3 = o.copy(), m.copy(), l.copy()
+            try:
+                w.submit(p, q, kb, vb, sel, n, ctx, o3, m3, l3)
+                w.wait()                       # the first job had ended meanwhile: three to wait for
+            except RuntimeError as e:
+                assert "-6" in str(e)
         w.wait()
+        w.wait()
+        assert w.done() and np.array_equal(o, o2) and np.array_equal(l, l2)
     finally:
         w.close()
 
@@ -182,3 +191,45 @@ def test_stage_recall_rejects_a_short_buffer_and_takes_an_empty_plan():
         assert off.tolist() == [0, 1]
     finally:
         w.close()
+
+
+def test_two_jobs_outstanding_are_run_in_order_and_a_third_is_refused():
+    """Alg. 1 spawns layer i+1's host job while layer i's may still be running: the worker takes one job
+    behind the running one, wait() reports them oldest first, and both give what they give alone."""
+    dims = dict(dtype="bf16", B=3, Hq=8, Hkv=2, d=128, S=32, mb=48, k=20)
+    cases = [_case(seed=s, **dims) for s in (21, 22, 23)]
+    worker = H.HostWorker(3)
+    try:
+        alone = [_run(worker, **dims, **dict(zip(("ctx", "q", "kb", "vb", "sel", "n"), c))) for c in cases]
+        p = H.HostProblem(dims["B"], dims["Hq"], dims["Hkv"], dims["d"], dims["S"], H.BF16, dims["mb"], dims["k"], 0.0)
+        outs = []
+        for rounds in range(20):                      # many times: the hand-over between jobs is a race if it is wrong
+            outs = []
+            for c in cases[:2]:
+                ctx, q, kb, vb, sel, n = c
+                o = np.full((dims["B"], dims["Hq"], dims["d"]), np.nan, dtype=np.float32)
+                m = np.full((dims["B"], dims["Hq"]), np.nan, dtype=np.float32)
+                l = np.full((dims["B"], dims["Hq"]), np.nan, dtype=np.float32)
+                worker.submit(p, q, kb, vb, sel, n, ctx, o, m, l)
+                outs.append((o, m, l))
+            # a third job while one may be running and one waits: refused, unless the first is done already
+            ctx, q, kb, vb, sel, n = cases[2]
+            o3 = np.zeros((dims["B"], dims["Hq"], dims["d"]), dtype=np.float32)
+            m3, l3 = np.zeros((dims["B"], dims["Hq"]), dtype=np.float32), np.zeros((dims["B"], dims["Hq"]), dtype=np.float32)
+            try:
+                worker.submit(p, q, kb, vb, sel, n, ctx, o3, m3, l3)
+                third = True
+            except RuntimeError as e:
+                assert "-6" in str(e)
+                third = False
+            assert worker.wait() >= 0.0 and worker.wait() >= 0.0
+            if third:
+                worker.wait()
+            assert worker.done()
+            for (o, m, l), (wo, wm, wl) in zip(outs, alone[:2]):
+                assert np.array_equal(o, wo) and np.array_equal(m, wm) and np.array_equal(l, wl)
+            if third:
+                assert np.array_equal(o3, alone[2][0])
+        assert worker.wait() == 0.0                   # nothing outstanding: returns at once
+    finally:
+        worker.close()
