@@ -22,8 +22,11 @@ STATIC_SCRATCH_BYTES = 8 << 20
 
 EXPORTS = ["scout_version", "scout_strerror", "scout_workspace_bytes", "build_digests", "append_token", "score_blocks",
            "select_topk", "sparse_decode_attn", "merge_partials", "periodic_recall", "recall_fetch", "recall_scatter",
-           "scout_layer_step", "scout_set_attn_mode", "scout_calib_copy", "scout_attn_partials",
-           "scout_calib_read", "scout_calib_gather", "scout_attn_finish", "sparse_decode_attn_static"]
+           "scout_layer_step", "scout_set_attn_mode", "scout_attn_partials", "scout_attn_finish",
+           "sparse_decode_attn_static"]
+# measurement aids live in a library of their own (include/scout_calib.h)
+CALIB_LIB_PATH = os.path.join(_HERE, "libscout_calib.so")
+CALIB_EXPORTS = ["scout_calib_copy", "scout_calib_read", "scout_calib_gather"]
 
 
 class ScoutError(RuntimeError):
@@ -69,9 +72,6 @@ def lib():
         L.periodic_recall.argtypes = [pp] + [vp] * 8 + [sz, vp]
         L.recall_fetch.argtypes = [pp] + [vp] * 7 + [i64, vp]
         L.recall_scatter.argtypes = [pp, vp, i64] + [vp] * 6 + [i64, vp]
-        L.scout_calib_copy.argtypes = [vp, vp, sz, vp]
-        L.scout_calib_read.argtypes = [vp, sz, vp, vp]
-        L.scout_calib_gather.argtypes = [pp, vp, vp, i64, vp, vp, vp, vp]
         L.scout_attn_partials.argtypes = [pp, vp, vp, vp, i64] + [vp] * 4 + [sz, vp]
         L.scout_attn_finish.argtypes = [pp] + [vp] * 6 + [sz, vp]
         L.scout_layer_step.argtypes = [pp, vp, vp, vp, vp, vp, i64] + [vp] * 13 + [sz, vp]
@@ -80,6 +80,26 @@ def lib():
                 getattr(L, name).restype = getattr(L, name).restype or ctypes.c_int
         _lib = L
     return _lib
+
+
+_calib = None
+
+
+def calib_lib():
+    """The measurement aids (copy of known size, bare stream, bare gather): benchmarks and profiling only."""
+    global _calib
+    if _calib is None:
+        if not os.path.exists(CALIB_LIB_PATH):
+            raise FileNotFoundError(f"{CALIB_LIB_PATH} is missing: build it first (python -m paper_2603_27138_amd.build)")
+        L = ctypes.CDLL(CALIB_LIB_PATH)
+        vp, sz, i64 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int64
+        L.scout_calib_copy.argtypes = [vp, vp, sz, vp]
+        L.scout_calib_read.argtypes = [vp, sz, vp, vp]
+        L.scout_calib_gather.argtypes = [ctypes.POINTER(Problem), vp, vp, i64, vp, vp, vp, vp]
+        for name in CALIB_EXPORTS:
+            getattr(L, name).restype = ctypes.c_int
+        _calib = L
+    return _calib
 
 
 def _check(fn: str, rc: int):
@@ -179,7 +199,7 @@ def alloc_workspace(p: Problem, device="cuda") -> torch.Tensor:
 
 def calib_copy(src: torch.Tensor, dst: torch.Tensor):
     n = src.numel() * src.element_size()
-    _call("scout_calib_copy", lib().scout_calib_copy, _ptr(src), _ptr(dst), n, _stream())
+    _call("scout_calib_copy", calib_lib().scout_calib_copy, _ptr(src), _ptr(dst), n, _stream())
 
 
 def build_digests(p: Problem, k_blocks, digest):
@@ -258,11 +278,11 @@ def recall_scatter(p: Problem, staged, tile_off, recall_blk, recall_slot, n_reca
 
 
 def calib_read(src, nbytes: int, sink=None):
-    _call("scout_calib_read", lib().scout_calib_read, _ptr(src), int(nbytes), _ptr(sink), _stream())
+    _call("scout_calib_read", calib_lib().scout_calib_read, _ptr(src), int(nbytes), _ptr(sink), _stream())
 
 
 def calib_gather(p: Problem, k_pool, v_pool, n_slots, slot_gpu, n_gpu, sink=None):
-    _call("scout_calib_gather", lib().scout_calib_gather, ctypes.byref(p), _ptr(k_pool), _ptr(v_pool), int(n_slots),
+    _call("scout_calib_gather", calib_lib().scout_calib_gather, ctypes.byref(p), _ptr(k_pool), _ptr(v_pool), int(n_slots),
           _ptr(slot_gpu), _ptr(n_gpu), _ptr(sink), _stream())
 
 

@@ -18,10 +18,12 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False) -> str:
-    """Compile every kernel source into libscout.so next to this file; returns its path."""
+CALIB_LIB = os.path.join(HERE, "libscout_calib.so")
+
+
+def _hipcc(sources, out, verbose):
     cmd = ["hipcc", *FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+           *[os.path.join(CSRC, s) for s in sources], "-o", out]
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(ln for ln in res.stderr.splitlines() if noise not in ln)
@@ -29,7 +31,14 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err)
-    return LIB
+    return out
+
+
+def build(verbose: bool = False) -> str:
+    """Compile every kernel source into libscout.so next to this file (and the measurement aids into
+    libscout_calib.so, a library of their own); returns the path of libscout.so."""
+    _hipcc(["calib.hip"], CALIB_LIB, verbose)
+    return _hipcc(SOURCES, LIB, verbose)
 
 
 HOST_LIB = os.path.join(HERE, "libscout_host.so")

@@ -15,7 +15,7 @@ def pytest_configure(config):
 def pytest_sessionstart(session):
     """The libraries are built beforehand; build here only what is missing (a fresh checkout)."""
     from paper_2603_27138_amd import build
-    if not os.path.exists(build.LIB):
+    if not os.path.exists(build.LIB) or not os.path.exists(build.CALIB_LIB):
         build.build()
     if not os.path.exists(build.HOST_LIB):
         build.build_host()

@@ -38,6 +38,21 @@ def test_every_declared_symbol_is_exported(lib):
     assert L.scout_strerror(-1) == b"invalid argument"
 
 
+def test_calibration_library_is_separate_and_exports_its_header(lib):
+    """The measurement aids are not in the product library: libscout.so exports none of them, and
+    libscout_calib.so exports what include/scout_calib.h declares."""
+    text = open(os.path.join(ROOT, "include", "scout_calib.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    syms = sorted(set(re.findall(r"\bint\s+(scout_calib_\w+)\s*\(", text)))
+    assert syms == sorted(lib.CALIB_EXPORTS) and len(syms) == 3
+    for s_ in syms:
+        assert hasattr(lib.calib_lib(), s_), s_
+        assert not hasattr(lib.lib(), s_), s_
+    assert lib.calib_lib().scout_calib_copy(None, None, 16, None) == lib.EINVAL
+    assert lib.calib_lib().scout_calib_read(FAKE, 24, None, None) == lib.EINVAL
+    assert lib.calib_lib().scout_calib_gather(None, FAKE, FAKE, 4, FAKE, FAKE, None, None) == lib.EINVAL
+
+
 def test_host_library_exports_every_declared_symbol():
     from paper_2603_27138_amd import build, host
     if not os.path.exists(build.HOST_LIB):
@@ -140,3 +155,24 @@ def test_static_scratch_entry_point_rejects_on_the_host(lib):
     assert lib.STATIC_SCRATCH_BYTES == 8 << 20
     text = open(os.path.join(ROOT, "include", "scout.h")).read()
     assert "#define SCOUT_STATIC_SCRATCH_BYTES (8u << 20)" in text
+
+
+def test_attention_mode_belongs_to_the_calling_thread(lib):
+    """scout_set_attn_mode in one thread leaves every other thread's setting alone (observable without a
+    GPU: the fp32 problem that is too large for the static scratch is refused as unsupported where the
+    MFMA family is forced, and for its size where the choice is automatic)."""
+    import threading
+    L = lib.lib()
+    big = _problem(lib, B=64, Hq=128, Hkv=8, dtype=lib.F32)
+    args = [FAKE, FAKE, FAKE, 10, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE]
+    seen = {}
+
+    def other():
+        assert L.scout_set_attn_mode(2, 0, 0) == 0
+        seen["forced"] = L.sparse_decode_attn_static(ctypes.byref(big), *args, None)
+
+    t = threading.Thread(target=other)
+    t.start()
+    t.join()
+    assert seen["forced"] == lib.EUNSUPPORTED
+    assert L.sparse_decode_attn_static(ctypes.byref(big), *args, None) == lib.ESCRATCH
