@@ -249,12 +249,17 @@ __device__ __forceinline__ void load_q(u32x4 (&qreg)[4], const Dims& D, const ui
 
 // The attention of one workgroup: its share (split) of the pair's list, folded over the waves
 // through LDS, then the epilogue.  sel / slot_list: the pair's list in global memory or LDS.
-template <int WAVES, int DEPTH>
+// PRIVATE: the wave holds its own list entries in registers instead (lane j: the entry of the wave's
+// j-th unit, units dealt to the pair's waves in stride: v, v + waves, ...), fetched by the wave
+// itself in the same trip as the count: no staging through LDS and no barrier before the first tile
+// request.  At most 64 units per wave; sel / slot_list are not read.
+template <int WAVES, int DEPTH, bool PRIVATE = false>
 __device__ __forceinline__ void attend_pair(const Dims& D, int b, int g, int split, const u32x4 (&qreg)[4],
                                             const uint16_t* __restrict__ k_pool,
                                             const uint16_t* __restrict__ v_pool, long long n_slots,
                                             const int32_t* sel, const int32_t* slot_list, int n, int ctx,
-                                            const Partials& P, const Epilogue& E, float* smem) {
+                                            const Partials& P, const Epilogue& E, float* smem, int my_sel = -1,
+                                            int my_slot = -1) {
   // per wave: [G][132] floats of o (padded rows), then m[16], l[16]
   constexpr int ROW = kMfmaD + 4;
   const int pair = b * D.Hkv + g;
@@ -291,20 +296,51 @@ __device__ __forceinline__ void attend_pair(const Dims& D, int b, int g, int spl
   // consumed.  Measured at the benchmark shapes, one unit in flight per wave with eight waves per
   // workgroup (64 KiB requested per compute unit at any time) beats two, three and four (17.0, 17.4,
   // 17.7 and 19.0 us for 64.5 MiB of tiles).
-  UnitRegs buf[DEPTH];
-  Entry ent[DEPTH];
-#pragma unroll
-  for (int d = 0; d < DEPTH; ++d) {
-    ent[d] = read_entry(sel, slot_list, u0 + d, u1, ush, S, ctx, n_slots);
-    issue_unit(buf[d], k_pool, v_pool, ent[d], ln, kg);
-  }
-  for (int u = u0; u < u1; u += DEPTH) {
+  if constexpr (PRIVATE) {
+    static_assert(DEPTH == 1, "one unit in flight");
+    // unit v + j * n_waves of the pair is this wave's j-th; its list entry sits in lane j
+    auto entry = [&](int j, int u) {
+      Entry e{0, 0};
+      if (u < n_units) {
+        const int bj = __builtin_amdgcn_readlane(my_sel, j);
+        const long long slot = __builtin_amdgcn_readlane(my_slot, j);
+        const int sub = u & ((1 << ush) - 1);
+        int valid = ctx - bj * S - sub * kUnitTokens;
+        valid = valid > kUnitTokens ? kUnitTokens : valid;
+        if (bj >= 0 && valid > 0 && slot >= 0 && slot < n_slots) {
+          e.elem_off = ((size_t)slot * S + sub * kUnitTokens) * kMfmaD;
+          e.valid = valid;
+        }
+      }
+      return e;
+    };
+    UnitRegs b0;
+    Entry e0 = entry(0, v);
+    issue_unit(b0, k_pool, v_pool, e0, ln, kg);
+    int j = 0;
+    for (int u = v; u < n_units; u += n_waves) {
+      ++j;
+      const Entry nx = entry(j, u + n_waves);
+      consume_unit(W, b0, qreg, e0.valid, scale2, kg);
+      e0 = nx;
+      issue_unit(b0, k_pool, v_pool, nx, ln, kg);
+    }
+  } else {
+    UnitRegs buf[DEPTH];
+    Entry ent[DEPTH];
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) {
-      const Entry nx = read_entry(sel, slot_list, u + d + DEPTH, u1, ush, S, ctx, n_slots);
-      consume_unit(W, buf[d], qreg, ent[d].valid, scale2, kg);
-      ent[d] = nx;
-      issue_unit(buf[d], k_pool, v_pool, nx, ln, kg);
+      ent[d] = read_entry(sel, slot_list, u0 + d, u1, ush, S, ctx, n_slots);
+      issue_unit(buf[d], k_pool, v_pool, ent[d], ln, kg);
+    }
+    for (int u = u0; u < u1; u += DEPTH) {
+#pragma unroll
+      for (int d = 0; d < DEPTH; ++d) {
+        const Entry nx = read_entry(sel, slot_list, u + d + DEPTH, u1, ush, S, ctx, n_slots);
+        consume_unit(W, buf[d], qreg, ent[d].valid, scale2, kg);
+        ent[d] = nx;
+        issue_unit(buf[d], k_pool, v_pool, nx, ln, kg);
+      }
     }
   }
   f32x4(&acc)[8] = W.acc;
@@ -423,6 +459,35 @@ __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
   load_q(qreg, D, q, b, g, lane & 15, lane >> 4);
   __syncthreads();
   attend_pair<WAVES, DEPTH>(D, b, g, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, n, ctx, P, E, smem);
+}
+
+// The same attention with the list entries fetched by the waves themselves (see attend_pair, PRIVATE):
+// used when no wave can have more than 64 units.  Without the staging of the list through LDS and its
+// barrier the first tile request leaves one trip to memory after the wave started: 16.4 us against
+// 17.0 us for config 3's 64.5 MiB of tiles (config 2: 10.4 against 10.9, config 5: 30.0 against 30.6).
+template <int WAVES>
+__global__ __launch_bounds__(WAVES* kWave) void attn_mfma_private_kernel(
+    Dims D, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_pool,
+    const uint16_t* __restrict__ v_pool, long long n_slots, const int32_t* __restrict__ sel_gpu,
+    const int32_t* __restrict__ slot_gpu, const int32_t* __restrict__ n_gpu, Partials P, Epilogue E) {
+  extern __shared__ float smem[];
+  const int b = blockIdx.z, g = blockIdx.y, pair = grid_pair(), split = blockIdx.x;
+  const int lane = lane_id();
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const size_t list0 = (size_t)pair * D.k;
+  const int n_waves = P.nsplit * WAVES, v = split * WAVES + wave;
+  const int e = (v + lane * n_waves) >> (D.s_shift - 4);  // the block of this wave's unit number `lane`
+  int my_sel = -1, my_slot = -1;
+  if (e < D.k) {
+    my_sel = sel_gpu[list0 + e];
+    my_slot = slot_gpu[list0 + e];
+  }
+  const int n = n_gpu[pair];
+  const int ctx = D.ctx_len[b];
+  u32x4 qreg[4];
+  load_q(qreg, D, q, b, g, lane & 15, lane >> 4);
+  attend_pair<WAVES, 1, true>(D, b, g, split, qreg, k_pool, v_pool, n_slots, nullptr, nullptr, n, ctx, P, E, smem,
+                              my_sel, my_slot);
 }
 
 // Selection and attention of a pair in one launch (the non-pipelined description of Sec. 3.2:
@@ -920,8 +985,12 @@ int launch_attn(const Dims& D, int dtype, int family, int waves, const void* q, 
     // units in flight per wave: few.  Requests that only queue in the memory system buy nothing (a
     // compute unit's loads return in the order they were issued), and fewer registers leave room for
     // the next workgroup to start its head while this one folds.
+    const long long units_per_wave = (((long long)D.k * (D.S / kUnitTokens)) + P.nsplit * waves - 1) / (P.nsplit * waves);
     if (waves == 16)
       SCOUT_ATTN(16, 1);
+    else if (waves == 8 && units_per_wave <= 64)
+      hipLaunchKernelGGL((attn_mfma_private_kernel<8>), grid, block, mfma_smem_bytes(D, 8), st, D, q16, k16, v16, n_slots,
+                         sel_gpu, slot_gpu, n_gpu, P, E);
     else if (waves == 8)
       SCOUT_ATTN(8, 1);
     else if (waves == 4)

@@ -360,15 +360,25 @@ def test_always_kept_blocks(cfg, n_sink, n_tail):
         for j in [j for j in range(nb) if kept[j]][:cfg.k]:
             assert j in got_sel[b, g]
     assert score_off <= 2
-    B.layer_step(p2, dev.q, dev.digest, dev.block_table, dev.k_pool, dev.v_pool, dev.n_slots, dev.host_o, dev.host_m,
-                 dev.host_l, dev.scores, dev.sel_all, dev.sel_gpu, dev.slot_gpu, dev.n_gpu, dev.sel_host, dev.n_host,
-                 dev.out, dev.lse, dev.ws)
-    got_sel = dev.sel_all.cpu().numpy()
-    for (b, g), op in res.items():
-        if not np.array_equal(got_sel[b, g], want[(b, g)]):
-            assert gap[(b, g)] < 1e-6, (b, g)
-            excused += 1
-    assert harness.few(excused, 2 * len(res)), excused
+    want_scores = dev.scores.clone()
+    # through the step: the automatic launches, and one workgroup per pair (the single-launch kernel where it applies)
+    modes = [(0, 0, 0), (2, 1, 8)] if cfg.dtype == "bf16" and cfg.d == 128 else [(0, 0, 0)]
+    for mode in modes:
+        dev.sel_all.fill_(-7); dev.scores.fill_(float("nan"))
+        B.set_attn_mode(*mode)
+        try:
+            B.layer_step(p2, dev.q, dev.digest, dev.block_table, dev.k_pool, dev.v_pool, dev.n_slots, dev.host_o, dev.host_m,
+                         dev.host_l, dev.scores, dev.sel_all, dev.sel_gpu, dev.slot_gpu, dev.n_gpu, dev.sel_host, dev.n_host,
+                         dev.out, dev.lse, dev.ws)
+        finally:
+            B.set_attn_mode(0, 0, 0)
+        assert torch.equal(dev.scores.view(torch.int32), want_scores.view(torch.int32)), mode
+        got_sel = dev.sel_all.cpu().numpy()
+        for (b, g), op in res.items():
+            if not np.array_equal(got_sel[b, g], want[(b, g)]):
+                assert gap[(b, g)] < 1e-6, (b, g)
+                excused += 1
+    assert harness.few(excused, 3 * len(res)), excused
 
 
 def test_group_max_aggregation(cfg):
@@ -473,6 +483,19 @@ def test_per_head_selection(cfg):
                  sel_gpu, slot_gpu, n_gpu, sel_host, n_host, dev.out, dev.lse, ws)
     torch.cuda.synchronize()
     check("layer step")
+    if cfg.dtype == "bf16" and cfg.d == 128:      # one workgroup per head: the single-launch kernel where it applies
+        for t in (scores, dev.out):
+            t.zero_()
+        for t in (sel_all, sel_gpu, slot_gpu, sel_host, n_gpu, n_host):
+            t.fill_(-7)
+        B.set_attn_mode(2, 1, 8)
+        try:
+            B.layer_step(p2, dev.q, dev.digest, dev.block_table, dev.k_pool, dev.v_pool, dev.n_slots, *host, scores, sel_all,
+                         sel_gpu, slot_gpu, n_gpu, sel_host, n_host, dev.out, dev.lse, ws)
+        finally:
+            B.set_attn_mode(0, 0, 0)
+        torch.cuda.synchronize()
+        check("layer step, one workgroup per head")
     # a recall plans for the KV head: not defined with a selection per query head
     with pytest.raises(B.ScoutError):
         B.periodic_recall(p2, dev.q, dev.digest, dev.block_table, dev.recall_blk, dev.recall_slot, dev.evict_blk,
