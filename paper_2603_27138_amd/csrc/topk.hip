@@ -140,6 +140,11 @@ __global__ __launch_bounds__(WAVES* kWave) void recall_kernel(
 
 // ------------------------------------------------------------ host launchers
 
+// Waves per pair and keys per lane by row length.  Few keys per lane and many waves win although the
+// waves then exchange through LDS: a wave with 16 keys per lane issues its ballots one after the
+// other (1024 blocks: 4.6 us with 8 waves x 2 keys against 8.9 us with one wave x 16; 4096 blocks:
+// 6.0 us with 16 waves x 4 against 9.3 us with 4 waves x 16).
+
 #define SCOUT_TOPK_DISPATCH(KERNEL, ...)                                                     \
   do {                                                                                       \
     dim3 grid(1, D.Hkv, D.B);                                                                   \
@@ -147,9 +152,9 @@ __global__ __launch_bounds__(WAVES* kWave) void recall_kernel(
     if (D.max_blocks <= 256)                                                                 \
       hipLaunchKernelGGL((KERNEL<1, 4>), grid, dim3(kWave), 0, st, __VA_ARGS__);             \
     else if (D.max_blocks <= 1024)                                                           \
-      hipLaunchKernelGGL((KERNEL<1, 16>), grid, dim3(kWave), 0, st, __VA_ARGS__);            \
+      hipLaunchKernelGGL((KERNEL<8, 2>), grid, dim3(8 * kWave), 0, st, __VA_ARGS__);         \
     else if (D.max_blocks <= 4096)                                                           \
-      hipLaunchKernelGGL((KERNEL<4, 16>), grid, dim3(4 * kWave), 0, st, __VA_ARGS__);        \
+      hipLaunchKernelGGL((KERNEL<16, 4>), grid, dim3(16 * kWave), 0, st, __VA_ARGS__);       \
     else if (D.max_blocks <= 16384)                                                          \
       hipLaunchKernelGGL((KERNEL<16, 16>), grid, dim3(16 * kWave), 0, st, __VA_ARGS__);      \
     else                                                                                     \
