@@ -40,6 +40,10 @@ def parse(argv=None):
     ap.add_argument("--group-max", action="store_true",
                     help="time the variant that combines the group's heads by their maximum (not the metric's setting)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--interleaved-pool", action="store_true",
+                    help="one pool [n_slots][2][S][d] in which a slot's K tile and V tile lie next to each other "
+                         "(tile_stride = 2 S d) instead of the two dense pools k_pool / v_pool [n_slots][S][d]; "
+                         "measured within 0.2 us of the dense layout at every configuration")
     ap.add_argument("--pipe-recall", type=int, default=0,
                     help="with --pipeline: every layer recalls after each R-th step (staged route)")
     ap.add_argument("--no-recall-overlap", action="store_true",
@@ -74,7 +78,16 @@ class LayerSet:
     def __init__(self, src=None):
         if src is not None:
             for k, v in src.__dict__.items():
+                if k in ("k_pool", "v_pool") and hasattr(src, "kv_pool"):
+                    continue            # views of kv_pool: made again below on the copy
                 setattr(self, k, v.clone() if hasattr(v, "clone") else v)
+            self.pool_views()
+
+    def pool_views(self):
+        """With the interleaved pool: what the library is handed (k_pool = the pool, v_pool = one tile in)."""
+        if hasattr(self, "kv_pool"):
+            flat = self.kv_pool.view(-1)
+            self.k_pool, self.v_pool = flat, flat[self.kv_pool.shape[2] * self.kv_pool.shape[3]:]
 
 
 class State:
@@ -115,7 +128,14 @@ def setup(args) -> State:
     L0.ctx_len = torch.from_numpy(wl.ctx_len).cuda()
     L0.q = dev(wl.q)
     L0.block_table = torch.from_numpy(wl.block_table).cuda()
-    L0.k_pool, L0.v_pool = dev(wl.k_pool), dev(wl.v_pool)
+    tile = cfg.S * cfg.d
+    st.tile_stride = 2 * tile if args.interleaved_pool else 0
+    if not args.interleaved_pool:
+        L0.k_pool, L0.v_pool = dev(wl.k_pool), dev(wl.v_pool)
+    else:   # one pool, K and V tile of a slot adjacent; the library gets v_pool = k_pool + one tile
+        L0.kv_pool = torch.empty(wl.k_pool.shape[0], 2, cfg.S, cfg.d, dtype=torch.bfloat16, device="cuda")
+        L0.kv_pool[:, 0], L0.kv_pool[:, 1] = dev(wl.k_pool), dev(wl.v_pool)
+        L0.pool_views()
     L0.digest = torch.zeros(*pairs, cfg.max_blocks, 2, cfg.d, dtype=torch.bfloat16, device="cuda")
     p0 = B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, B.BF16, cfg.max_blocks, cfg.k, L0.ctx_len)
     st.ws = B.alloc_workspace(p0)
@@ -160,8 +180,11 @@ def setup(args) -> State:
 
     st.sets = [L0] + [LayerSet(L0) for _ in range(args.layers - 1)]
     st.probs = [B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, B.BF16, cfg.max_blocks, cfg.k, s.ctx_len,
-                               group_max=int(args.group_max))
+                               group_max=int(args.group_max), tile_stride=st.tile_stride)
                 for s in st.sets]
+    # the side measurements (append, recall transfer) keep private dense pools
+    st.probs_dense = [B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, B.BF16, cfg.max_blocks, cfg.k, s.ctx_len)
+                      for s in st.sets]
     st.part_o = torch.empty(cfg.B, cfg.Hq, cfg.d, **f32)
     st.part_m = torch.empty(cfg.B, cfg.Hq, **f32)
     st.part_l = torch.empty(cfg.B, cfg.Hq, **f32)
@@ -279,7 +302,7 @@ def fetch_setup(st, per_pair=8):
 def fetch_only(st, i):
     f = st.fetch
     blk, slot = f.plans[i % len(f.plans)]
-    st.B.recall_fetch(st.probs[0], f.k, f.v, blk, slot, f.n, f.k_pool, f.v_pool, f.n_slots)
+    st.B.recall_fetch(st.probs_dense[0], f.k, f.v, blk, slot, f.n, f.k_pool, f.v_pool, f.n_slots)
 
 
 def recall_setup(st):
@@ -360,7 +383,7 @@ def staged_recall(st, i):
     g.d_staged.copy_(g.staged, non_blocking=True)
     g.d_off.copy_(g.off, non_blocking=True)
     blk, slot = f.plans[i % len(f.plans)]
-    st.B.recall_scatter(st.probs[0], g.d_staged, g.d_off, blk, slot, f.n, f.k_pool, f.v_pool, f.n_slots)
+    st.B.recall_scatter(st.probs_dense[0], g.d_staged, g.d_off, blk, slot, f.n, f.k_pool, f.v_pool, f.n_slots)
     return sec
 
 
@@ -377,7 +400,7 @@ def recall_overlap(st, n, us_recall, us_step, route):
     f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     with torch.cuda.stream(side):
         if route == "direct":
-            calls = [st.B.prepare(st.B.recall_fetch, st.probs[0], f.k, f.v, *f.plans[i % len(f.plans)], f.n,
+            calls = [st.B.prepare(st.B.recall_fetch, st.probs_dense[0], f.k, f.v, *f.plans[i % len(f.plans)], f.n,
                                   f.k_pool, f.v_pool, f.n_slots) for i in range(len(f.plans))]
         torch.cuda.synchronize()
         f0.record(side)
@@ -409,6 +432,7 @@ def gather_study(args):
       ascending    each pair's tiles consecutive and ascending (a stream in tile-sized pieces)
       tile16k      blocks of 64 tokens: half as many tiles of 16 KiB (K) + 16 KiB (V), shuffled
       tile4k       blocks of 16 tokens: twice as many tiles of 4 KiB + 4 KiB, shuffled"""
+    args.interleaved_pool = False  # the study builds every layout itself, from the two dense pools
     st = setup(args)
     torch, B, cfg, wl = st.torch, st.B, st.cfg, st.wl
     assert cfg.S == 32 and cfg.d == 128
@@ -755,7 +779,8 @@ def main():
                                 "C4": "C4 long context single layer", "C5": "C5 ragged batch, one layer"}[args.config],
                    "batch": cfg.B, "q_heads": cfg.Hq,
                    "kv_heads": cfg.Hkv, "head_dim": cfg.d, "context": int(max(cfg.ctx)), "block": cfg.S, "k_blocks": cfg.k,
-                   "host_resident": cfg.p_host, "layer_copies": len(st.sets), "gpu_blocks_per_step": n_blocks},
+                   "host_resident": cfg.p_host, "layer_copies": len(st.sets), "gpu_blocks_per_step": n_blocks,
+                   "pool_layout": "one pool [slots][2][S][d]" if args.interleaved_pool else "k_pool, v_pool [slots][S][d]"},
         "kv_gbps": round(attn_gbps, 1),
         "kernels_us": {"score_blocks": round(us_score, 3), "select_topk": round(us_select, 3),
                        "attn_mfma_kernel": round(us_attn_kernel, 3), "sparse_decode_attn": round(us_attn, 3),
@@ -780,7 +805,9 @@ def main():
                               "gather_tiles_gbps": round(attn_bytes / us_gather * 1e-3, 1),
                               "attn_frac_of_gather": round(us_gather / us_attn_kernel, 4),
                               "score_frac_of_stream": round(us_stream * digest_bytes / s0_digest_bytes / us_score, 4)},
-        "roofline": {"bound": "hbm", "kernel": "attn_mfma_kernel", "achieved": round(attn_gbps, 1),
+        # kernels_us.attn_mfma_kernel: the attention pass alone (scout_attn_partials), whose kernel at these shapes
+        # is attn_mfma_private_kernel<8> (the variant in which every wave fetches its own list entries)
+        "roofline": {"bound": "hbm", "kernel": "attn_mfma_private_kernel<8>", "achieved": round(attn_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
                      "traffic": traffic, "traffic_source": None if traffic is None else os.path.relpath(tpath, ROOT),
                      "algorithmic_bytes": attn_bytes},

@@ -82,6 +82,12 @@ typedef struct scout_problem {
                          keys in binary32 added in token order (an append is one
                          addition and equals a rebuild bit for bit), and a block's
                          importance is sum_h q_h . sum / count; not with group_max */
+  int32_t tile_stride; /* elements from the tile of one pool slot to the tile of the next, in
+                         k_pool and in v_pool alike.  0 = S * d: two dense pools
+                         [n_slots][S][d].  2 * S * d with v_pool = k_pool + S * d is ONE pool
+                         [n_slots][2][S][d] in which the K tile and the V tile of a slot lie
+                         next to each other (one 16 KiB region per block instead of two 8 KiB
+                         regions).  Otherwise >= S * d and a multiple of 8                  */
   const int32_t* ctx_len; /* DEVICE int32 [B]: tokens per sequence; blocks beyond
                              max_blocks are ignored                                  */
 } scout_problem;

@@ -40,7 +40,8 @@ class Problem(ctypes.Structure):
                 ("d", ctypes.c_int32), ("S", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("max_blocks", ctypes.c_int32), ("k", ctypes.c_int32), ("sm_scale", ctypes.c_float),
                 ("n_sink", ctypes.c_int32), ("n_tail", ctypes.c_int32), ("group_max", ctypes.c_int32),
-                ("per_head", ctypes.c_int32), ("digest_kind", ctypes.c_int32), ("ctx_len", ctypes.c_void_p)]
+                ("per_head", ctypes.c_int32), ("digest_kind", ctypes.c_int32), ("tile_stride", ctypes.c_int32),
+                ("ctx_len", ctypes.c_void_p)]
 
 
 _lib = None
@@ -173,10 +174,10 @@ def dtype_code(t: torch.Tensor) -> int:
 
 def make_problem(B, Hq, Hkv, d, S, dtype, max_blocks, k, ctx_len: torch.Tensor, sm_scale: float = 0.0,
                  n_sink: int = 0, n_tail: int = 0, group_max: int = 0, per_head: int = 0,
-                 digest_kind: int = 0):
+                 digest_kind: int = 0, tile_stride: int = 0):
     assert ctx_len.dtype == torch.int32 and ctx_len.is_cuda
     return Problem(B, Hq, Hkv, d, S, dtype, max_blocks, k, float(sm_scale), int(n_sink), int(n_tail),
-                   int(group_max), int(per_head), int(digest_kind), ctx_len.data_ptr())
+                   int(group_max), int(per_head), int(digest_kind), int(tile_stride), ctx_len.data_ptr())
 
 
 def version() -> int:

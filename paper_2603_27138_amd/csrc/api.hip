@@ -76,6 +76,8 @@ static int check_problem(const scout_problem* p, Dims* D) {
   D->group_max = p->group_max;
   D->digest_kind = p->digest_kind;
   D->s_shift = p->S == 16 ? 4 : (p->S == 32 ? 5 : 6);
+  if (p->tile_stride != 0 && (p->tile_stride < p->S * p->d || p->tile_stride % 8 != 0)) return SCOUT_EINVAL;
+  D->tile_stride = p->tile_stride != 0 ? p->tile_stride : p->S * p->d;
   D->share = 1;
   D->share_magic = 0;
   if (p->per_head) {  // every query head is a pair of its own that reads its KV head's digest and table rows

@@ -55,7 +55,7 @@ __global__ __launch_bounds__(1024) void append_kernel(Dims D, int32_t* ctx_len, 
         if (kf > load1<DT>(dg, i_max)) dg[i_max] = k;
       }
       if (slot >= 0 && slot < n_slots) {
-        const size_t row = ((size_t)slot * D.S + r) * D.d + c;
+        const size_t row = (size_t)slot * D.tile_stride + (size_t)r * D.d + c;
         kp[row] = k;
         vp[row] = v;
       }

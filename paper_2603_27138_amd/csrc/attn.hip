@@ -141,7 +141,7 @@ struct Entry {
 
 // sel / slot_list point at the pair's list (global memory or LDS); u is wave-uniform.
 __device__ __forceinline__ Entry read_entry(const int32_t* sel, const int32_t* slot_list, int u, int u_end,
-                                            int ush, int S, int ctx, long long n_slots) {
+                                            int ush, int S, int ctx, long long n_slots, int tile_stride) {
   Entry e{0, 0};
   if (u < u_end) {
     const int i = u >> ush, sub = u - (i << ush);  // ush = log2(units per block)
@@ -150,7 +150,7 @@ __device__ __forceinline__ Entry read_entry(const int32_t* sel, const int32_t* s
     int valid = ctx - j * S - sub * kUnitTokens;
     valid = valid > kUnitTokens ? kUnitTokens : valid;
     if (j >= 0 && valid > 0 && slot >= 0 && slot < n_slots) {
-      e.elem_off = ((size_t)slot * S + sub * kUnitTokens) * kMfmaD;
+      e.elem_off = (size_t)slot * tile_stride + sub * kUnitTokens * kMfmaD;
       e.valid = valid;
     }
   }
@@ -308,7 +308,7 @@ __device__ __forceinline__ void attend_pair(const Dims& D, int b, int g, int spl
         int valid = ctx - bj * S - sub * kUnitTokens;
         valid = valid > kUnitTokens ? kUnitTokens : valid;
         if (bj >= 0 && valid > 0 && slot >= 0 && slot < n_slots) {
-          e.elem_off = ((size_t)slot * S + sub * kUnitTokens) * kMfmaD;
+          e.elem_off = (size_t)slot * D.tile_stride + sub * kUnitTokens * kMfmaD;
           e.valid = valid;
         }
       }
@@ -330,13 +330,13 @@ __device__ __forceinline__ void attend_pair(const Dims& D, int b, int g, int spl
     Entry ent[DEPTH];
 #pragma unroll
     for (int d = 0; d < DEPTH; ++d) {
-      ent[d] = read_entry(sel, slot_list, u0 + d, u1, ush, S, ctx, n_slots);
+      ent[d] = read_entry(sel, slot_list, u0 + d, u1, ush, S, ctx, n_slots, D.tile_stride);
       issue_unit(buf[d], k_pool, v_pool, ent[d], ln, kg);
     }
     for (int u = u0; u < u1; u += DEPTH) {
 #pragma unroll
       for (int d = 0; d < DEPTH; ++d) {
-        const Entry nx = read_entry(sel, slot_list, u + d + DEPTH, u1, ush, S, ctx, n_slots);
+        const Entry nx = read_entry(sel, slot_list, u + d + DEPTH, u1, ush, S, ctx, n_slots, D.tile_stride);
         consume_unit(W, buf[d], qreg, ent[d].valid, scale2, kg);
         ent[d] = nx;
         issue_unit(buf[d], k_pool, v_pool, nx, ln, kg);
@@ -815,7 +815,7 @@ __global__ __launch_bounds__(kWave) void attn_valu_kernel(
     int valid = ctx - j * D.S;
     valid = valid > D.S ? D.S : valid;
     if (j < 0 || valid <= 0 || slot < 0 || slot >= n_slots) continue;
-    const size_t tile = (size_t)slot * D.S * DH;
+    const size_t tile = (size_t)slot * D.tile_stride;
     for (int t0 = 0; t0 < D.S; t0 += TPW) {
       const int t = t0 + tl;
       const bool live = t < valid;

@@ -40,7 +40,8 @@ __global__ __launch_bounds__(256) void calib_read_kernel(const uint4* __restrict
 // (a list is rarely full, so folding it keeps most workgroups from being launched for nothing).
 __global__ __launch_bounds__(256) void calib_gather_kernel(const char* __restrict__ k_pool,
                                                            const char* __restrict__ v_pool, long long n_slots,
-                                                           int tile_bytes, const int32_t* __restrict__ slot_gpu,
+                                                           int tile_bytes, int stride_bytes,
+                                                           const int32_t* __restrict__ slot_gpu,
                                                            const int32_t* __restrict__ n_gpu, int k, uint32_t* sink) {
   const int pair = blockIdx.y, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int i = wave < 2 ? (int)blockIdx.x : k - 1 - (int)blockIdx.x;
@@ -49,7 +50,7 @@ __global__ __launch_bounds__(256) void calib_gather_kernel(const char* __restric
   int n = n_gpu[pair];
   n = n < k ? n : k;
   if (i >= n || slot < 0 || slot >= n_slots) return;
-  const char* tile = ((wave & 1) ? v_pool : k_pool) + (size_t)slot * tile_bytes;
+  const char* tile = ((wave & 1) ? v_pool : k_pool) + (size_t)slot * stride_bytes;
   uint32_t acc = 0;
   for (int off = lane * 16; off < tile_bytes; off += 8 * 1024) {  // 8 KiB per trip: 8 loads in flight
     uint4 v[8];
@@ -91,12 +92,15 @@ int scout_calib_gather(const scout_problem* p, const void* k_pool, const void* v
     return SCOUT_EINVAL;
   if (!k_pool || !v_pool || !slot_gpu || !n_gpu || !aligned16(k_pool) || !aligned16(v_pool) || n_slots < 0)
     return SCOUT_EINVAL;
-  const int tile_bytes = p->S * p->d * (p->dtype == SCOUT_BF16 ? 2 : 4);
+  const int esize = p->dtype == SCOUT_BF16 ? 2 : 4;
+  const int tile_bytes = p->S * p->d * esize;
+  if (p->tile_stride != 0 && (p->tile_stride < p->S * p->d || p->tile_stride % 8 != 0)) return SCOUT_EINVAL;
+  const int stride_bytes = p->tile_stride != 0 ? p->tile_stride * esize : tile_bytes;
   dim3 grid((p->k + 1) / 2, p->B * p->Hkv);
   if (grid.y == 0) return SCOUT_OK;
   hipLaunchKernelGGL(calib_gather_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<const char*>(k_pool), static_cast<const char*>(v_pool), (long long)n_slots,
-                     tile_bytes, slot_gpu, n_gpu, p->k, static_cast<uint32_t*>(sink));
+                     tile_bytes, stride_bytes, slot_gpu, n_gpu, p->k, static_cast<uint32_t*>(sink));
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
 }
 

@@ -22,6 +22,8 @@ struct Dims {
                        // per query head the real group size (then Hkv = Hq and G = 1 here)
   uint32_t share_magic;  // ceil(2^32 / share) for share > 1: pair / share without a division
   int s_shift;         // log2(S): integer divisions are slow enough here to show in the launch heads
+  int tile_stride;     // elements from one slot's tile to the next, in k_pool and in v_pool alike: S * d for
+                       // two dense pools, 2 * S * d where a slot's K tile and V tile lie next to each other
   const int32_t* ctx_len;
 };
 

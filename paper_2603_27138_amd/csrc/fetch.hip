@@ -52,7 +52,7 @@ __device__ __forceinline__ void move_tiles(const char* __restrict__ from_k, cons
 // Workgroup w of W: if there are fewer pairs than workgroups, W / pairs workgroups share a pair and
 // deal its entries round robin; otherwise workgroups take whole pairs, W apart.
 __global__ __launch_bounds__(kFetchThreads) void recall_fetch_kernel(
-    Dims D, int tile_bytes, int wgs_per_pair, const char* __restrict__ src_k, const char* __restrict__ src_v,
+    Dims D, int tile_bytes, int stride_bytes, int wgs_per_pair, const char* __restrict__ src_k, const char* __restrict__ src_v,
     const int32_t* __restrict__ recall_blk, const int32_t* __restrict__ recall_slot,
     const int32_t* __restrict__ n_recall, char* __restrict__ k_pool, char* __restrict__ v_pool,
     long long n_slots) {
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(kFetchThreads) void recall_fetch_kernel(
     for (int i = first_entry; i < n; i += wgs_per_pair) {
       const int blk = recall_blk[(size_t)pair * D.k + i], slot = recall_slot[(size_t)pair * D.k + i];
       if (blk < 0 || blk >= D.max_blocks || slot < 0 || slot >= n_slots) continue;
-      const size_t src = ((size_t)pair * D.max_blocks + blk) * tile_bytes, dst = (size_t)slot * tile_bytes;
+      const size_t src = ((size_t)pair * D.max_blocks + blk) * tile_bytes, dst = (size_t)slot * stride_bytes;
       move_tiles(src_k + src, src_v + src, k_pool + dst, v_pool + dst, tile_bytes / 16);
     }
   }
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(kFetchThreads) void recall_fetch_kernel(
 // deal the pair's entries round robin (a recall moves a fraction of the budget, so a workgroup per
 // possible entry would mostly launch workgroups that find nothing to do).
 __global__ __launch_bounds__(kFetchThreads) void recall_scatter_kernel(
-    Dims D, int tile_bytes, const char* __restrict__ staged, long long n_tiles,
+    Dims D, int tile_bytes, int stride_bytes, const char* __restrict__ staged, long long n_tiles,
     const int32_t* __restrict__ tile_off, const int32_t* __restrict__ recall_blk,
     const int32_t* __restrict__ recall_slot, const int32_t* __restrict__ n_recall, char* __restrict__ k_pool,
     char* __restrict__ v_pool, long long n_slots) {
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(kFetchThreads) void recall_scatter_kernel(
     if (blk < 0 || blk >= D.max_blocks || slot < 0 || slot >= n_slots) continue;
     if (first < 0 || first + i >= n_tiles) continue;  // an offset that points outside the buffer moves nothing
     const char* from = staged + (size_t)(first + i) * 2 * tile_bytes;
-    const size_t dst = (size_t)slot * tile_bytes;
+    const size_t dst = (size_t)slot * stride_bytes;
     move_tiles(from, from + tile_bytes, k_pool + dst, v_pool + dst, tile_bytes / 16);
   }
 }
@@ -106,7 +106,8 @@ int launch_recall_fetch(const Dims& D, int dtype, const void* src_k, const void*
   if (wgs_per_pair > D.k) wgs_per_pair = D.k;
   const long long want = pairs * wgs_per_pair;
   const unsigned grid = (unsigned)(want < kFetchWgs ? want : kFetchWgs);
-  hipLaunchKernelGGL(recall_fetch_kernel, dim3(grid), dim3(kFetchThreads), 0, st, D, tile_bytes, wgs_per_pair,
+  const int stride_bytes = D.tile_stride * (dtype == SCOUT_BF16 ? 2 : 4);
+  hipLaunchKernelGGL(recall_fetch_kernel, dim3(grid), dim3(kFetchThreads), 0, st, D, tile_bytes, stride_bytes, wgs_per_pair,
                      static_cast<const char*>(src_k), static_cast<const char*>(src_v), recall_blk, recall_slot,
                      n_recall, static_cast<char*>(k_pool), static_cast<char*>(v_pool), n_slots);
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
@@ -119,7 +120,8 @@ int launch_recall_scatter(const Dims& D, int dtype, const void* staged, long lon
   if (tile_bytes % 16 != 0 || tile_bytes / 16 > kFetchMaxPieces * kFetchThreads) return SCOUT_EUNSUPPORTED;
   dim3 grid(D.k < 16 ? D.k : 16, D.B * D.Hkv);
   if (grid.x == 0 || grid.y == 0) return SCOUT_OK;
-  hipLaunchKernelGGL(recall_scatter_kernel, grid, dim3(kFetchThreads), 0, st, D, tile_bytes,
+  const int stride_bytes = D.tile_stride * (dtype == SCOUT_BF16 ? 2 : 4);
+  hipLaunchKernelGGL(recall_scatter_kernel, grid, dim3(kFetchThreads), 0, st, D, tile_bytes, stride_bytes,
                      static_cast<const char*>(staged), n_tiles, tile_off, recall_blk, recall_slot, n_recall,
                      static_cast<char*>(k_pool), static_cast<char*>(v_pool), n_slots);
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;

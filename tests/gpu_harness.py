@@ -81,17 +81,30 @@ class Dev:
     """One layer's inputs and outputs in device memory.  Every tensor an entry point writes lives in a
     guarded arena (see Arena); the call wrappers below check the guards after each call."""
 
-    def __init__(self, wl: W.Workload, k_blocks: bool = True):
+    def __init__(self, wl: W.Workload, k_blocks: bool = True, interleaved: bool = False):
+        """interleaved: ONE pool [n_slots][2][S][d] (a slot's K tile and V tile next to each other)
+        instead of two dense pools; k_pool / v_pool are then what the library is
+        handed (v_pool = k_pool + one tile, tile_stride = 2 S d), k_tiles / v_tiles the [n_slots][S][d] views."""
         cfg = wl.cfg
         self.cfg, self.wl = cfg, wl
         self.tdt = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
         self.ctx_len = torch.from_numpy(wl.ctx_len).cuda()
+        self.tile_stride = 2 * cfg.S * cfg.d if interleaved else 0
         self.p = B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, B.F32 if cfg.dtype == "f32" else B.BF16,
-                                cfg.max_blocks, cfg.k, self.ctx_len, 0.0)
+                                cfg.max_blocks, cfg.k, self.ctx_len, 0.0, tile_stride=self.tile_stride)
         self.q = to_dev(wl.q)
         self.n_slots = wl.n_slots
-        self.k_pool = to_dev(wl.k_pool)
-        self.v_pool = to_dev(wl.v_pool)
+        if interleaved:
+            kd, vd = to_dev(wl.k_pool), to_dev(wl.v_pool)
+            self.kv_pool = torch.empty(kd.shape[0], 2, cfg.S, cfg.d, dtype=kd.dtype, device="cuda")
+            self.kv_pool[:, 0], self.kv_pool[:, 1] = kd, vd
+            flat = self.kv_pool.view(-1)
+            self.k_pool, self.v_pool = flat, flat[cfg.S * cfg.d:]
+            self.k_tiles, self.v_tiles = self.kv_pool[:, 0], self.kv_pool[:, 1]
+        else:
+            self.k_pool = to_dev(wl.k_pool)
+            self.v_pool = to_dev(wl.v_pool)
+            self.k_tiles, self.v_tiles = self.k_pool, self.v_pool
         pairs = (cfg.B, cfg.Hkv)
         if k_blocks:
             kb = np.full((cfg.B, cfg.Hkv, cfg.max_blocks, cfg.S, cfg.d), W._GARBAGE[cfg.dtype],

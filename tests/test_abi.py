@@ -84,7 +84,7 @@ def test_workspace_bytes(lib):
 
 @pytest.mark.parametrize("kw,code", [
     (dict(Hq=7), -1), (dict(Hkv=0), -1), (dict(B=-1), -1), (dict(k=0), -1), (dict(max_blocks=0), -1),
-    (dict(dtype=5), -1), (dict(sm_scale=-1.0), -1), (dict(ctx_len=None), -1), (dict(n_sink=-1), -1), (dict(n_tail=-3), -1), (dict(group_max=2), -1), (dict(per_head=2), -1), (dict(digest_kind=2), -1), (dict(digest_kind=1, group_max=1), -2), (dict(per_head=-1), -1), (dict(B=70000), -2),
+    (dict(dtype=5), -1), (dict(sm_scale=-1.0), -1), (dict(ctx_len=None), -1), (dict(n_sink=-1), -1), (dict(n_tail=-3), -1), (dict(group_max=2), -1), (dict(per_head=2), -1), (dict(digest_kind=2), -1), (dict(digest_kind=1, group_max=1), -2), (dict(per_head=-1), -1), (dict(tile_stride=100), -1), (dict(tile_stride=4100), -1), (dict(tile_stride=-8192), -1), (dict(B=70000), -2),
     (dict(d=96), -2), (dict(S=8), -2), (dict(Hq=64, Hkv=2), -2), (dict(k=5000), -2), (dict(max_blocks=1 << 20), -2),
 ])
 def test_bad_problem_is_rejected_before_launch(lib, kw, code):

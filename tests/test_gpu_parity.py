@@ -757,3 +757,71 @@ def test_layer_step_without_scores():
         for a, b in zip(want, got):
             assert torch.equal(a, b), mode
         assert torch.isnan(dev.scores).all()      # not written
+
+
+@pytest.mark.parametrize("which", ["C3-qwen3-32b", "ragged-f32", "bf16-d64-s16", "bf16-s64-g2"])
+def test_interleaved_pool_layout(which):
+    """tile_stride: one pool [n_slots][2][S][d] (a slot's K tile and V tile adjacent, v_pool = k_pool + one
+    tile) gives bit for bit what two dense pools give, through every entry point that touches the pools:
+    the attention alone and inside the step, the decode append, the recall's transfer by both routes."""
+    cfg = next(c for c in CFGS if c.name == which)
+    wl, res, dense = setup(cfg)
+    inter = Dev(wl, interleaved=True)
+    for dev in (dense, inter):
+        dev.set_digest_from_oracle(res)
+        dev.set_host_partials_from_oracle(res)
+        dev.set_selection_from_oracle(res)
+    modes = [(0, 0, 0), (2, 1, 8), (2, 2, 4), (1, 3, 0)] if cfg.dtype == "bf16" and cfg.d == 128 else [(0, 0, 0)]
+    for mode in modes:
+        outs = []
+        for dev in (dense, inter):
+            B.set_attn_mode(*mode)
+            try:
+                dev.set_selection_from_oracle(res)
+                dev.attn()
+                part = [t.clone() for t in (dev.o, dev.m, dev.l)]
+                dev.layer_step()
+            finally:
+                B.set_attn_mode(0, 0, 0)
+            outs.append(part + [t.clone() for t in (dev.out, dev.lse, dev.sel_all, dev.slot_gpu, dev.n_gpu)])
+        for a, b in zip(*outs):
+            assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a, b.view(torch.int32) if b.dtype == torch.float32 else b), mode
+    # decode append: one token per sequence (sequences at their capacity are left alone), on private copies
+    rng = np.random.default_rng(3)
+    k_new = to_dev(W.to_storage(rng.standard_normal((cfg.B, cfg.Hkv, cfg.d)).astype(np.float32), cfg.dtype))
+    v_new = to_dev(W.to_storage(rng.standard_normal((cfg.B, cfg.Hkv, cfg.d)).astype(np.float32), cfg.dtype))
+    new_slot = torch.full((cfg.B, cfg.Hkv), -1, dtype=torch.int32, device="cuda")
+    q1 = W.gen_q(cfg, 0, step=5)
+    pools = []
+    for dev in (dense, inter):
+        table0, dig0, ctx0 = dev.block_table.clone(), dev.digest.clone(), dev.ctx_len.clone()
+        B.append_token(dev.p, dev.ctx_len, k_new, v_new, new_slot, dev.digest, dev.block_table, dev.k_pool, dev.v_pool,
+                       dev.n_slots)
+        # the recall for a drifted query, moved by the direct route from a device copy of every block
+        kb = np.zeros((cfg.B, cfg.Hkv, cfg.max_blocks, cfg.S, cfg.d), dtype=wl.k_pool.dtype)
+        vb = np.zeros_like(kb)
+        for (b, g) in wl.K:
+            kb[b, g, :cfg.nb(b)] = wl.blocks_padded(b, g, "K")
+            vb[b, g, :cfg.nb(b)] = wl.blocks_padded(b, g, "V")
+        dev.recall(to_dev(q1))
+        B.recall_fetch(dev.p, to_dev(kb), to_dev(vb), dev.recall_blk, dev.recall_slot, dev.n_recall, dev.k_pool, dev.v_pool,
+                       dev.n_slots)
+        # and once more by the staged route: the same tiles packed in plan order
+        nr = dev.n_recall.cpu().numpy().reshape(-1)
+        rb = dev.recall_blk.cpu().numpy().reshape(len(nr), cfg.k)
+        staged, off = oracle.recall_stage(kb.reshape(len(nr), cfg.max_blocks, cfg.S, cfg.d),
+                                          vb.reshape(len(nr), cfg.max_blocks, cfg.S, cfg.d), rb, nr)
+        if staged.size:
+            B.recall_scatter(dev.p, to_dev(staged), torch.from_numpy(off).cuda(), dev.recall_blk, dev.recall_slot,
+                             dev.n_recall, dev.k_pool, dev.v_pool, dev.n_slots)
+        dev.check_guards()
+        pools.append((dev.k_tiles.clone(), dev.v_tiles.clone(), dev.digest.clone(), dev.block_table.clone(),
+                      dev.ctx_len.clone()))
+        dev.block_table.copy_(table0); dev.digest.copy_(dig0); dev.ctx_len.copy_(ctx0)
+    # NaN patterns (the tails of partly filled blocks) compare by bits
+    bits = lambda t: t.contiguous().view(torch.int16 if t.element_size() == 2 else torch.int32)
+    for a, b in zip(*pools):
+        assert torch.equal(bits(a), bits(b))
+    if 0.0 < cfg.p_host < 1.0:
+        assert not torch.equal(bits(pools[0][0]), bits(to_dev(wl.k_pool)))    # something did move
+    dense.k_pool.copy_(to_dev(wl.k_pool)); dense.v_pool.copy_(to_dev(wl.v_pool))
