@@ -282,21 +282,52 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_kernel(
 
 // The same stream with the group's heads combined by their maximum instead of their sum.  The fold of
 // the group is not possible then: every head keeps its own estimate, sum over channels of the larger
-// of q*min and q*max (= q*max where q >= 0, q*min elsewhere), reduced over the 8 lanes of an entry
-// head by head.  G times the arithmetic of the folded kernel, on the same loads.
-template <int DT, int DH>
+// of q*min and q*max, which is P_h . max + N_h . min with the positive and negative parts of that head's
+// queries.  G times the multiply-adds of the folded kernel on the same loads, so the arithmetic, not the
+// stream, sets the pace, and everything around the multiply-adds is kept small:
+//  * the per-head coefficients are made once per workgroup, as binary64 in LDS, and a wave takes
+//    16 loads per lane (2 to 8 entries per lane) so that each coefficient it reads serves that many entries;
+//  * heads are taken four at a time, or eight where the group has more than four (one pass, an element
+//    converted to binary64 once, for the common group of eight);
+//  * the sums of (entries per lane) x 4 heads are added across the 8 lanes of an entry by a butterfly
+//    that exchanges half of the remaining sums at each of its three steps, instead of three steps for
+//    every sum: 7/8 of a step per sum.
+// Heads beyond G in the last pass repeat head G - 1, which leaves the maximum as it is.
+template <int N, int LEVEL>
+__device__ __forceinline__ void halve_across(double* a, bool hi) {
+#pragma unroll
+  for (int i = 0; i < N / 2; ++i) {
+    const double keep = hi ? a[i + N / 2] : a[i], send = hi ? a[i] : a[i + N / 2];
+    a[i] = keep + partner_f64<LEVEL>(send);
+  }
+}
+
+constexpr int score_max_entries(int lines) { return 16 / lines < 4 ? 16 / lines : 4; }  // per lane
+
+template <int DT, int DH, int HC>
 __global__ __launch_bounds__(kScoreWaves* kWave) void score_max_kernel(Dims D, const void* q, const void* digest,
                                                                       float* scores) {
-  constexpr int EPL = (DT == SCOUT_BF16) ? 8 : 4;
+  constexpr int EPL = (DT == SCOUT_BF16) ? 8 : 4;   // elements per 16-byte load
   constexpr int ESZ = (DT == SCOUT_BF16) ? 2 : 4;
-  constexpr int EB = 2 * DH * ESZ;
-  constexpr int NL = EB / 128;
-  constexpr int NG = kScoreBatch / NL;
-  constexpr int BLK_PER_WAVE = NG * 8;
+  constexpr int EB = 2 * DH * ESZ;                  // bytes per digest entry
+  constexpr int NL = EB / 128;                      // 128-byte lines per entry
+  constexpr int E = score_max_entries(NL);          // entries per lane
+  constexpr int V = E * HC;                         // sums per lane and pass (HC heads per pass: 4 or 8)
+  constexpr int W = HC == 8 ? 2 : 4;                // elements per step of the inner loop
+  constexpr int BLK_PER_WAVE = 8 * E;
   constexpr int NT = kScoreWaves * kWave;
-  static_assert(NL >= 2 && NL <= kScoreBatch, "layout");
+  static_assert(NL >= 2 && NL <= 8 && V >= 8 && HC % (V / 8) == 0, "layout");
 
-  __shared__ __align__(16) float q_lds[16 * DH];  // the group's queries as binary32, [head][channel]
+  // [head][0: N_h, goes with the min row; 1: P_h][channel], the channels of a row in the order in which the
+  // lanes read them: a lane's EPL channels of a line are EPL / 2 reads of 16 bytes, and the 8 lanes of an
+  // entry read 128 consecutive bytes each time (channel by channel they would be 64 bytes apart and
+  // collide on the banks)
+  __shared__ __align__(16) double coef_lds[16][2][DH];
+  constexpr int CPL = 128 / ESZ;  // channels per line
+  auto coef_at = [](int c) {      // where channel c of a row sits
+    const int lr = c / CPL, l8 = (c % CPL) / EPL, i = c % EPL;
+    return ((lr * (EPL / 2) + i / 2) * 8 + l8) * 2 + (i & 1);
+  };
 
   const int pair = grid_pair();  // grid (x, Hkv, B)
   const int b = blockIdx.z, g = blockIdx.y;
@@ -306,78 +337,110 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_max_kernel(Dims D, c
   const int j_wave = (blockIdx.x * kScoreWaves + wave) * BLK_PER_WAVE;
   const bool active = j_wave < D.max_blocks;
   if ((int)blockIdx.x * kScoreWaves * BLK_PER_WAVE >= nb) {  // as in score_kernel: only the row's tail to mark
-    const int j = (int)blockIdx.x * kScoreWaves * BLK_PER_WAVE + threadIdx.x;
-    if (threadIdx.x < kScoreWaves * BLK_PER_WAVE && j < D.max_blocks) scores[(size_t)pair * D.max_blocks + j] = -INFINITY;
+    for (int t = threadIdx.x; t < kScoreWaves * BLK_PER_WAVE; t += NT) {
+      const int j = (int)blockIdx.x * kScoreWaves * BLK_PER_WAVE + t;
+      if (j < D.max_blocks) scores[(size_t)pair * D.max_blocks + j] = -INFINITY;
+    }
     return;
   }
 
   // queries first (see score_kernel for why the order of issue matters)
-  constexpr int QPT = (16 * DH + NT - 1) / NT;  // elements per thread
+  constexpr int QPT = 16 * DH / NT;  // elements per thread
+  static_assert(16 * DH % NT == 0, "layout");
+  const int heads4 = (D.G + HC - 1) & ~(HC - 1);  // heads that are read, the repeated ones included
   float qreg[QPT];
-  const int n_q = D.G * DH;
 #pragma unroll
   for (int i = 0; i < QPT; ++i) {
-    const int e = threadIdx.x + i * NT;
-    qreg[i] = load1<DT>(q, ((size_t)b * D.Hq + g * D.G) * DH + (e < n_q ? e : n_q - 1));
+    const int e = threadIdx.x + i * NT, h = e / DH, c = e % DH;
+    const int hs = h < D.G ? h : D.G - 1;
+    qreg[i] = load1<DT>(q, ((size_t)b * D.Hq + g * D.G + hs) * DH + c);
   }
   const char* dpair = static_cast<const char*>(digest) + (size_t)kv_row(D, pair) * D.max_blocks * EB;
   const __amdgpu_buffer_rsrc_t rs =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(dpair), 0, active ? nb * EB : 0, 0x00020000);
   const int voff0 = (j_wave + (lane >> 3)) * EB + (lane & 7) * 16;
-  u32x4 raw[kScoreBatch];
+  u32x4 raw[E * NL];  // load gq * NL + u: line u of the lane's entry in group gq of 8 entries
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-  for (int it = 0; it < kScoreBatch; ++it)
-    raw[it] = __builtin_bit_cast(
-        u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff0 + (it / NL) * 8 * EB + (it % NL) * 128, 0, 0));
+  for (int u = 0; u < NL; ++u)  // requested in the order of use: line by line, the E entries of a line together
+#pragma unroll
+    for (int gq = 0; gq < E; ++gq)
+      raw[gq * NL + u] = __builtin_bit_cast(
+          u32x4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff0 + gq * 8 * EB + u * 128, 0, 0));
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int i = 0; i < QPT; ++i) {
-    const int e = threadIdx.x + i * NT;
-    if (e < 16 * DH) q_lds[e] = qreg[i];
+    const int e = threadIdx.x + i * NT, h = e / DH, c = e % DH;
+    if (h < heads4) {
+      coef_lds[h][0][coef_at(c)] = (double)fminf(qreg[i], 0.0f);
+      coef_lds[h][1][coef_at(c)] = (double)fmaxf(qreg[i], 0.0f);
+    }
   }
   __syncthreads();
 
+  const bool b2 = (lane >> 2) & 1, b1 = (lane >> 1) & 1, b0 = lane & 1;
+  double best = -INFINITY;
+  for (int h0 = 0; h0 < D.G; h0 += HC) {
+    double acc[V];  // sum of entry group gq, head h0 + hh at gq * HC + hh
 #pragma unroll
-  for (int gq = 0; gq < NG; ++gq) {
-    // the entry's elements this lane holds: channels (u * 128 / ESZ + (lane & 7) * EPL + i), min and max row
-    float mn[NL / 2][EPL], mx[NL / 2][EPL];
+    for (int i = 0; i < V; ++i) acc[i] = 0.0;
+    // (the loaded words are declared changed here: otherwise their binary64 forms, which do not depend on
+    // the pass, are all made ahead of the loop and take four times the registers of the words themselves)
 #pragma unroll
-    for (int u = 0; u < NL / 2; ++u) {
-      const u32x4 a = raw[gq * NL + u], c = raw[gq * NL + u + NL / 2];
+    for (int it = 0; it < E * NL; ++it)
+      asm volatile("" : "+v"(raw[it][0]), "+v"(raw[it][1]), "+v"(raw[it][2]), "+v"(raw[it][3]));
 #pragma unroll
-      for (int i = 0; i < EPL; ++i) {
-        if (DT == SCOUT_BF16) {
-          mn[u][i] = (i & 1) ? bf16_hi(a[i >> 1]) : bf16_lo(a[i >> 1]);
-          mx[u][i] = (i & 1) ? bf16_hi(c[i >> 1]) : bf16_lo(c[i >> 1]);
-        } else {
-          mn[u][i] = __uint_as_float(a[i]);
-          mx[u][i] = __uint_as_float(c[i]);
+    for (int u = 0; u < NL; ++u) {
+      // line u of an entry: min row for u < NL/2, max row after; channels c0 .. c0 + EPL of that row
+      const int row = u / (NL / 2), c0 = (u % (NL / 2)) * CPL + (lane & 7) * EPL;
+#pragma unroll
+      for (int i0 = 0; i0 < EPL; i0 += W) {  // W elements at a time: HC x W coefficients in registers
+        double cf[HC][W];
+#pragma unroll
+        for (int hh = 0; hh < HC; ++hh)
+#pragma unroll
+          for (int i = 0; i < W; ++i) cf[hh][i] = coef_lds[h0 + hh][row][coef_at(c0 + i0 + i)];
+#pragma unroll
+        for (int gq = 0; gq < E; ++gq) {
+          const u32x4 w = raw[gq * NL + u];
+          double x[W];
+#pragma unroll
+          for (int i = 0; i < W; ++i) {
+            if (DT == SCOUT_BF16)
+              x[i] = (double)(((i0 + i) & 1) ? bf16_hi(w[(i0 + i) >> 1]) : bf16_lo(w[(i0 + i) >> 1]));
+            else
+              x[i] = (double)__uint_as_float(w[i0 + i]);
+          }
+#pragma unroll
+          for (int hh = 0; hh < HC; ++hh)
+#pragma unroll
+            for (int i = 0; i < W; ++i) acc[gq * HC + hh] = fma(cf[hh][i], x[i], acc[gq * HC + hh]);
         }
       }
     }
-    double best = -INFINITY;
-    for (int h = 0; h < D.G; ++h) {
-      double acc = 0.0;
+    // across the 8 lanes of an entry: each step keeps the half of the sums that the lane's bit names and
+    // adds the partner's; V / 8 finished sums remain, index (4 b2 + 2 b1 + b0) * V / 8 + r of the V
+    halve_across<V, 2>(acc, b2);
+    halve_across<V / 2, 1>(acc, b1);
+    halve_across<V / 4, 0>(acc, b0);
 #pragma unroll
-      for (int u = 0; u < NL / 2; ++u) {
-        const float* qh = q_lds + h * DH + u * (128 / ESZ) + (lane & 7) * EPL;
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) {
-          const float qv = qh[i];
-          acc = fma((double)qv, (double)(qv >= 0.0f ? mx[u][i] : mn[u][i]), acc);
-        }
-      }
-      acc += partner_f64<2>(acc);
-      acc += partner_f64<1>(acc);
-      acc += partner_f64<0>(acc);
-      best = acc > best ? acc : best;
-    }
-    const int j = j_wave + gq * 8 + (lane >> 3);
-    if ((lane & 7) == 0 && j < D.max_blocks) {
-      const bool kept = j < D.n_sink || j >= nb - D.n_tail;
-      scores[(size_t)pair * D.max_blocks + j] = j < nb ? (kept ? INFINITY : (float)best) : -INFINITY;
-    }
+    for (int r = 0; r < V / 8; ++r) best = acc[r] > best ? acc[r] : best;  // heads of one entry (V / 8 divides HC)
+  }
+  // lanes whose finished sums were heads of the same entry
+  if constexpr (E <= 2) {
+    const double o = partner_f64<1>(best);
+    best = o > best ? o : best;
+  }
+  if constexpr (E <= 4) {
+    const double o = partner_f64<0>(best);
+    best = o > best ? o : best;
+  }
+  const int gq_mine = E >= 8 ? (lane & 7) : E == 4 ? (lane & 7) >> 1 : (lane & 7) >> 2;
+  const bool writer = E >= 8 ? true : E == 4 ? (lane & 1) == 0 : (lane & 3) == 0;
+  const int j = j_wave + gq_mine * 8 + (lane >> 3);
+  if (writer && j < D.max_blocks) {
+    const bool kept = j < D.n_sink || j >= nb - D.n_tail;
+    scores[(size_t)pair * D.max_blocks + j] = j < nb ? (kept ? INFINITY : (float)best) : -INFINITY;
   }
 }
 
@@ -403,23 +466,31 @@ int launch_digest(const Dims& D, int dtype, const void* k_blocks, void* digest, 
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
 }
 
-int launch_score_max(const Dims& D, int dtype, const void* q, const void* digest, float* scores, hipStream_t st) {
+template <int HC>
+static int launch_score_max_hc(const Dims& D, int dtype, const void* q, const void* digest, float* scores,
+                               hipStream_t st) {
   const int lines = 2 * D.d * (dtype == SCOUT_BF16 ? 2 : 4) / 128;
-  const int blocks_per_wg = kScoreBatch / lines * 8 * kScoreWaves;
+  const int blocks_per_wg = score_max_entries(lines) * 8 * kScoreWaves;  // 8 entries per wave-wide load
   dim3 grid((D.max_blocks + blocks_per_wg - 1) / blocks_per_wg, D.Hkv, D.B);
   dim3 block(kScoreWaves * kWave);
   if (grid.x == 0 || grid.y == 0 || grid.z == 0) return SCOUT_OK;
   if (dtype == SCOUT_BF16 && D.d == 128)
-    hipLaunchKernelGGL((score_max_kernel<SCOUT_BF16, 128>), grid, block, 0, st, D, q, digest, scores);
+    hipLaunchKernelGGL((score_max_kernel<SCOUT_BF16, 128, HC>), grid, block, 0, st, D, q, digest, scores);
   else if (dtype == SCOUT_BF16 && D.d == 64)
-    hipLaunchKernelGGL((score_max_kernel<SCOUT_BF16, 64>), grid, block, 0, st, D, q, digest, scores);
+    hipLaunchKernelGGL((score_max_kernel<SCOUT_BF16, 64, HC>), grid, block, 0, st, D, q, digest, scores);
   else if (dtype == SCOUT_F32 && D.d == 128)
-    hipLaunchKernelGGL((score_max_kernel<SCOUT_F32, 128>), grid, block, 0, st, D, q, digest, scores);
+    hipLaunchKernelGGL((score_max_kernel<SCOUT_F32, 128, HC>), grid, block, 0, st, D, q, digest, scores);
   else if (dtype == SCOUT_F32 && D.d == 64)
-    hipLaunchKernelGGL((score_max_kernel<SCOUT_F32, 64>), grid, block, 0, st, D, q, digest, scores);
+    hipLaunchKernelGGL((score_max_kernel<SCOUT_F32, 64, HC>), grid, block, 0, st, D, q, digest, scores);
   else
     return SCOUT_EUNSUPPORTED;
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
+}
+
+int launch_score_max(const Dims& D, int dtype, const void* q, const void* digest, float* scores, hipStream_t st) {
+  // groups of 5 to 8 heads in one pass of eight, every other size in passes of four
+  if (D.G > 4 && D.G <= 8) return launch_score_max_hc<8>(D, dtype, q, digest, scores, st);
+  return launch_score_max_hc<4>(D, dtype, q, digest, scores, st);
 }
 
 template <bool MEAN>
