@@ -1058,7 +1058,9 @@ int launch_select_attend(const Dims& D, const void* q, const float* scores, cons
 // One workgroup streams its pair's whole digest row: worth it while a row is short enough that one
 // long sequence among short ones cannot hold the launch up for long (2048 blocks = 1 MiB of digest).
 bool step_kernel_supported(const Dims& D, int dtype) {
-  return select_attend_supported(D, dtype) && D.digest_kind == 0 && D.group_max == 0 && D.max_blocks <= 2048;
+  // (with a selection per query head the scoring pass of its own serves the G heads of a row in one reading)
+  return select_attend_supported(D, dtype) && D.digest_kind == 0 && D.group_max == 0 && D.share == 1 &&
+         D.max_blocks <= 2048;
 }
 
 // Scoring, selection, attention and merge of every pair in one launch, one workgroup per pair

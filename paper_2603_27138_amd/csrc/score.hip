@@ -304,7 +304,9 @@ __device__ __forceinline__ void halve_across(double* a, bool hi) {
 
 constexpr int score_max_entries(int lines) { return 16 / lines < 4 ? 16 / lines : 4; }  // per lane
 
-template <int DT, int DH, int HC>
+// ROWS: every head's estimate goes to a row of its own, scores[B][Hq][max_blocks] (a selection per query head:
+// one pass over the KV head's digests serves its G query heads), instead of their maximum into the KV head's row.
+template <int DT, int DH, int HC, bool ROWS>
 __global__ __launch_bounds__(kScoreWaves* kWave) void score_max_kernel(Dims D, const void* q, const void* digest,
                                                                       float* scores) {
   constexpr int EPL = (DT == SCOUT_BF16) ? 8 : 4;   // elements per 16-byte load
@@ -316,7 +318,7 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_max_kernel(Dims D, c
   constexpr int W = HC == 8 ? 2 : 4;                // elements per step of the inner loop
   constexpr int BLK_PER_WAVE = 8 * E;
   constexpr int NT = kScoreWaves * kWave;
-  static_assert(NL >= 2 && NL <= 8 && V >= 8 && HC % (V / 8) == 0, "layout");
+  static_assert(NL >= 2 && NL <= 8 && V >= 8 && (HC / (V / 8) == 2 || HC / (V / 8) == 4), "layout");
 
   // [head][0: N_h, goes with the min row; 1: P_h][channel], the channels of a row in the order in which the
   // lanes read them: a lane's EPL channels of a line are EPL / 2 reads of 16 bytes, and the 8 lanes of an
@@ -336,10 +338,12 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_max_kernel(Dims D, c
   const int nb = num_blocks_of(D, b);
   const int j_wave = (blockIdx.x * kScoreWaves + wave) * BLK_PER_WAVE;
   const bool active = j_wave < D.max_blocks;
-  if ((int)blockIdx.x * kScoreWaves * BLK_PER_WAVE >= nb) {  // as in score_kernel: only the row's tail to mark
+  const int n_rows = ROWS ? D.G : 1;  // rows of `scores` per pair
+  if ((int)blockIdx.x * kScoreWaves * BLK_PER_WAVE >= nb) {  // as in score_kernel: only the rows' tails to mark
     for (int t = threadIdx.x; t < kScoreWaves * BLK_PER_WAVE; t += NT) {
       const int j = (int)blockIdx.x * kScoreWaves * BLK_PER_WAVE + t;
-      if (j < D.max_blocks) scores[(size_t)pair * D.max_blocks + j] = -INFINITY;
+      if (j < D.max_blocks)
+        for (int r = 0; r < n_rows; ++r) scores[((size_t)pair * n_rows + r) * D.max_blocks + j] = -INFINITY;
     }
     return;
   }
@@ -379,6 +383,12 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_max_kernel(Dims D, c
   __syncthreads();
 
   const bool b2 = (lane >> 2) & 1, b1 = (lane >> 1) & 1, b0 = lane & 1;
+  // what the butterfly below leaves in this lane: sums (lane & 7) * V / 8 + r of the V, that is heads
+  // hh_mine + r of the pass for the entry of group gq_mine
+  constexpr int R = V / 8;
+  const int gq_mine = (lane & 7) * R / HC, hh_mine = (lane & 7) * R % HC;
+  const int j = j_wave + gq_mine * 8 + (lane >> 3);
+  const bool kept = j < D.n_sink || j >= nb - D.n_tail;  // always-kept blocks rank above every score
   double best = -INFINITY;
   for (int h0 = 0; h0 < D.G; h0 += HC) {
     double acc[V];  // sum of entry group gq, head h0 + hh at gq * HC + hh
@@ -423,24 +433,30 @@ __global__ __launch_bounds__(kScoreWaves* kWave) void score_max_kernel(Dims D, c
     halve_across<V, 2>(acc, b2);
     halve_across<V / 2, 1>(acc, b1);
     halve_across<V / 4, 0>(acc, b0);
+    if constexpr (ROWS) {
 #pragma unroll
-    for (int r = 0; r < V / 8; ++r) best = acc[r] > best ? acc[r] : best;  // heads of one entry (V / 8 divides HC)
+      for (int r = 0; r < R; ++r) {
+        const int h = h0 + hh_mine + r;
+        if (h < D.G && j < D.max_blocks)
+          scores[((size_t)pair * D.G + h) * D.max_blocks + j] = j < nb ? (kept ? INFINITY : (float)acc[r]) : -INFINITY;
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < R; ++r) best = acc[r] > best ? acc[r] : best;  // heads of one entry (R divides HC)
+    }
   }
-  // lanes whose finished sums were heads of the same entry
-  if constexpr (E <= 2) {
-    const double o = partner_f64<1>(best);
-    best = o > best ? o : best;
-  }
-  if constexpr (E <= 4) {
-    const double o = partner_f64<0>(best);
-    best = o > best ? o : best;
-  }
-  const int gq_mine = E >= 8 ? (lane & 7) : E == 4 ? (lane & 7) >> 1 : (lane & 7) >> 2;
-  const bool writer = E >= 8 ? true : E == 4 ? (lane & 1) == 0 : (lane & 3) == 0;
-  const int j = j_wave + gq_mine * 8 + (lane >> 3);
-  if (writer && j < D.max_blocks) {
-    const bool kept = j < D.n_sink || j >= nb - D.n_tail;
-    scores[(size_t)pair * D.max_blocks + j] = j < nb ? (kept ? INFINITY : (float)best) : -INFINITY;
+  if constexpr (!ROWS) {
+    // lanes whose finished sums were heads of the same entry: HC / R of them, neighbours
+    if constexpr (HC / R >= 4) {
+      const double o = partner_f64<1>(best);
+      best = o > best ? o : best;
+    }
+    if constexpr (HC / R >= 2) {
+      const double o = partner_f64<0>(best);
+      best = o > best ? o : best;
+    }
+    if (hh_mine == 0 && j < D.max_blocks)
+      scores[(size_t)pair * D.max_blocks + j] = j < nb ? (kept ? INFINITY : (float)best) : -INFINITY;
   }
 }
 
@@ -466,7 +482,7 @@ int launch_digest(const Dims& D, int dtype, const void* k_blocks, void* digest, 
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
 }
 
-template <int HC>
+template <int HC, bool ROWS>
 static int launch_score_max_hc(const Dims& D, int dtype, const void* q, const void* digest, float* scores,
                                hipStream_t st) {
   const int lines = 2 * D.d * (dtype == SCOUT_BF16 ? 2 : 4) / 128;
@@ -475,13 +491,13 @@ static int launch_score_max_hc(const Dims& D, int dtype, const void* q, const vo
   dim3 block(kScoreWaves * kWave);
   if (grid.x == 0 || grid.y == 0 || grid.z == 0) return SCOUT_OK;
   if (dtype == SCOUT_BF16 && D.d == 128)
-    hipLaunchKernelGGL((score_max_kernel<SCOUT_BF16, 128, HC>), grid, block, 0, st, D, q, digest, scores);
+    hipLaunchKernelGGL((score_max_kernel<SCOUT_BF16, 128, HC, ROWS>), grid, block, 0, st, D, q, digest, scores);
   else if (dtype == SCOUT_BF16 && D.d == 64)
-    hipLaunchKernelGGL((score_max_kernel<SCOUT_BF16, 64, HC>), grid, block, 0, st, D, q, digest, scores);
+    hipLaunchKernelGGL((score_max_kernel<SCOUT_BF16, 64, HC, ROWS>), grid, block, 0, st, D, q, digest, scores);
   else if (dtype == SCOUT_F32 && D.d == 128)
-    hipLaunchKernelGGL((score_max_kernel<SCOUT_F32, 128, HC>), grid, block, 0, st, D, q, digest, scores);
+    hipLaunchKernelGGL((score_max_kernel<SCOUT_F32, 128, HC, ROWS>), grid, block, 0, st, D, q, digest, scores);
   else if (dtype == SCOUT_F32 && D.d == 64)
-    hipLaunchKernelGGL((score_max_kernel<SCOUT_F32, 64, HC>), grid, block, 0, st, D, q, digest, scores);
+    hipLaunchKernelGGL((score_max_kernel<SCOUT_F32, 64, HC, ROWS>), grid, block, 0, st, D, q, digest, scores);
   else
     return SCOUT_EUNSUPPORTED;
   return hipGetLastError() == hipSuccess ? SCOUT_OK : SCOUT_EHIP;
@@ -489,8 +505,21 @@ static int launch_score_max_hc(const Dims& D, int dtype, const void* q, const vo
 
 int launch_score_max(const Dims& D, int dtype, const void* q, const void* digest, float* scores, hipStream_t st) {
   // groups of 5 to 8 heads in one pass of eight, every other size in passes of four
-  if (D.G > 4 && D.G <= 8) return launch_score_max_hc<8>(D, dtype, q, digest, scores, st);
-  return launch_score_max_hc<4>(D, dtype, q, digest, scores, st);
+  if (D.G > 4 && D.G <= 8) return launch_score_max_hc<8, false>(D, dtype, q, digest, scores, st);
+  return launch_score_max_hc<4, false>(D, dtype, q, digest, scores, st);
+}
+
+// A selection per query head (D describes every query head as a pair of its own that shares its KV head's
+// rows): the same kernel over the KV heads, every head's estimate to its own row.
+static int launch_score_rows(const Dims& D, int dtype, const void* q, const void* digest, float* scores,
+                             hipStream_t st) {
+  Dims K = D;
+  K.G = D.share;
+  K.Hkv = D.Hkv / D.share;
+  K.share = 1;
+  K.share_magic = 0;
+  if (K.G > 4 && K.G <= 8) return launch_score_max_hc<8, true>(K, dtype, q, digest, scores, st);
+  return launch_score_max_hc<4, true>(K, dtype, q, digest, scores, st);
 }
 
 template <bool MEAN>
@@ -519,6 +548,7 @@ int launch_score(const Dims& D, int dtype, const void* q, const void* digest, fl
                  hipStream_t st) {
   if (D.digest_kind == 1) return D.group_max ? SCOUT_EUNSUPPORTED : launch_score_sum<true>(D, dtype, q, digest, scores, st);
   if (D.group_max) return launch_score_max(D, dtype, q, digest, scores, st);
+  if (D.share > 1) return launch_score_rows(D, dtype, q, digest, scores, st);
   return launch_score_sum<false>(D, dtype, q, digest, scores, st);
 }
 
