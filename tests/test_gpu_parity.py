@@ -427,6 +427,42 @@ def test_group_max_aggregation(cfg):
     dev.set_host_partials_from_oracle(res0)
 
 
+@pytest.mark.parametrize("G,d,dtype", [(3, 128, "bf16"), (5, 128, "bf16"), (6, 64, "bf16"), (7, 128, "f32"),
+                                       (12, 64, "f32"), (16, 128, "bf16")])
+def test_head_wise_scores_for_group_sizes(G, d, dtype):
+    """The kernel behind group_max and per_head takes the heads of a group four or eight at a time and repeats
+    the last head where a group does not fill its last pass: group sizes that do not, rows that span several
+    workgroups with a ragged tail, every score of both variants against the oracle's."""
+    cfg = W.shrink(W.tiny(), name=f"heads-G{G}", B=2, Hq=2 * G, Hkv=2, d=d, S=16, dtype=dtype, ctx=(16 * 333 + 5, 16 * 130),
+                   k=8, p_host=0.5, seed=900 + G)
+    wl = W.generate(cfg)
+    dev = Dev(wl)
+    res = harness.run_all(wl, agg="max", attention=False)
+    dev.set_digest_from_oracle(res)
+    code = B.F32 if dtype == "f32" else B.BF16
+    for variant in ("group_max", "per_head"):
+        p2 = B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, code, cfg.max_blocks, cfg.k, dev.ctx_len, 0.0,
+                            n_sink=1, n_tail=1, **{variant: 1})
+        rows = cfg.Hq if variant == "per_head" else cfg.Hkv
+        scores = torch.full((cfg.B, rows, cfg.max_blocks), float("nan"), dtype=torch.float32, device="cuda")
+        B.score_blocks(p2, dev.q, dev.digest, scores, B.alloc_workspace(p2))
+        got = scores.cpu().numpy()
+        for b in range(cfg.B):
+            for r in range(rows):
+                if variant == "per_head":
+                    want = harness.run_head(wl, b, r, attention=False).s32
+                else:
+                    want = res[(b, r)].s32
+                nb = len(want)
+                kept = np.zeros(nb, dtype=bool)
+                kept[:1] = True
+                kept[nb - 1:] = True
+                assert np.isposinf(got[b, r, :nb][kept]).all(), (variant, b, r)
+                rel = np.abs(got[b, r, :nb][~kept].astype(np.float64) - want[~kept]) / np.maximum(np.abs(want[~kept]), 1e-30)
+                assert rel.max() <= 2e-7, (variant, b, r, rel.max())
+                assert np.isneginf(got[b, r, nb:]).all(), (variant, b, r)
+
+
 def test_per_head_selection(cfg):
     """per_head = 1: every query head scores, selects and attends on its own (lists per query head, the
     KV head's digest, table and pools shared), step by step and through the fused layer-step."""
