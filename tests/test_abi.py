@@ -176,3 +176,54 @@ def test_attention_mode_belongs_to_the_calling_thread(lib):
     t.join()
     assert seen["forced"] == lib.EUNSUPPORTED
     assert L.sparse_decode_attn_static(ctypes.byref(big), *args, None) == lib.ESCRATCH
+
+
+def test_headers_are_plain_c_and_the_binding_has_the_header_layout(lib, tmp_path):
+    """The three headers compile as C99 with no warnings, a C program links against the library and
+    calls its host-only entry points, and the struct the Python binding marshals has the size and the
+    field offsets of the header's."""
+    import subprocess
+    from paper_2603_27138_amd import build
+    src = tmp_path / "abi.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <stddef.h>
+#include "scout.h"
+#include "scout_calib.h"
+#include "scout_host.h"
+int main(void) {
+  scout_problem p = {0};
+  size_t bytes = 0;
+  int rc;
+  p.B = 2; p.Hq = 8; p.Hkv = 2; p.d = 128; p.S = 32; p.dtype = SCOUT_BF16; p.max_blocks = 100; p.k = 8;
+  printf("%d\n", scout_version());
+  printf("%s\n", scout_strerror(SCOUT_EWORKSPACE));
+  rc = scout_workspace_bytes(&p, &bytes);
+  printf("%d %zu\n", rc, bytes);
+  p.d = 96;
+  rc = scout_workspace_bytes(&p, &bytes);
+  printf("%d\n", rc);
+  printf("%zu", sizeof(scout_problem));
+  printf(" %zu %zu %zu %zu %zu\n", offsetof(scout_problem, B), offsetof(scout_problem, sm_scale),
+         offsetof(scout_problem, per_head), offsetof(scout_problem, tile_stride), offsetof(scout_problem, ctx_len));
+  return 0;
+}
+''')
+    exe = tmp_path / "abi"
+    libdir = os.path.dirname(build.LIB)
+    cmd = ["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"), str(src),
+           "-o", str(exe), "-L", libdir, "-lscout", "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib",
+           "-Wl,--allow-shlib-undefined"]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=60)
+    assert out.returncode == 0, out.stderr
+    lines = out.stdout.split("\n")
+    assert int(lines[0]) == lib.lib().scout_version()
+    assert lines[1] == lib.lib().scout_strerror(lib.EWORKSPACE).decode()
+    rc, nbytes = lines[2].split()
+    assert int(rc) == 0 and int(nbytes) > 0 and int(nbytes) % 256 == 0
+    assert int(lines[3]) == lib.EUNSUPPORTED
+    P = lib.Problem
+    want = [ctypes.sizeof(P), P.B.offset, P.sm_scale.offset, P.per_head.offset, P.tile_stride.offset, P.ctx_len.offset]
+    assert [int(x) for x in lines[4].split()] == want
