@@ -40,6 +40,10 @@ def parse(argv=None):
     ap.add_argument("--group-max", action="store_true",
                     help="time the variant that combines the group's heads by their maximum (not the metric's setting)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--q-drift", type=float, default=0.98,
+                    help="cosine between the two queries a layer copy is visited with in turn (1 = always the same "
+                         "query): consecutive decode steps select overlapping but not equal block sets, and the fused "
+                         "step uses the lists it finds as a prefetch hint")
     ap.add_argument("--interleaved-pool", action="store_true",
                     help="one pool [n_slots][2][S][d] in which a slot's K tile and V tile lie next to each other "
                          "(tile_stride = 2 S d) instead of the two dense pools k_pool / v_pool [n_slots][S][d]; "
@@ -179,6 +183,13 @@ def setup(args) -> State:
     torch.cuda.empty_cache()
 
     st.sets = [L0] + [LayerSet(L0) for _ in range(args.layers - 1)]
+    # the query of the step after: rho q + sqrt(1 - rho^2) noise, rounded to bf16 (timed steps visit a layer copy
+    # with the two in turn, so the lists a step finds are those of a neighbouring decode step, not its own)
+    rho = min(max(args.q_drift, 0.0), 1.0)
+    gen = torch.Generator(device="cuda").manual_seed(20260327)
+    for s in st.sets:
+        noise = torch.randn(s.q.shape, generator=gen, device="cuda", dtype=torch.float32)
+        s.q_alt = (rho * s.q.float() + (1.0 - rho * rho) ** 0.5 * noise).to(torch.bfloat16)
     st.probs = [B.make_problem(cfg.B, cfg.Hq, cfg.Hkv, cfg.d, cfg.S, B.BF16, cfg.max_blocks, cfg.k, s.ctx_len,
                                group_max=int(args.group_max), tile_stride=st.tile_stride)
                 for s in st.sets]
@@ -197,7 +208,7 @@ def prepared(fn):
     def run(st, i, **kw):
         if kw:
             return fn(st, i, **kw)
-        j = i % len(st.sets)
+        j = i % (2 * len(st.sets))      # a layer copy and which of its two queries (see step)
         cache = st.__dict__.setdefault("_prepared", {})
         key = (fn.__name__, j)
         if key not in cache:
@@ -207,7 +218,7 @@ def prepared(fn):
         """Marshal the calls for every layer copy now (nothing is launched), so that no timed iteration pays
         for it however few steps are asked for."""
         cache = st.__dict__.setdefault("_prepared", {})
-        for j in range(len(st.sets)):
+        for j in range(2 * len(st.sets)):
             if (fn.__name__, j) not in cache:
                 cache[(fn.__name__, j)] = st.B.prepare(fn, st, j)
 
@@ -219,7 +230,8 @@ def prepared(fn):
 @prepared
 def step(st, i, ws=None):
     s, p = st.sets[i % len(st.sets)], st.probs[i % len(st.sets)]
-    st.B.layer_step(p, s.q, s.digest, s.block_table, s.k_pool, s.v_pool, st.wl.n_slots, s.host_o, s.host_m,
+    q = s.q if (i // len(st.sets)) % 2 == 0 else s.q_alt      # every other visit: the neighbouring step's query
+    st.B.layer_step(p, q, s.digest, s.block_table, s.k_pool, s.v_pool, st.wl.n_slots, s.host_o, s.host_m,
                     s.host_l, s.scores, s.sel_all, s.sel_gpu, s.slot_gpu, s.n_gpu, s.sel_host, s.n_host,
                     s.out, s.lse, st.ws if ws is None else ws)
 
@@ -715,6 +727,8 @@ def main():
     # launches): the attention kernel alone (the pass that streams the K/V rows; one launch per call),
     # sparse_decode_attn (that pass plus, when a pair is split over workgroups, the small combine
     # pass), the scoring pass, the selection
+    for j in range(len(st.sets)):     # every copy back on its first query's lists for the per-kernel loops
+        step(st, j)
     for i in range(args.warmup):
         attn_split_only(st, i)
     us_attn_kernel = timed(st, attn_split_only, args.steps)
@@ -756,6 +770,19 @@ def main():
         us_step_ovs, us_staged_ov = recall_overlap(st, args.steps, us_staged, us_step, "staged")
     st.staged.worker.close()
 
+    # how much of a step's resident list the lists of the neighbouring step (what it finds as its hint) share
+    step(st, 0)
+    torch.cuda.synchronize()
+    a_sel, a_n = st.sets[0].sel_gpu.cpu().numpy().copy(), st.sets[0].n_gpu.cpu().numpy().copy()
+    step(st, len(st.sets))
+    torch.cuda.synchronize()
+    b_sel, b_n = st.sets[0].sel_gpu.cpu().numpy(), st.sets[0].n_gpu.cpu().numpy()
+    shared = sum(len(np.intersect1d(a_sel[b, g, :a_n[b, g]], b_sel[b, g, :b_n[b, g]]))
+                 for b in range(cfg.B) for g in range(cfg.Hkv))
+    list_overlap = shared / max(1, int(a_n.sum()))
+    step(st, 0)                                              # leave copy 0 with the first query's lists
+    torch.cuda.synchronize()
+
     tile_bytes = 2 * cfg.S * cfg.d * 2                       # K + V tile of one block, bf16
     n_blocks = int(st.sets[0].n_gpu.sum().item())
     attn_bytes = n_blocks * tile_bytes                       # algorithmic bytes of one attention launch
@@ -792,6 +819,7 @@ def main():
                    "batch": cfg.B, "q_heads": cfg.Hq,
                    "kv_heads": cfg.Hkv, "head_dim": cfg.d, "context": int(max(cfg.ctx)), "block": cfg.S, "k_blocks": cfg.k,
                    "host_resident": cfg.p_host, "layer_copies": len(st.sets), "gpu_blocks_per_step": n_blocks,
+                   "query_cosine_between_visits": args.q_drift, "resident_list_overlap_between_visits": round(list_overlap, 4),
                    "pool_layout": "one pool [slots][2][S][d]" if args.interleaved_pool else "k_pool, v_pool [slots][S][d]"},
         "kv_gbps": round(attn_gbps, 1),
         "kernels_us": {"score_blocks": round(us_score, 3), "select_topk": round(us_select, 3),

@@ -340,6 +340,17 @@ int recall_scatter(const scout_problem* p, const void* staged, int64_t n_tiles, 
  * spread over several workgroups (scoring; selection + attention; combine +
  * merge), one where the pairs alone fill the chip (bf16, d = 128, at least 192
  * pairs: every step of a pair in one workgroup).
+ *
+ * slot_gpu and n_gpu are read before they are written: what they hold on entry
+ * is taken as a HINT of where this step's tiles will be (adjacent decode tokens
+ * attend to highly overlapping sets of blocks, Sec. 1; a caller that keeps one set
+ * of list buffers per layer hands over the previous step's lists by doing nothing).
+ * While the selection runs, the kernel touches the tiles of the hinted slots
+ * so that they are on their way from HBM.  The hint changes no result, whatever
+ * it holds: counts are clamped to [0, k], slots outside [0, n_slots) are
+ * skipped, nothing outside the pools is read, and the values read are dropped.
+ * Buffers that were never written are a valid (useless) hint.  Only budgets up to
+ * k = 128 use it.
  */
 int scout_layer_step(const scout_problem* p, const void* q, const void* digest,
                      const int32_t* block_table, const void* k_pool, const void* v_pool,

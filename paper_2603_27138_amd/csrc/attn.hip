@@ -520,6 +520,46 @@ __global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
   load_q(qreg, D, q, b, g, lane & 15, lane >> 4);
   const int ctx = D.ctx_len[b];  // once, here: the attention below must not wait for it again
 
+  // A hint from the lists as the caller left them (in a decode loop: the previous step's lists of this
+  // layer; adjacent decode tokens attend to highly overlapping sets of blocks, Sec. 1).  While the
+  // selection below runs, the workgroups ask memory for nothing; the unit this wave would start with
+  // under the old lists is touched now, one dword of every 64 bytes, so that its rows are on their way
+  // from HBM into the caches while the waves select (one unit per wave is what memory delivers in that
+  // time: touching two measured no gain).  A hint is only ever a slot number inside [0, n_slots):
+  // whatever the arrays hold, the touch stays inside the pools, and its value is never used.
+  uint32_t touched_k = 0, touched_v = 0;
+  const bool hinted = D.k <= 2 * kWave;
+  int n_old = 0, s_lo = -1, s_hi = -1;
+  if (hinted) {  // the old count and, lane l, old entries l and 64 + l: the same trip as the keys' loads below
+    const size_t row = (size_t)pair * D.k;
+    n_old = n_gpu[pair];
+    s_lo = slot_gpu[row + (lane < D.k ? lane : D.k - 1)];
+    s_hi = slot_gpu[row + (kWave + lane < D.k ? kWave + lane : D.k - 1)];
+  }
+  // (issued once the keys are in: a wave's loads return in the order they were issued, and the keys must
+  // not wait behind a touch that takes a loaded memory system's full latency.  The touch goes through a
+  // buffer descriptor that covers the unit, or nothing: no branch, so nothing ever waits for its value)
+  auto touch_old_unit = [&]() {
+    int n = __builtin_amdgcn_readfirstlane(n_old);
+    n = n < 0 ? 0 : (n > D.k ? D.k : n);
+    const int ush = D.s_shift - 4;
+    const int n_units = hinted ? n << ush : 0, v = split * WAVES + wave;
+    const int per = P.waves_magic ? (int)__umulhi((uint32_t)n_units, P.waves_magic) : n_units;
+    const int extra = n_units - per * (P.nsplit * WAVES);
+    const int u0 = v * per + (v < extra ? v : extra);  // the first unit of this wave's share of the old list
+    const int uc = u0 < n_units ? u0 : 0;
+    const int e = uc >> ush, sub = uc & ((1 << ush) - 1);
+    long long slot = e < kWave ? __builtin_amdgcn_readlane(s_lo, e & (kWave - 1)) : __builtin_amdgcn_readlane(s_hi, e & (kWave - 1));
+    const bool ok = u0 < n_units && slot >= 0 && slot < n_slots;
+    slot = ok ? slot : 0;
+    const size_t off = (size_t)slot * D.tile_stride + sub * kUnitTokens * kMfmaD;
+    const int bytes = ok ? kUnitBytes : 0;
+    const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(k_pool + off), 0, bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(v_pool + off), 0, bytes, 0x00020000);
+    touched_k = __builtin_amdgcn_raw_buffer_load_b32(kr, lane * 64, 0, 0);  // one dword of every 64 bytes of the unit
+    touched_v = __builtin_amdgcn_raw_buffer_load_b32(vr, lane * 64, 0, 0);
+  };
+
   if (SEL_WAVES == WAVES || wave == 0) {  // wave-uniform
     const int sw = SEL_WAVES == WAVES ? wave : 0;
     int nb = (ctx < 0 ? 0 : ctx + D.S - 1) >> D.s_shift;
@@ -528,6 +568,9 @@ __global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
     uint32_t key[KPL];
     int slot[KPL];
     load_keys<SEL_WAVES, KPL>(D, scores, table, pair, nb, sw, lane, key, slot);
+    __builtin_amdgcn_sched_barrier(0);
+    touch_old_unit();
+    __builtin_amdgcn_sched_barrier(0);
     Selector<SEL_WAVES, KPL> S{l_x, 0, sw};
     uint32_t sel = 0;
     if (k_eff > 0) sel = S.best(key, k_eff, false);
@@ -576,6 +619,7 @@ __global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
   }
   __syncthreads();
   attend_pair<WAVES, 1>(D, b, g, split, qreg, k_pool, v_pool, n_slots, l_sel, l_slot, l_n[0], ctx, P, E, smem);
+  asm volatile("" ::"v"(touched_k), "v"(touched_v));  // the touches stay loads, their registers reserved until they have returned
 }
 
 // The whole layer-step of a pair in one launch (the non-pipelined sequence of Sec. 3.2: score every

@@ -800,6 +800,59 @@ def test_layer_step_without_scores():
         assert torch.isnan(dev.scores).all()      # not written
 
 
+@pytest.mark.parametrize("which", ["C3-qwen3-32b", "ragged-partial", "bf16-s16-ragged", "bf16-s64-g2", "bf16-k-beyond-nb",
+                                   "bf16-empty-sequence", "bf16-all-host"])
+def test_layer_step_hint_changes_nothing(which):
+    """scout_layer_step reads slot_gpu and n_gpu before it writes them, as a hint of where this step's tiles
+    will be.  Whatever they hold (nothing, the right lists, another step's lists, the extremes of int32, random
+    words, counts beyond k), every output has the same bits, and nothing outside the tensors is written."""
+    cfg = next(c for c in CFGS if c.name == which)
+    wl, res, dev = setup(cfg)
+    dev.set_digest_from_oracle(res)
+    dev.set_host_partials_from_oracle(res)
+    outs = ("out", "lse", "scores", "sel_all", "sel_gpu", "slot_gpu", "sel_host", "n_gpu", "n_host")
+    g = torch.Generator(device="cuda").manual_seed(5)
+    i32 = torch.iinfo(torch.int32)
+
+    def fill(kind):
+        if kind == "minus one":
+            dev.slot_gpu.fill_(-1); dev.n_gpu.fill_(-1)
+        elif kind == "own lists":
+            pass                                      # what the last call left
+        elif kind == "max":
+            dev.slot_gpu.fill_(i32.max); dev.n_gpu.fill_(i32.max)
+        elif kind == "min":
+            dev.slot_gpu.fill_(i32.min); dev.n_gpu.fill_(i32.min)
+        elif kind == "random words":
+            dev.slot_gpu.copy_(torch.randint(i32.min, i32.max, dev.slot_gpu.shape, generator=g, device="cuda", dtype=torch.int64).to(torch.int32))
+            dev.n_gpu.copy_(torch.randint(i32.min, i32.max, dev.n_gpu.shape, generator=g, device="cuda", dtype=torch.int64).to(torch.int32))
+        elif kind == "valid slots, full counts":
+            dev.slot_gpu.copy_(torch.randint(0, max(1, dev.n_slots), dev.slot_gpu.shape, generator=g, device="cuda", dtype=torch.int64).to(torch.int32))
+            dev.n_gpu.fill_(cfg.k)
+        elif kind == "last slot":
+            dev.slot_gpu.fill_(max(0, dev.n_slots - 1)); dev.n_gpu.fill_(cfg.k + 5)
+
+    modes = [(0, 0, 0), (2, 1, 8), (2, 3, 8)] if cfg.dtype == "bf16" and cfg.d == 128 else [(0, 0, 0)]
+    for mode in modes:
+        B.set_attn_mode(*mode)
+        try:
+            fill("minus one")
+            dev.layer_step()
+            want = {n: getattr(dev, n).clone() for n in outs}
+            for kind in ("own lists", "max", "min", "random words", "valid slots, full counts", "last slot"):
+                fill(kind)
+                for n in ("out", "lse", "scores"):
+                    getattr(dev, n).zero_()
+                dev.layer_step()
+                dev.check_guards()
+                for n in outs:
+                    a, b_ = want[n], getattr(dev, n)
+                    same = torch.equal(a, b_) if a.dtype != torch.float32 else torch.equal(a.view(torch.int32), b_.view(torch.int32))
+                    assert same, (mode, kind, n)
+        finally:
+            B.set_attn_mode(0, 0, 0)
+
+
 @pytest.mark.parametrize("which", ["C3-qwen3-32b", "ragged-f32", "bf16-d64-s16", "bf16-s64-g2"])
 def test_interleaved_pool_layout(which):
     """tile_stride: one pool [n_slots][2][S][d] (a slot's K tile and V tile adjacent, v_pool = k_pool + one
