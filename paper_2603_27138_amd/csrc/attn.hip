@@ -490,6 +490,64 @@ __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_private_kernel(
                               my_sel, my_slot);
 }
 
+// A hint from the lists as the caller left them (in a decode loop: the previous step's lists of this
+// layer; adjacent decode tokens attend to highly overlapping sets of blocks, Sec. 1).  While the waves of
+// a workgroup select, they ask memory for nothing; the unit a wave would start with under the old lists
+// is touched just before, one dword of every 64 bytes, so that its rows are on their way from HBM into
+// the caches meanwhile (one unit per wave is what memory delivers in that time: touching two measured
+// no gain).  A hint is only ever a slot number inside [0, n_slots): whatever the arrays hold, the touch
+// stays inside the pools, and its value is never used.  Budgets above 128 blocks take no hint.  (Not in
+// step_kernel: its workgroups are at different stages at any time, memory is never idle there, and the
+// touch measured no gain: 65.5 against 65.2 us at 256 ragged pairs.)
+struct Hint {
+  int n_old, s_lo, s_hi;  // the old count; lane l: old slot entries l and 64 + l
+};
+
+// Requested in the same trip as whatever else the kernel asks for first.
+__device__ __forceinline__ Hint load_hint(const Dims& D, int pair, int lane, const int32_t* slot_gpu,
+                                          const int32_t* n_gpu) {
+  Hint h{0, -1, -1};
+  if (D.k <= 2 * kWave) {
+    const size_t row = (size_t)pair * D.k;
+    h.n_old = n_gpu[pair];
+    h.s_lo = slot_gpu[row + (lane < D.k ? lane : D.k - 1)];
+    h.s_hi = slot_gpu[row + (kWave + lane < D.k ? kWave + lane : D.k - 1)];
+  }
+  return h;
+}
+
+// Wave v of the pair's P.nsplit * WAVES waves touches the first unit of its share of the old list.  To be
+// issued when the loads whose values are needed next have returned (a wave's loads return in the order
+// they were issued, and a touch takes a loaded memory system's full latency).  The touch goes through a
+// buffer descriptor that covers the unit, or nothing: no branch, so nothing ever waits for its value.
+// The caller keeps tk and tv alive (an empty asm that names them) until its own later loads have returned.
+template <int WAVES>
+__device__ __forceinline__ void touch_hint(const Dims& D, const Hint& h, const Partials& P, int v, int lane,
+                                           const uint16_t* k_pool, const uint16_t* v_pool, long long n_slots,
+                                           uint32_t& tk, uint32_t& tv) {
+  int n = __builtin_amdgcn_readfirstlane(h.n_old);
+  n = n < 0 ? 0 : (n > D.k ? D.k : n);
+  const int ush = D.s_shift - 4;
+  const int n_units = D.k <= 2 * kWave ? n << ush : 0;
+  const int per = P.waves_magic ? (int)__umulhi((uint32_t)n_units, P.waves_magic) : n_units;
+  const int extra = n_units - per * (P.nsplit * WAVES);
+  const int u0 = v * per + (v < extra ? v : extra);  // the first unit of this wave's share of the old list
+  const int uc = u0 < n_units ? u0 : 0;
+  const int e = uc >> ush, sub = uc & ((1 << ush) - 1);
+  long long slot = e < kWave ? __builtin_amdgcn_readlane(h.s_lo, e & (kWave - 1))
+                             : __builtin_amdgcn_readlane(h.s_hi, e & (kWave - 1));
+  const bool ok = u0 < n_units && slot >= 0 && slot < n_slots;
+  slot = ok ? slot : 0;
+  const size_t off = (size_t)slot * D.tile_stride + sub * kUnitTokens * kMfmaD;
+  const int bytes = ok ? kUnitBytes : 0;
+  const __amdgpu_buffer_rsrc_t kr =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(k_pool + off), 0, bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t vr =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(v_pool + off), 0, bytes, 0x00020000);
+  tk = __builtin_amdgcn_raw_buffer_load_b32(kr, lane * 64, 0, 0);  // one dword of every 64 bytes of the unit
+  tv = __builtin_amdgcn_raw_buffer_load_b32(vr, lane * 64, 0, 0);
+}
+
 // Selection and attention of a pair in one launch (the non-pipelined description of Sec. 3.2:
 // identify the top-k blocks, then attend to the resident ones).  Every workgroup of the pair
 // repeats the cheap selection from the scores (integer work on a few KiB of keys), keeps the
@@ -520,45 +578,8 @@ __global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
   load_q(qreg, D, q, b, g, lane & 15, lane >> 4);
   const int ctx = D.ctx_len[b];  // once, here: the attention below must not wait for it again
 
-  // A hint from the lists as the caller left them (in a decode loop: the previous step's lists of this
-  // layer; adjacent decode tokens attend to highly overlapping sets of blocks, Sec. 1).  While the
-  // selection below runs, the workgroups ask memory for nothing; the unit this wave would start with
-  // under the old lists is touched now, one dword of every 64 bytes, so that its rows are on their way
-  // from HBM into the caches while the waves select (one unit per wave is what memory delivers in that
-  // time: touching two measured no gain).  A hint is only ever a slot number inside [0, n_slots):
-  // whatever the arrays hold, the touch stays inside the pools, and its value is never used.
+  const Hint hint = load_hint(D, pair, lane, slot_gpu, n_gpu);
   uint32_t touched_k = 0, touched_v = 0;
-  const bool hinted = D.k <= 2 * kWave;
-  int n_old = 0, s_lo = -1, s_hi = -1;
-  if (hinted) {  // the old count and, lane l, old entries l and 64 + l: the same trip as the keys' loads below
-    const size_t row = (size_t)pair * D.k;
-    n_old = n_gpu[pair];
-    s_lo = slot_gpu[row + (lane < D.k ? lane : D.k - 1)];
-    s_hi = slot_gpu[row + (kWave + lane < D.k ? kWave + lane : D.k - 1)];
-  }
-  // (issued once the keys are in: a wave's loads return in the order they were issued, and the keys must
-  // not wait behind a touch that takes a loaded memory system's full latency.  The touch goes through a
-  // buffer descriptor that covers the unit, or nothing: no branch, so nothing ever waits for its value)
-  auto touch_old_unit = [&]() {
-    int n = __builtin_amdgcn_readfirstlane(n_old);
-    n = n < 0 ? 0 : (n > D.k ? D.k : n);
-    const int ush = D.s_shift - 4;
-    const int n_units = hinted ? n << ush : 0, v = split * WAVES + wave;
-    const int per = P.waves_magic ? (int)__umulhi((uint32_t)n_units, P.waves_magic) : n_units;
-    const int extra = n_units - per * (P.nsplit * WAVES);
-    const int u0 = v * per + (v < extra ? v : extra);  // the first unit of this wave's share of the old list
-    const int uc = u0 < n_units ? u0 : 0;
-    const int e = uc >> ush, sub = uc & ((1 << ush) - 1);
-    long long slot = e < kWave ? __builtin_amdgcn_readlane(s_lo, e & (kWave - 1)) : __builtin_amdgcn_readlane(s_hi, e & (kWave - 1));
-    const bool ok = u0 < n_units && slot >= 0 && slot < n_slots;
-    slot = ok ? slot : 0;
-    const size_t off = (size_t)slot * D.tile_stride + sub * kUnitTokens * kMfmaD;
-    const int bytes = ok ? kUnitBytes : 0;
-    const __amdgpu_buffer_rsrc_t kr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(k_pool + off), 0, bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t vr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(v_pool + off), 0, bytes, 0x00020000);
-    touched_k = __builtin_amdgcn_raw_buffer_load_b32(kr, lane * 64, 0, 0);  // one dword of every 64 bytes of the unit
-    touched_v = __builtin_amdgcn_raw_buffer_load_b32(vr, lane * 64, 0, 0);
-  };
 
   if (SEL_WAVES == WAVES || wave == 0) {  // wave-uniform
     const int sw = SEL_WAVES == WAVES ? wave : 0;
@@ -569,7 +590,7 @@ __global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
     int slot[KPL];
     load_keys<SEL_WAVES, KPL>(D, scores, table, pair, nb, sw, lane, key, slot);
     __builtin_amdgcn_sched_barrier(0);
-    touch_old_unit();
+    touch_hint<WAVES>(D, hint, P, split * WAVES + wave, lane, k_pool, v_pool, n_slots, touched_k, touched_v);
     __builtin_amdgcn_sched_barrier(0);
     Selector<SEL_WAVES, KPL> S{l_x, 0, sw};
     uint32_t sel = 0;
