@@ -435,13 +435,47 @@ __device__ __forceinline__ void attend_pair(const Dims& D, int b, int g, int spl
   }
 }
 
+// Which (sequence, KV head, pair, split) a workgroup of the attention kernels works on.  Normally the grid
+// is (splits, KV heads, sequences).  With a selection per query head and one workgroup per head, the launcher
+// asks for a grid of one dimension instead (REMAP, a kernel instance of its own so that the usual path keeps its
+// short head): the heads of a KV head choose overlapping blocks,
+// so they get workgroup ids 8 apart, which the dispatcher hands to the same XCD one after the other: what one
+// head reads from memory the others find in that XCD's L2 (a layer-step with per-head selection at config 3's
+// shape: 96 us instead of 111 us).
+template <bool REMAP>
+__device__ __forceinline__ void which_pair(const Dims& D, int& b, int& g, int& pair, int& split) {
+  b = blockIdx.z;
+  g = blockIdx.y;
+  pair = grid_pair();
+  split = blockIdx.x;
+  if constexpr (REMAP) {
+    const int L = blockIdx.x, t = L >> 3;
+    const int row = ((t / D.share) << 3) | (L & 7);  // the KV head's row; its heads are t % share
+    pair = row * D.share + t % D.share;
+    b = pair / D.Hkv;
+    g = pair - b * D.Hkv;
+    split = 0;
+  }
+}
+
+// True, and the grid to launch, if the pairs that share a row can be placed on one XCD (see which_pair).
+static bool xcd_grid(const Dims& D, int nsplit, dim3& grid) {
+  const int pairs = D.B * D.Hkv;
+  if (D.share > 1 && nsplit == 1 && (pairs / D.share) % 8 == 0) {
+    grid = dim3(pairs, 1, 1);
+    return true;
+  }
+  return false;
+}
+
 template <int WAVES, int DEPTH>
 __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
     Dims D, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_pool,
     const uint16_t* __restrict__ v_pool, long long n_slots, const int32_t* __restrict__ sel_gpu,
     const int32_t* __restrict__ slot_gpu, const int32_t* __restrict__ n_gpu, Partials P, Epilogue E) {
   extern __shared__ float smem[];
-  const int b = blockIdx.z, g = blockIdx.y, pair = grid_pair(), split = blockIdx.x;
+  int b, g, pair, split;
+  which_pair<false>(D, b, g, pair, split);
   const int lane = lane_id();
   // The pair's whole list is copied to LDS by all threads at once, in the same round trip that
   // brings the count and the queries: which entries a wave needs depends on the count, and a
@@ -465,13 +499,14 @@ __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_kernel(
 // used when no wave can have more than 64 units.  Without the staging of the list through LDS and its
 // barrier the first tile request leaves one trip to memory after the wave started: 16.4 us against
 // 17.0 us for config 3's 64.5 MiB of tiles (config 2: 10.4 against 10.9, config 5: 30.0 against 30.6).
-template <int WAVES>
+template <int WAVES, bool REMAP>
 __global__ __launch_bounds__(WAVES* kWave) void attn_mfma_private_kernel(
     Dims D, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_pool,
     const uint16_t* __restrict__ v_pool, long long n_slots, const int32_t* __restrict__ sel_gpu,
     const int32_t* __restrict__ slot_gpu, const int32_t* __restrict__ n_gpu, Partials P, Epilogue E) {
   extern __shared__ float smem[];
-  const int b = blockIdx.z, g = blockIdx.y, pair = grid_pair(), split = blockIdx.x;
+  int b, g, pair, split;
+  which_pair<REMAP>(D, b, g, pair, split);
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const size_t list0 = (size_t)pair * D.k;
@@ -555,7 +590,7 @@ __device__ __forceinline__ void touch_hint(const Dims& D, const Hint& h, const P
 // lists out, because the host needs to know which selected blocks are its own.
 // SEL_WAVES = 8: all waves share the keys and exchange counts through LDS; SEL_WAVES = 1: one wave
 // holds all keys and selects without a barrier while the others wait (kept for comparison).
-template <int SEL_WAVES, int KPL>
+template <int SEL_WAVES, int KPL, bool REMAP>
 __global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
     Dims D, const uint16_t* __restrict__ q, const float* __restrict__ scores,
     const int32_t* __restrict__ table, const uint16_t* __restrict__ k_pool,
@@ -564,7 +599,8 @@ __global__ __launch_bounds__(8 * kWave) void select_attend_kernel(
     int32_t* __restrict__ sel_host, int32_t* __restrict__ n_host, Partials P, Epilogue E) {
   constexpr int WAVES = 8;
   extern __shared__ float smem[];
-  const int b = blockIdx.z, g = blockIdx.y, pair = grid_pair(), split = blockIdx.x;
+  int b, g, pair, split;
+  which_pair<REMAP>(D, b, g, pair, split);
   const int lane = lane_id();
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   // LDS after the fold area: resident list (block, slot), the selector's exchange words, the count
@@ -1053,9 +1089,12 @@ int launch_attn(const Dims& D, int dtype, int family, int waves, const void* q, 
     const long long units_per_wave = (((long long)D.k * (D.S / kUnitTokens)) + P.nsplit * waves - 1) / (P.nsplit * waves);
     if (waves == 16)
       SCOUT_ATTN(16, 1);
+    else if (waves == 8 && units_per_wave <= 64 && xcd_grid(D, P.nsplit, grid))
+      hipLaunchKernelGGL((attn_mfma_private_kernel<8, true>), grid, block, mfma_smem_bytes(D, 8), st, D, q16, k16, v16,
+                         n_slots, sel_gpu, slot_gpu, n_gpu, P, E);
     else if (waves == 8 && units_per_wave <= 64)
-      hipLaunchKernelGGL((attn_mfma_private_kernel<8>), grid, block, mfma_smem_bytes(D, 8), st, D, q16, k16, v16, n_slots,
-                         sel_gpu, slot_gpu, n_gpu, P, E);
+      hipLaunchKernelGGL((attn_mfma_private_kernel<8, false>), grid, block, mfma_smem_bytes(D, 8), st, D, q16, k16, v16,
+                         n_slots, sel_gpu, slot_gpu, n_gpu, P, E);
     else if (waves == 8)
       SCOUT_ATTN(8, 1);
     else if (waves == 4)
@@ -1096,13 +1135,20 @@ int launch_select_attend(const Dims& D, const void* q, const float* scores, cons
   const int pairs = D.B * D.Hkv;
   if (pairs == 0) return SCOUT_OK;
   dim3 grid(P.nsplit, D.Hkv, D.B), block(8 * kWave);
+  const bool remap = xcd_grid(D, P.nsplit, grid);
   const size_t lds = mfma_smem_bytes(D, 8) + (2 * (size_t)((D.k + 3) & ~3) + selector_lds_ints<8>() + 4) * sizeof(int);
   const uint16_t* q16 = static_cast<const uint16_t*>(q);
   const uint16_t* k16 = static_cast<const uint16_t*>(k_pool);
   const uint16_t* v16 = static_cast<const uint16_t*>(v_pool);
-#define SCOUT_SA(SW, KPL)                                                                              \
-  hipLaunchKernelGGL((select_attend_kernel<SW, KPL>), grid, block, lds, st, D, q16, scores, table, k16, \
-                     v16, n_slots, sel_all, sel_gpu, slot_gpu, n_gpu, sel_host, n_host, P, E)
+#define SCOUT_SA(SW, KPL)                                                                                      \
+  do {                                                                                                         \
+    if (remap)                                                                                                 \
+      hipLaunchKernelGGL((select_attend_kernel<SW, KPL, true>), grid, block, lds, st, D, q16, scores, table, k16, \
+                         v16, n_slots, sel_all, sel_gpu, slot_gpu, n_gpu, sel_host, n_host, P, E);             \
+    else                                                                                                       \
+      hipLaunchKernelGGL((select_attend_kernel<SW, KPL, false>), grid, block, lds, st, D, q16, scores, table, k16, \
+                         v16, n_slots, sel_all, sel_gpu, slot_gpu, n_gpu, sel_host, n_host, P, E);             \
+  } while (0)
   // All eight waves share the keys: measured faster than one wave selecting alone while seven wait
   // (46.9 vs 44.1 us per step at 1024 blocks per pair), a lone wave issues too slowly.
   const int per_lane = (D.max_blocks + 8 * kWave - 1) / (8 * kWave);
