@@ -846,8 +846,8 @@ def main():
                               "attn_frac_of_gather": round(us_gather / us_attn_kernel, 4),
                               "score_frac_of_stream": round(us_stream * digest_bytes / s0_digest_bytes / us_score, 4)},
         # kernels_us.attn_mfma_kernel: the attention pass alone (scout_attn_partials), whose kernel at these shapes
-        # is attn_mfma_private_kernel<8> (the variant in which every wave fetches its own list entries)
-        "roofline": {"bound": "hbm", "kernel": "attn_mfma_private_kernel<8>", "achieved": round(attn_gbps, 1),
+        # is attn_mfma_private_kernel<8, false> (the variant in which every wave fetches its own list entries)
+        "roofline": {"bound": "hbm", "kernel": "attn_mfma_private_kernel<8, false>", "achieved": round(attn_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
                      "traffic": traffic, "traffic_source": None if traffic is None else os.path.relpath(tpath, ROOT),
                      "algorithmic_bytes": attn_bytes},
